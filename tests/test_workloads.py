@@ -8,7 +8,7 @@ from paper_2307_11339_amd import workloads as W
 def test_bf16_rounding_matches_library_rne():
     torch = pytest.importorskip("torch")
     rng = np.random.default_rng(0)
-    a = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 10 ** rng.integers(-6, 6, 20000),
+    a = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 6, 20000),
                         np.array([0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, 1e-40], dtype=np.float32)])
     a = a.astype(np.float32)
     bits = W.f32_to_bf16_bits(a)
