@@ -1,0 +1,148 @@
+/*
+ * rnn.h - C ABI of the MI355X (gfx950) stacked-RNN forward library.
+ *
+ * The operation.  A stacked recurrent network is unrolled over layers and time steps into a
+ * grid of cell operators A_t^l; cell (l, t) may run as soon as cell (l, t-1) and cell (l-1, t)
+ * have finished, so cells on one anti-diagonal are independent (paper: Section 1, "parallelism
+ * after unfolding along the number of layers and the sequence length"; Section 2.2, figure of
+ * the folded and unfolded RNN).  Where the paper runs independent cells on CPU cores next to a
+ * GPU that executes cells one by one, this library runs the whole grid inside one persistent
+ * GPU kernel whose workgroups are split into one group per (layer, direction).
+ *
+ * The paper names the cell (LSTM) but prints no equations; this library uses the standard ones:
+ *   LSTM  a = W_ih x_t + b_ih + W_hh h_{t-1} + b_hh  (row blocks i, f, g, o)
+ *         c_t = sigma(a_f) c_{t-1} + sigma(a_i) tanh(a_g);   h_t = sigma(a_o) tanh(c_t)
+ *   GRU   r = sigma(W_ir x + b_ir + W_hr h + b_hr),  z likewise        (row blocks r, z, n)
+ *         n = tanh(W_in x + b_in + r (W_hn h + b_hn));   h_t = (1 - z) n + z h_{t-1}
+ * Layer l >= 1 reads the concatenation [forward, backward] of layer l-1.  The forward
+ * direction visits t = 0 .. len-1, the backward direction t = len-1 .. 0 of each sequence.
+ *
+ * Conventions for every entry point:
+ *   - no C++ or framework types cross this boundary: plain pointers, ints and sizes;
+ *   - "device pointer" means memory of the current HIP device, "host pointer" ordinary memory;
+ *   - every function returning int returns an rnn_status; nothing throws; on failure outputs
+ *     passed by pointer are left untouched;
+ *   - a model belongs to the HIP device that was current when it was created, and at most one
+ *     rnn_forward may be in flight per model (its workspace and step flags are per model).
+ */
+#ifndef RNN_MI355X_H
+#define RNN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnn_model rnn_model; /* opaque; created and destroyed by the library */
+
+enum rnn_cell { RNN_LSTM = 0, RNN_GRU = 1 };
+
+/* Storage type of x, y, the weights and the activations handed from layer to layer.
+ * Accumulation, gate arithmetic, the cell state and h0/c0/hT/cT are always fp32.
+ * With RNN_BF16 every h_t is rounded to bf16 (nearest even) when it is produced; that rounded
+ * value is what the next step, the next layer, y and hT see. */
+enum rnn_dtype { RNN_F32 = 0, RNN_BF16 = 1 };
+
+enum rnn_status {
+    RNN_OK = 0,
+    RNN_EINVAL = 1,       /* NULL where a pointer is required, size <= 0, bad enum value */
+    RNN_EUNSUPPORTED = 2, /* shape outside what the kernels support (see rnn_model_create) */
+    RNN_ENOMEM = 3,       /* host or device allocation failed */
+    RNN_EDEVICE = 4       /* a HIP call failed, or a previous forward reported a stalled step */
+};
+
+/* How the cell grid is executed.
+ *   RNN_PLAN_AUTO       wavefront when the shape allows it, otherwise cellwise.
+ *   RNN_PLAN_CELLWISE   one launch sequence per cell, cells strictly one after another on the
+ *                       stream: the single-GPU regime the paper describes in the caption of its
+ *                       unfolded-RNN figure.  Kept as the reference path and as a baseline.
+ *   RNN_PLAN_WAVEFRONT  one persistent kernel; workgroup groups per (layer, direction) advance
+ *                       along anti-diagonals of the grid, synchronised by device-scope flags. */
+enum rnn_plan { RNN_PLAN_AUTO = 0, RNN_PLAN_CELLWISE = 1, RNN_PLAN_WAVEFRONT = 2 };
+
+/*
+ * Create a model (paper, Section 1 / Section 4.1: the input of the system is a trained model).
+ *   out                receives the handle.
+ *   cell               rnn_cell.
+ *   num_layers         L >= 1.
+ *   input_size         I >= 1, width of x.
+ *   hidden_size        H >= 1.
+ *   num_directions     D = 1 or 2.
+ *   dtype              rnn_dtype of the weights, x and y.
+ *   weights            host array of L*D*4 pointers in order (l, d, {W_ih, W_hh, b_ih, b_hh}).
+ *                      W_ih[l,d] is [G*H, I_l] row-major with I_0 = I and I_l = D*H for l >= 1;
+ *                      W_hh[l,d] is [G*H, H] row-major; b_* are [G*H]; G = 4 (LSTM, row blocks
+ *                      i,f,g,o) or 3 (GRU, row blocks r,z,n).  Elements have type `dtype`
+ *                      (bf16 = the upper 16 bits of an IEEE float).  A NULL bias means zeros.
+ *   weights_on_device  0: the pointed-to arrays are host memory; 1: device memory.
+ * The library copies and repacks the weights; the caller keeps ownership of its arrays and may
+ * free them when the call returns.  The call synchronises the device.
+ * Supported shapes: hidden_size a multiple of 4 for RNN_F32 and a multiple of 8 for RNN_BF16,
+ * input_size a multiple of 8 for RNN_BF16; otherwise RNN_EUNSUPPORTED.
+ */
+int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
+                     int num_directions, int dtype, const void* const* weights,
+                     int weights_on_device);
+
+/* Free the model, its device weights and its workspace.  NULL is accepted.  The caller must
+ * have synchronised any stream that still runs a forward of this model. */
+void rnn_model_destroy(rnn_model* model);
+
+/* Choose the execution plan (rnn_plan) for later forwards.  RNN_EUNSUPPORTED when the model's
+ * shape cannot run under that plan. */
+int rnn_model_set_plan(rnn_model* model, int plan);
+
+/* Size the workspace for sequences of up to T steps and B sequences now, so that later
+ * rnn_forward calls within these limits allocate nothing.  May synchronise the device. */
+int rnn_model_reserve(rnn_model* model, int T, int B);
+
+/*
+ * Run the forward pass of the whole cell grid (Section 2.2, unfolded-RNN figure; Section 3,
+ * the computation graph G = (V, E) whose vertices here are the cells).
+ * All tensors are contiguous, time-major DEVICE pointers owned by the caller:
+ *   x        [T, B, I]      dtype     input
+ *   lengths  [B]            int32     valid steps per sequence, 1 <= lengths[b] <= T; NULL = all T.
+ *                                      Values outside the range are clamped to [0, T] on the device.
+ *   h0, c0   [L*D, B, H]    fp32      initial state, row l*D+d; NULL = zeros; c0 unused for GRU
+ *   y        [T, B, D*H]    dtype     output of the last layer; positions t >= lengths[b] receive
+ *                                      +0.0 (all-zero bits)
+ *   hT, cT   [L*D, B, H]    fp32      state after the last valid step of each sequence in each
+ *                                      direction; either may be NULL; cT unused for GRU
+ *   T, B                               steps and sequences in this call (>= 1)
+ *   stream                             hipStream_t passed as void* (NULL = the default stream)
+ * The call enqueues work on `stream` and returns without waiting; outputs are valid once the
+ * stream has reached the end of that work.  It allocates device memory only if T or B exceed
+ * what earlier calls or rnn_model_reserve sized the workspace for (then it synchronises).
+ * x and y must not overlap.  Inputs are not validated on the device beyond the clamping above.
+ */
+int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,
+                const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream);
+
+/*
+ * The input projection alone, for all time steps at once (the step that does not depend on the
+ * recurrence: cell (l, t) consumes x_t, Section 2.2): for layer `layer`, all directions,
+ *   gx[row, d, u, s] = sum_k in[row, k] * W_ih[l, d][s-th gate row of unit u, k]
+ * in (DEVICE, [rows, I_l], dtype, row-major) -> gx (DEVICE, [rows, D, H, 4], fp32).
+ * Slot s is i,f,g,o for LSTM and r,z,n,(zero) for GRU.  No bias is added.  Asynchronous on
+ * `stream`.  Exposed so the projection can be tested and measured on its own.
+ */
+int rnn_input_projection(rnn_model* model, int layer, const void* in, float* gx, int rows,
+                         void* stream);
+
+/* After the stream has been synchronised: RNN_OK, or RNN_EDEVICE if a workgroup of the last
+ * persistent forward gave up waiting for a step flag (its outputs are then undefined). */
+int rnn_model_check(rnn_model* model);
+
+/* Bytes of device memory the model currently holds: repacked weights plus workspace
+ * (the quantity the paper's memory model sums per operator, Section 3, Equation 4). */
+size_t rnn_model_device_bytes(const rnn_model* model);
+
+/* Static, NUL-terminated description of an rnn_status value. */
+const char* rnn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNN_MI355X_H */

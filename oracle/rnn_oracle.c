@@ -114,6 +114,16 @@ static void gru_cell(int variant, int In, int H, const double *W_ih, const doubl
     }
 }
 
+/* The input projection on its own: P[r, j] = sum_k in[r, k] * W[j, k] for r < rows, j < n_out.
+ * This is the part of a cell that depends only on x_t (Section 2.2: every cell consumes its
+ * own x_t), written as one dot product per output element. */
+int rnn_oracle_projection(int rows, int n_out, int K, const double *in, const double *W, double *P) {
+    if (!in || !W || !P || rows < 1 || n_out < 1 || K < 1) return 1;
+    for (int r = 0; r < rows; ++r)
+        for (int j = 0; j < n_out; ++j) P[(size_t)r * n_out + j] = dot(W + (size_t)j * K, in + (size_t)r * K, K);
+    return 0;
+}
+
 int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, int T, int B,
                        const double *const *weights, const double *x, const int *lengths,
                        const double *h0, const double *c0, double *y, double *hT, double *cT,

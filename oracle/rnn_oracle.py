@@ -48,6 +48,8 @@ def _load():
         lib.rnn_oracle_forward.argtypes = [ctypes.c_int] * 8 + [
             ctypes.POINTER(dp), dp, ctypes.POINTER(ctypes.c_int), dp, dp, dp, dp, dp, dp,
             ctypes.c_int]
+        lib.rnn_oracle_projection.restype = ctypes.c_int
+        lib.rnn_oracle_projection.argtypes = [ctypes.c_int] * 3 + [dp, dp, dp]
         _lib = lib
     return _lib
 
@@ -119,3 +121,18 @@ def forward_workload(wl, nthreads: int = 1, **kw):
     c = wl.cfg
     return forward(c.cell, c.L, c.D, c.I, c.H, wl.weights, wl.x, wl.lengths, wl.h0, wl.c0,
                    nthreads=nthreads, **kw)
+
+
+def projection(inp, W_ih):
+    """P = inp @ W_ih.T, one scalar dot product per element (inp [rows, K], W_ih [n_out, K])."""
+    lib = _load()
+    inp = _as_f64(inp)
+    W_ih = _as_f64(W_ih)
+    rows, K = inp.shape
+    n_out, K2 = W_ih.shape
+    assert K == K2
+    P = np.empty((rows, n_out), dtype=np.float64)
+    rc = lib.rnn_oracle_projection(rows, n_out, K, _ptr(inp), _ptr(W_ih), _ptr(P))
+    if rc != 0:
+        raise ValueError("rnn_oracle_projection failed with status %d" % rc)
+    return P

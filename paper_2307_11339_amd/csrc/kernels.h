@@ -1,0 +1,73 @@
+// Launchers of the gfx950 kernels (internal to the library; the public boundary is include/rnn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rnn {
+
+// ---- input projection (gemm.hip) -----------------------------------------------------------
+// C[m, n] = sum_k A[m, k] * W[n, k];  A is [M, K] with row stride lda, W is [N, K] with row
+// stride ldw (both in `dtype`), C is fp32 with row stride ldc.  bf16 needs K, lda, ldw multiples
+// of 8 and 16-byte aligned base pointers.
+hipError_t launch_gemm_nt(int dtype, const void* A, int lda, const void* W, int ldw, float* C,
+                          int ldc, int M, int N, int K, hipStream_t stream);
+
+// ---- state set-up / tear-down and the cellwise plan (cellwise.hip) -------------------------
+// h_f32, c_f32: [n] fp32 working state; h_st: [n] storage-type copy of h (operand of the next
+// recurrent product).  h0 / c0 may be NULL (zeros).
+hipError_t launch_state_init(int dtype, const float* h0, const float* c0, float* h_f32,
+                             float* c_f32, void* h_st, size_t n, hipStream_t stream);
+hipError_t launch_state_export(const float* h_f32, const float* c_f32, float* hT, float* cT,
+                               size_t n, hipStream_t stream);
+
+struct CellStepArgs {
+    int cell, dtype;
+    int B, H, D, d, t;
+    const float* gx;      // [T*B, D, H, 4] projection of this layer (no bias)
+    const float* gh;      // [B, H, 4] recurrent product of this step and direction
+    const float* bias;    // [H, 4]
+    float* h_f32;         // [B, H] in/out
+    float* c_f32;         // [B, H] in/out
+    void* h_st;           // [B, H] storage type, out
+    void* out;            // [T, B, D*H] storage type; this step writes row t, columns d*H..
+    const int32_t* lengths;  // [B] or NULL
+    int T;
+};
+hipError_t launch_cell_step(const CellStepArgs& a, hipStream_t stream);
+
+// ---- persistent wavefront kernel (wavefront.hip) -------------------------------------------
+constexpr int WF_MAX_LAYERS = 16;  // layers that may run concurrently in one launch
+
+struct WavefrontArgs {
+    int cell, dtype;
+    int T, B, H, D;
+    int L_total;                 // layers of the model (for the hT / cT row index)
+    int l0, LP;                  // this launch runs layers [l0, l0 + LP)
+    int RT, CT;                  // 16-row tiles and 16-column tiles per workgroup
+    int nrb, ncb;                // row blocks and column blocks per (layer, direction)
+    const void* whh[WF_MAX_LAYERS * 2];   // packed W_hh per (local layer, direction): [4H, H]
+    const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
+    const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
+    const float* gx;             // projection of layer l0: [T*B, D, H, 4]
+    void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type
+    void* ring;                  // [LP*D, 2, B, H] storage type: h of the previous / current step
+    const float* h0;             // [L*D, B, H] or NULL
+    const float* c0;
+    float* hT;                   // [L*D, B, H] or NULL
+    float* cT;
+    const int32_t* lengths;      // [B] or NULL
+    unsigned* flags;             // [LP*D, ncb, T] step counters, zero on entry
+    unsigned* status;            // [1]: set to 1 if a workgroup gave up waiting
+    unsigned long long* ticks;   // NULL, or [LP*D, T] device clock when a step was published
+    unsigned spin_limit;         // polls before a wait is abandoned
+};
+// Returns hipErrorInvalidValue when no kernel variant exists for (dtype, RT, CT, H).
+hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream);
+// True when launch_wavefront has a variant for this combination.
+bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool fused);
+// Prepare ring slot 1 (the state "before step 0") from h0 and clear the step flags.
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int B, int H,
+                                 void* ring, unsigned* flags, size_t nflags, hipStream_t stream);
+
+}  // namespace rnn

@@ -1,0 +1,460 @@
+// Host side of the library: the C ABI of include/rnn.h, weight repacking, workspace and the
+// choice of execution plan.  All arithmetic of the forward pass runs in the HIP kernels.
+#include "../../include/rnn.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "kernels.h"
+
+using namespace rnn;
+
+namespace {
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+};
+
+struct Plan {
+    int kind = RNN_PLAN_CELLWISE;   // resolved plan (never AUTO)
+    int LP = 1, RT = 1, CT = 1, nrb = 0, ncb = 0;
+};
+
+}  // namespace
+
+struct rnn_model {
+    int cell, L, I, H, D, dtype;
+    int device = 0;
+    int num_cus = 0;
+    int requested_plan = RNN_PLAN_AUTO;
+    size_t esize = 4;  // bytes per stored element
+
+    // packed weights per layer: W_ih for all directions [D*4H, I_l]; per (l, d): W_hh [4H, H], bias [H, 4]
+    std::vector<DevBuf> wih, whh, bias;
+    size_t weight_bytes = 0;
+
+    // workspace, sized for (T_res, B_res)
+    int T_res = 0, B_res = 0;
+    DevBuf gx, ring, flags, status, h_f32, c_f32, h_st, gh, ticks;
+    std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
+    size_t workspace_bytes = 0;
+    bool want_ticks = false;
+
+    int layer_input(int l) const { return l == 0 ? I : D * H; }
+};
+
+namespace {
+
+int dev_alloc(DevBuf& b, size_t bytes) {
+    b.p = nullptr;
+    b.bytes = 0;
+    if (bytes == 0) return RNN_OK;
+    if (hipMalloc(&b.p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        b.p = nullptr;
+        return RNN_ENOMEM;
+    }
+    b.bytes = bytes;
+    return RNN_OK;
+}
+
+void dev_free(DevBuf& b) {
+    if (b.p) (void)hipFree(b.p);
+    b.p = nullptr;
+    b.bytes = 0;
+}
+
+void free_workspace(rnn_model* m) {
+    dev_free(m->gx); dev_free(m->ring); dev_free(m->flags); dev_free(m->h_f32);
+    dev_free(m->c_f32); dev_free(m->h_st); dev_free(m->gh); dev_free(m->ticks);
+    for (auto& b : m->ybuf) dev_free(b);
+    m->ybuf.clear();
+    m->workspace_bytes = 0;
+    m->T_res = m->B_res = 0;
+}
+
+constexpr int FLAG_COLBLOCKS_MAX = 16;
+
+int alloc_workspace(rnn_model* m, int T, int B) {
+    free_workspace(m);
+    const size_t rows = (size_t)T * B;
+    const size_t state = (size_t)m->L * m->D * B * m->H;
+    int rc = RNN_OK;
+    auto get = [&](DevBuf& b, size_t bytes) {
+        if (rc == RNN_OK) {
+            rc = dev_alloc(b, bytes);
+            if (rc == RNN_OK) m->workspace_bytes += bytes;
+        }
+    };
+    get(m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
+    m->ybuf.resize(m->L > 1 ? m->L - 1 : 0);
+    for (auto& b : m->ybuf) get(b, rows * m->D * m->H * m->esize);
+    get(m->ring, state * 2 * m->esize);
+    get(m->flags, (size_t)m->L * m->D * FLAG_COLBLOCKS_MAX * T * sizeof(unsigned));
+    get(m->h_f32, state * sizeof(float));
+    get(m->c_f32, state * sizeof(float));
+    get(m->h_st, state * m->esize);
+    get(m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
+    get(m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    if (rc != RNN_OK) {
+        free_workspace(m);
+        return rc;
+    }
+    m->T_res = T;
+    m->B_res = B;
+    return RNN_OK;
+}
+
+// Choose how the grid of cells is laid over the compute units for batch size B.
+bool choose_wavefront(const rnn_model* m, int B, Plan& plan) {
+    if (m->H % 4 != 0) return false;
+    const int row_tiles = m->H / 4;
+    const int col_tiles = (B + 15) / 16;
+    const int lp_max = (m->D == 1) ? (m->L < WF_MAX_LAYERS ? m->L : WF_MAX_LAYERS) : 1;
+    static const int cand[][2] = {{1, 1}, {2, 1}, {4, 1}, {1, 4}, {4, 4}};
+    for (int launches = (m->L + lp_max - 1) / lp_max; launches <= m->L; ++launches) {
+        const int LP = (m->L + launches - 1) / launches;
+        const int budget = m->num_cus / (LP * m->D);
+        int best = -1, best_cost = 0, best_rt = 0;
+        for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
+            const int RT = cand[c][0], CT = cand[c][1];
+            if (row_tiles % RT) continue;
+            if (!wavefront_variant_exists(m->dtype, RT, CT, m->H, LP > 1)) continue;
+            const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
+            if (nrb * ncb > budget || ncb > FLAG_COLBLOCKS_MAX) continue;
+            const int cost = RT * CT;
+            if (best < 0 || cost < best_cost || (cost == best_cost && RT > best_rt)) {
+                best = c; best_cost = cost; best_rt = RT;
+            }
+        }
+        if (best >= 0) {
+            plan.kind = RNN_PLAN_WAVEFRONT;
+            plan.LP = LP;
+            plan.RT = cand[best][0];
+            plan.CT = cand[best][1];
+            plan.nrb = row_tiles / plan.RT;
+            plan.ncb = (col_tiles + plan.CT - 1) / plan.CT;
+            return true;
+        }
+    }
+    return false;
+}
+
+int resolve_plan(const rnn_model* m, int B, Plan& plan) {
+    if (m->requested_plan == RNN_PLAN_CELLWISE) {
+        plan = Plan();
+        return RNN_OK;
+    }
+    if (choose_wavefront(m, B, plan)) return RNN_OK;
+    if (m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    plan = Plan();
+    return RNN_OK;
+}
+
+// Gate row of the caller's [G*H, K] matrix that feeds slot s of unit u; -1 = no row (zeros).
+int source_row(int cell, bool recurrent, int H, int u, int s) {
+    if (cell == CELL_LSTM) return s * H + u;           // i, f, g, o
+    if (s < 2) return s * H + u;                        // r, z
+    if (s == 2) return recurrent ? -1 : 2 * H + u;      // n_x: input part of the candidate
+    return recurrent ? 2 * H + u : -1;                  // n_h: recurrent part of the candidate
+}
+
+float elem_to_f32(const void* base, size_t i, int dtype) {
+    if (dtype == DT_BF16) return bf16_to_f32(((const bf16_t*)base)[i]);
+    return ((const float*)base)[i];
+}
+
+#define HIP_TRY(expr)                       \
+    do {                                    \
+        if ((expr) != hipSuccess) {         \
+            (void)hipGetLastError();        \
+            return RNN_EDEVICE;             \
+        }                                   \
+    } while (0)
+
+int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
+                     const float* c0, void* y, float* hT, float* cT, int T, int B,
+                     hipStream_t st) {
+    const size_t per = (size_t)B * m->H;
+    const size_t state = (size_t)m->L * m->D * per;
+    HIP_TRY(launch_state_init(m->dtype, h0, c0, (float*)m->h_f32.p, (float*)m->c_f32.p,
+                              m->h_st.p, state, st));
+    const int N4 = SLOTS * m->H;
+    for (int l = 0; l < m->L; ++l) {
+        const void* in = (l == 0) ? x : m->ybuf[l - 1].p;
+        void* out = (l == m->L - 1) ? y : m->ybuf[l].p;
+        const int K = m->layer_input(l);
+        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l].p, K, (float*)m->gx.p, m->D * N4,
+                               T * B, m->D * N4, K, st));
+        for (int s = 0; s < T; ++s) {
+            for (int d = 0; d < m->D; ++d) {
+                const int g = l * m->D + d;
+                float* gh = (float*)m->gh.p + (size_t)d * B * N4;
+                void* hst = (char*)m->h_st.p + (size_t)g * per * m->esize;
+                HIP_TRY(launch_gemm_nt(m->dtype, hst, m->H, m->whh[g].p, m->H, gh, N4, B, N4,
+                                       m->H, st));
+                CellStepArgs a;
+                a.cell = m->cell; a.dtype = m->dtype;
+                a.B = B; a.H = m->H; a.D = m->D; a.d = d; a.t = d ? (T - 1 - s) : s;
+                a.gx = (const float*)m->gx.p; a.gh = gh; a.bias = (const float*)m->bias[g].p;
+                a.h_f32 = (float*)m->h_f32.p + (size_t)g * per;
+                a.c_f32 = (float*)m->c_f32.p + (size_t)g * per;
+                a.h_st = hst; a.out = out; a.lengths = lengths; a.T = T;
+                HIP_TRY(launch_cell_step(a, st));
+            }
+        }
+    }
+    HIP_TRY(launch_state_export((const float*)m->h_f32.p, (const float*)m->c_f32.p, hT,
+                                m->cell == CELL_LSTM ? cT : nullptr, state, st));
+    return RNN_OK;
+}
+
+int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
+                      const float* h0, const float* c0, void* y, float* hT, float* cT, int T,
+                      int B, hipStream_t st) {
+    const int N4 = SLOTS * m->H;
+    for (int l0 = 0; l0 < m->L; l0 += plan.LP) {
+        const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
+        const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
+        const int K = m->layer_input(l0);
+        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
+                               T * B, m->D * N4, K, st));
+        const size_t nflags = (size_t)LP * m->D * plan.ncb * T;
+        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, B, m->H, m->ring.p,
+                                      (unsigned*)m->flags.p, nflags, st));
+        WavefrontArgs a;
+        memset(&a, 0, sizeof(a));
+        a.cell = m->cell; a.dtype = m->dtype;
+        a.T = T; a.B = B; a.H = m->H; a.D = m->D; a.L_total = m->L;
+        a.l0 = l0; a.LP = LP; a.RT = plan.RT; a.CT = plan.CT; a.nrb = plan.nrb; a.ncb = plan.ncb;
+        for (int ll = 0; ll < LP; ++ll) {
+            const int l = l0 + ll;
+            for (int d = 0; d < m->D; ++d) {
+                a.whh[ll * m->D + d] = m->whh[l * m->D + d].p;
+                a.wih[ll * m->D + d] = m->wih[l].p;  // fused layers have D = 1
+                a.bias[ll * m->D + d] = (const float*)m->bias[l * m->D + d].p;
+            }
+            a.out[ll] = (l == m->L - 1) ? y : m->ybuf[l].p;
+        }
+        a.gx = (const float*)m->gx.p;
+        a.ring = m->ring.p;
+        a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
+        a.flags = (unsigned*)m->flags.p;
+        a.status = (unsigned*)m->status.p;
+        a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
+        a.spin_limit = 1u << 22;
+        HIP_TRY(launch_wavefront(a, st));
+    }
+    return RNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
+                     int num_directions, int dtype, const void* const* weights,
+                     int weights_on_device) {
+    if (!out || !weights) return RNN_EINVAL;
+    if (cell != RNN_LSTM && cell != RNN_GRU) return RNN_EINVAL;
+    if (dtype != RNN_F32 && dtype != RNN_BF16) return RNN_EINVAL;
+    if (num_layers < 1 || input_size < 1 || hidden_size < 1) return RNN_EINVAL;
+    if (num_directions != 1 && num_directions != 2) return RNN_EINVAL;
+    if (num_layers > 1024 || input_size > (1 << 20) || hidden_size > (1 << 16)) return RNN_EUNSUPPORTED;
+    const int align = (dtype == RNN_BF16) ? 8 : 4;
+    if (hidden_size % align != 0) return RNN_EUNSUPPORTED;
+    if (dtype == RNN_BF16 && input_size % 8 != 0) return RNN_EUNSUPPORTED;
+    const int G = (cell == RNN_LSTM) ? 4 : 3;
+    for (int i = 0; i < num_layers * num_directions * 4; ++i)
+        if ((i % 4) < 2 && !weights[i]) return RNN_EINVAL;  // the two matrices are mandatory
+
+    rnn_model* m = new (std::nothrow) rnn_model();
+    if (!m) return RNN_ENOMEM;
+    m->cell = cell; m->L = num_layers; m->I = input_size; m->H = hidden_size;
+    m->D = num_directions; m->dtype = dtype;
+    m->esize = (dtype == RNN_BF16) ? 2 : 4;
+    int rc = RNN_OK;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&m->device) != hipSuccess ||
+        hipGetDeviceProperties(&prop, m->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete m;
+        return RNN_EDEVICE;
+    }
+    m->num_cus = prop.multiProcessorCount;
+
+    const int H = m->H, D = m->D;
+    m->wih.resize(m->L);
+    m->whh.resize((size_t)m->L * D);
+    m->bias.resize((size_t)m->L * D);
+    std::vector<unsigned char> src, packed;
+    std::vector<float> bias_host((size_t)H * SLOTS);
+    auto fetch = [&](const void* p, size_t bytes) -> const unsigned char* {
+        if (!weights_on_device) return (const unsigned char*)p;
+        src.resize(bytes);
+        if (hipMemcpy(src.data(), p, bytes, hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        return src.data();
+    };
+    auto pack_matrix = [&](const void* wsrc, int K, bool recurrent, unsigned char* dst) -> int {
+        const unsigned char* s = fetch(wsrc, (size_t)G * H * K * m->esize);
+        if (!s) return RNN_EDEVICE;
+        const size_t rowb = (size_t)K * m->esize;
+        for (int u = 0; u < H; ++u)
+            for (int sl = 0; sl < SLOTS; ++sl) {
+                const int r = source_row(cell, recurrent, H, u, sl);
+                unsigned char* d = dst + ((size_t)u * SLOTS + sl) * rowb;
+                if (r < 0) memset(d, 0, rowb);
+                else memcpy(d, s + (size_t)r * rowb, rowb);
+            }
+        return RNN_OK;
+    };
+    for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
+        const int K = m->layer_input(l);
+        const size_t one = (size_t)SLOTS * H * K * m->esize;
+        packed.assign(one * D, 0);
+        for (int d = 0; d < D && rc == RNN_OK; ++d)
+            rc = pack_matrix(weights[(l * D + d) * 4 + 0], K, false, packed.data() + one * d);
+        if (rc == RNN_OK) rc = dev_alloc(m->wih[l], one * D);
+        if (rc == RNN_OK && hipMemcpy(m->wih[l].p, packed.data(), one * D, hipMemcpyHostToDevice) != hipSuccess)
+            rc = RNN_EDEVICE;
+        m->weight_bytes += one * D;
+        for (int d = 0; d < D && rc == RNN_OK; ++d) {
+            const int g = l * D + d;
+            const size_t hb = (size_t)SLOTS * H * H * m->esize;
+            packed.assign(hb, 0);
+            rc = pack_matrix(weights[g * 4 + 1], H, true, packed.data());
+            if (rc == RNN_OK) rc = dev_alloc(m->whh[g], hb);
+            if (rc == RNN_OK && hipMemcpy(m->whh[g].p, packed.data(), hb, hipMemcpyHostToDevice) != hipSuccess)
+                rc = RNN_EDEVICE;
+            m->weight_bytes += hb;
+            if (rc != RNN_OK) break;
+            // biases: LSTM folds b_ih + b_hh per gate; GRU keeps b_in and b_hn apart
+            const size_t bb = (size_t)G * H * m->esize;
+            std::vector<unsigned char> bi(bb, 0), bh(bb, 0);
+            if (weights[g * 4 + 2]) {
+                const unsigned char* s = fetch(weights[g * 4 + 2], bb);
+                if (!s) { rc = RNN_EDEVICE; break; }
+                memcpy(bi.data(), s, bb);
+            }
+            if (weights[g * 4 + 3]) {
+                const unsigned char* s = fetch(weights[g * 4 + 3], bb);
+                if (!s) { rc = RNN_EDEVICE; break; }
+                memcpy(bh.data(), s, bb);
+            }
+            for (int u = 0; u < H; ++u)
+                for (int sl = 0; sl < SLOTS; ++sl) {
+                    const int ri = source_row(cell, false, H, u, sl);
+                    const int rh = source_row(cell, true, H, u, sl);
+                    float v = 0.0f;
+                    if (ri >= 0) v += elem_to_f32(bi.data(), ri, dtype);
+                    if (rh >= 0) v += elem_to_f32(bh.data(), rh, dtype);
+                    bias_host[(size_t)u * SLOTS + sl] = v;
+                }
+            const size_t pb = bias_host.size() * sizeof(float);
+            rc = dev_alloc(m->bias[g], pb);
+            if (rc == RNN_OK && hipMemcpy(m->bias[g].p, bias_host.data(), pb, hipMemcpyHostToDevice) != hipSuccess)
+                rc = RNN_EDEVICE;
+            m->weight_bytes += pb;
+        }
+    }
+    if (rc == RNN_OK) rc = dev_alloc(m->status, sizeof(unsigned));
+    if (rc == RNN_OK && hipMemset(m->status.p, 0, sizeof(unsigned)) != hipSuccess) rc = RNN_EDEVICE;
+    if (rc == RNN_OK && hipDeviceSynchronize() != hipSuccess) rc = RNN_EDEVICE;
+    if (rc != RNN_OK) {
+        (void)hipGetLastError();
+        rnn_model_destroy(m);
+        return rc;
+    }
+    m->want_ticks = getenv("RNN_DEBUG_TICKS") != nullptr;
+    *out = m;
+    return RNN_OK;
+}
+
+void rnn_model_destroy(rnn_model* m) {
+    if (!m) return;
+    free_workspace(m);
+    for (auto& b : m->wih) dev_free(b);
+    for (auto& b : m->whh) dev_free(b);
+    for (auto& b : m->bias) dev_free(b);
+    dev_free(m->status);
+    delete m;
+}
+
+int rnn_model_set_plan(rnn_model* m, int plan) {
+    if (!m) return RNN_EINVAL;
+    if (plan != RNN_PLAN_AUTO && plan != RNN_PLAN_CELLWISE && plan != RNN_PLAN_WAVEFRONT)
+        return RNN_EINVAL;
+    if (plan == RNN_PLAN_WAVEFRONT) {
+        Plan p;
+        if (!choose_wavefront(m, 1, p)) return RNN_EUNSUPPORTED;
+    }
+    m->requested_plan = plan;
+    return RNN_OK;
+}
+
+int rnn_model_reserve(rnn_model* m, int T, int B) {
+    if (!m || T < 1 || B < 1) return RNN_EINVAL;
+    if (T <= m->T_res && B <= m->B_res) return RNN_OK;
+    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return RNN_EDEVICE; }
+    const int Tn = T > m->T_res ? T : m->T_res, Bn = B > m->B_res ? B : m->B_res;
+    return alloc_workspace(m, Tn, Bn);
+}
+
+int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
+                const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
+    if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
+    if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
+    int rc = rnn_model_reserve(m, T, B);
+    if (rc != RNN_OK) return rc;
+    Plan plan;
+    rc = resolve_plan(m, B, plan);
+    if (rc != RNN_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
+    if (plan.kind == RNN_PLAN_WAVEFRONT)
+        return forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
+    return forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);
+}
+
+int rnn_input_projection(rnn_model* m, int layer, const void* in, float* gx, int rows,
+                         void* stream) {
+    if (!m || !in || !gx || rows < 1 || layer < 0 || layer >= m->L) return RNN_EINVAL;
+    const int K = m->layer_input(layer);
+    const int N = m->D * SLOTS * m->H;
+    HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[layer].p, K, gx, N, rows, N, K,
+                           (hipStream_t)stream));
+    return RNN_OK;
+}
+
+int rnn_model_check(rnn_model* m) {
+    if (!m) return RNN_EINVAL;
+    unsigned st = 0;
+    HIP_TRY(hipMemcpy(&st, m->status.p, sizeof(st), hipMemcpyDeviceToHost));
+    return st == 0 ? RNN_OK : RNN_EDEVICE;
+}
+
+size_t rnn_model_device_bytes(const rnn_model* m) {
+    if (!m) return 0;
+    return m->weight_bytes + m->workspace_bytes + sizeof(unsigned);
+}
+
+const char* rnn_status_string(int status) {
+    switch (status) {
+        case RNN_OK: return "ok";
+        case RNN_EINVAL: return "invalid argument";
+        case RNN_EUNSUPPORTED: return "unsupported shape or plan";
+        case RNN_ENOMEM: return "out of memory";
+        case RNN_EDEVICE: return "device error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,381 @@
+// Persistent wavefront kernel: the whole layer x time grid of cells in one launch.
+//
+// The paper's observation (Section 1; Section 2.2, figure of the unfolded RNN): after unrolling,
+// cell (l, t) depends only on cells (l, t-1) and (l-1, t), so the cells of one anti-diagonal
+// can run side by side; a GPU that is handed the cells one at a time cannot use this.  Here
+// the workgroups of one launch are divided into one group per (layer, direction).  A group
+// walks along time; it starts step t as soon as its own step t-1 and the step t of the layer
+// below have been published, so the groups settle on successive anti-diagonals of the grid.
+//
+// Inside a group, a workgroup owns RT*4 hidden units (RT tiles of 16 gate rows, the four
+// pre-activation slots of a unit being adjacent rows) for CT*16 sequences.  Its slice of W_hh
+// (and of W_ih for layers whose projection is fused) stays in registers for the whole launch as
+// the A operand of 16-row MFMA tiles; the activations h_{t-1} (and x_t) are the B operand.  The
+// four waves of a workgroup split K, so each wave reads a disjoint quarter of the activation
+// vector straight from global memory; partial sums meet in LDS, then every (unit, sequence)
+// pair is finished by one fixed lane that keeps c and h of that pair in registers.
+//
+// Steps are published through one counter per (layer, direction, column block, step):
+// a workgroup that has written its part of h_t adds 1 (after a device-scope release); readers
+// poll until the counter equals the number of row blocks, then acquire.  Every wait is bounded:
+// a wave that exhausts its poll budget raises the status word and stops waiting, so the grid
+// always drains.
+#include "common.h"
+#include "kernels.h"
+
+namespace rnn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+namespace {
+
+struct TraitsBf16 {
+    typedef bf16_t elem;
+    typedef bf16x8 frag;
+    static constexpr int KW = 32;  // K elements consumed by one MFMA
+    // lane -> first K element of its fragment inside a KW block
+    static __device__ inline int koff(int lane) { return 8 * (lane >> 4); }
+    static __device__ inline frag load(const elem* p) { return *reinterpret_cast<const frag*>(p); }
+    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ inline elem store_val(float h, float& kept) {
+        const bf16_t b = f32_to_bf16(h);
+        kept = bf16_to_f32(b);
+        return b;
+    }
+    static __device__ inline elem zero() { return 0; }
+};
+
+struct TraitsF32 {
+    typedef float elem;
+    typedef float frag;
+    static constexpr int KW = 4;
+    static __device__ inline int koff(int lane) { return lane >> 4; }
+    static __device__ inline frag load(const elem* p) { return *p; }
+    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
+    static __device__ inline elem zero() { return 0.0f; }
+};
+
+// Wait until *flag >= target.  Lane 0 polls; the verdict is shared through a scalar register.
+// Returns false when the wait was abandoned (budget exhausted or another workgroup gave up).
+__device__ inline bool wait_flag(unsigned* flag, unsigned target, unsigned* status,
+                                 unsigned spin_limit, bool& aborted) {
+    if (aborted) return false;
+    unsigned spins = 0;
+    for (;;) {
+        const unsigned v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v >= target) break;
+        ++spins;
+        if ((spins & 1023u) == 0u) {
+            const unsigned st = __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (st != 0u || spins >= spin_limit) {
+                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                aborted = true;
+                return false;
+            }
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return true;
+}
+
+template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
+__global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
+    typedef typename TR::elem elem;
+    typedef typename TR::frag frag;
+    constexpr int KW = TR::KW;
+    constexpr int NTILE = RT * CT;                 // 16x16 output tiles per workgroup
+    constexpr int NOWN = (NTILE + 3) / 4;          // tiles finished by one wave
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+
+    // Workgroups are handed to the 8 XCDs round-robin; renumber them so that the workgroups of
+    // one (layer, direction, column block) chain sit on as few XCDs as possible.
+    int v = blockIdx.x;
+    if ((gridDim.x & 7) == 0) v = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int wpg = p.nrb * p.ncb;
+    const int g = v / wpg;                          // local (layer, direction) index
+    if (g >= p.LP * p.D) return;
+    const int r = v - g * wpg;
+    const int cb = r / p.nrb, rb = r - cb * p.nrb;
+    const int ll = g / p.D, d = g - ll * p.D;
+    const int l = p.l0 + ll;
+    const bool fused = FUSED && ll > 0;
+    const int H = p.H, B = p.B, T = p.T;
+    const int kq = H / 4;                           // K range of one wave inside each part
+
+    // ---- resident weights: A operand fragments ---------------------------------------------
+    frag wh[RT][KB];
+    frag wx[FUSED ? RT : 1][FUSED ? KB : 1];
+    {
+        const elem* whh = static_cast<const elem*>(p.whh[g]);
+        const elem* wih = static_cast<const elem*>(p.wih[g]);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const int k = w * kq + kb * KW + TR::koff(lane);
+                wh[rt][kb] = TR::load(whh + row * H + k);
+                if (FUSED) {
+                    if (fused) wx[rt][kb] = TR::load(wih + row * H + k);
+                    else wx[rt][kb] = wh[rt][kb];
+                }
+            }
+        }
+    }
+
+    // ---- per-lane state of the (unit, sequence) pairs this lane finishes ---------------------
+    float c_reg[NOWN], h_reg[NOWN];
+    f32x4 bias_reg[NOWN];
+    int len_reg[NOWN], col_reg[NOWN], unit_reg[NOWN];
+    const size_t state_row = (size_t)(l * p.D + d) * B;
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) {
+        const int j = w + 4 * o;                    // tile index = rt * CT + ct
+        const int rt = j / CT, ct = j - rt * CT;
+        const int unit = (rb * RT + rt) * 4 + (lane >> 4);
+        const int col = (cb * CT + ct) * 16 + (lane & 15);
+        unit_reg[o] = unit;
+        col_reg[o] = col;
+        c_reg[o] = 0.0f;
+        h_reg[o] = 0.0f;
+        len_reg[o] = 0;
+        bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (j < NTILE && col < B) {
+            const size_t si = (state_row + col) * H + unit;
+            if (p.h0) h_reg[o] = p.h0[si];
+            if (p.c0) c_reg[o] = p.c0[si];
+            len_reg[o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
+            bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+        }
+    }
+
+    // B operand columns of this lane (clamped so that loads stay in bounds; columns >= B are
+    // computed from a duplicate of the last sequence and never stored)
+    int bcol[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) bcol[ct] = min((cb * CT + ct) * 16 + (lane & 15), B - 1);
+
+    elem* ring = static_cast<elem*>(p.ring) + (size_t)g * 2 * B * H;
+    elem* out = static_cast<elem*>(p.out[ll]);
+    const elem* below = fused ? static_cast<const elem*>(p.out[ll - 1]) : nullptr;
+    const int out_ld = p.D * H;
+    unsigned* my_flags = p.flags + ((size_t)g * p.ncb + cb) * T;
+    unsigned* below_flags = fused ? p.flags + ((size_t)(g - p.D) * p.ncb + cb) * T : nullptr;
+    const unsigned target = (unsigned)p.nrb;
+    bool aborted = false;
+    const int kbase = w * kq + TR::koff(lane);
+
+    for (int s = 0; s < T; ++s) {
+        const int t = d ? (T - 1 - s) : s;
+
+        // projection of this step for the pairs this lane finishes (not needed until the gates;
+        // issued first so that the loads fly while the wave waits for the flags)
+        f32x4 gx_reg[NOWN];
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            gx_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (!fused && (w + 4 * o) < NTILE && col_reg[o] < B)
+                gx_reg[o] = *reinterpret_cast<const f32x4*>(
+                    p.gx + ((((size_t)t * B + col_reg[o]) * p.D + d) * H + unit_reg[o]) * SLOTS);
+        }
+
+        f32x4 acc[RT][CT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        if (FUSED) {
+            if (fused) {  // x_t = h_t of the layer below
+                wait_flag(below_flags + s, target, p.status, p.spin_limit, aborted);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    frag xb[CT];
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+                        xb[ct] = TR::load(below + ((size_t)t * B + bcol[ct]) * H + kbase + kb * KW);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct)
+                            acc[rt][ct] = TR::mfma(wx[rt][kb], xb[ct], acc[rt][ct]);
+                }
+            }
+        }
+
+        if (s > 0) wait_flag(my_flags + (s - 1), target, p.status, p.spin_limit, aborted);
+        {
+            const elem* hprev = ring + (size_t)((s + 1) & 1) * B * H;  // slot of step s-1
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                frag hb[CT];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    hb[ct] = TR::load(hprev + (size_t)bcol[ct] * H + kbase + kb * KW);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct)
+                        acc[rt][ct] = TR::mfma(wh[rt][kb], hb[ct], acc[rt][ct]);
+            }
+        }
+
+        // partial sums of the four K quarters meet in LDS
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+                red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
+        __syncthreads();
+
+        elem* hcur = ring + (size_t)(s & 1) * B * H;
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int j = w + 4 * o;
+            if (j < NTILE && col_reg[o] < B) {
+                f32x4 a = red[(0 * NTILE + j) * 64 + lane];
+#pragma unroll
+                for (int q = 1; q < 4; ++q) {
+                    const f32x4 b = red[(q * NTILE + j) * 64 + lane];
+                    a += b;
+                }
+                a += gx_reg[o];
+                a += bias_reg[o];
+                const bool active = t < len_reg[o];
+                const size_t oidx = ((size_t)t * B + col_reg[o]) * out_ld + (size_t)d * H + unit_reg[o];
+                if (active) {
+                    const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
+                    const float hn = cell_update<CELL>(pre, h_reg[o], c_reg[o]);
+                    const elem hv = TR::store_val(hn, h_reg[o]);
+                    out[oidx] = hv;
+                    hcur[(size_t)col_reg[o] * H + unit_reg[o]] = hv;
+                } else {
+                    float kept;
+                    out[oidx] = TR::zero();
+                    hcur[(size_t)col_reg[o] * H + unit_reg[o]] = TR::store_val(h_reg[o], kept);
+                }
+            }
+        }
+
+        // publish: every writer releases at device scope, then one thread bumps the counter
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            __hip_atomic_fetch_add(my_flags + s, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            if (p.ticks && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
+        }
+    }
+
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) {
+        const int j = w + 4 * o;
+        if (j < NTILE && col_reg[o] < B) {
+            const size_t si = (state_row + col_reg[o]) * H + unit_reg[o];
+            if (p.hT) p.hT[si] = h_reg[o];
+            if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[o];
+        }
+    }
+}
+
+template <int DT>
+__global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, int B, int H,
+                                      void* ring, unsigned* flags, size_t nflags) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nflags) flags[i] = 0u;
+    const size_t per = (size_t)B * H;
+    const size_t n = (size_t)LP * D * per;
+    if (i < n) {
+        const size_t g = i / per, rem = i - g * per;
+        const float h = h0 ? h0[((size_t)l0 * D) * per + i] : 0.0f;
+        const size_t dst = (g * 2 + 1) * per + rem;  // slot 1 holds "step -1"
+        if (DT == DT_BF16) ((bf16_t*)ring)[dst] = f32_to_bf16(h);
+        else ((float*)ring)[dst] = h;
+    }
+}
+
+template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
+hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
+    const int grid = a.LP * a.D * a.nrb * a.ncb;
+    const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
+    auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    kern<<<dim3(grid), dim3(256), smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+template <class TR, int RT, int CT, int KB>
+hipError_t launch_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
+    const bool fused = a.LP > 1;
+    if (a.cell == CELL_LSTM)
+        return fused ? launch_variant<TR, CELL_LSTM, RT, CT, KB, true>(a, stream)
+                     : launch_variant<TR, CELL_LSTM, RT, CT, KB, false>(a, stream);
+    return fused ? launch_variant<TR, CELL_GRU, RT, CT, KB, true>(a, stream)
+                 : launch_variant<TR, CELL_GRU, RT, CT, KB, false>(a, stream);
+}
+
+// (dtype, RT, CT, KB) combinations that are compiled.  KB = H / (4 * KW).
+#define RNN_WF_VARIANTS(X)                                                        \
+    X(TraitsBf16, 1, 1, 1) X(TraitsBf16, 1, 1, 2) X(TraitsBf16, 1, 1, 4) X(TraitsBf16, 1, 1, 8) \
+    X(TraitsBf16, 4, 1, 4) X(TraitsBf16, 4, 1, 8)                                 \
+    X(TraitsBf16, 1, 4, 4) X(TraitsBf16, 4, 4, 4) X(TraitsBf16, 4, 4, 8)          \
+    X(TraitsF32, 1, 1, 2) X(TraitsF32, 1, 1, 4) X(TraitsF32, 1, 1, 8)             \
+    X(TraitsF32, 2, 1, 8) X(TraitsF32, 1, 4, 4)
+
+template <class TR> struct DtOf;
+template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
+template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
+
+}  // namespace
+
+bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool /*fused*/) {
+    const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (H % (4 * kw) != 0) return false;
+    const int KB = H / (4 * kw);
+#define X(TR, rt, ct, kb) \
+    if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb) return true;
+    RNN_WF_VARIANTS(X)
+#undef X
+    return false;
+}
+
+hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
+    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
+    const int KB = a.H / (4 * kw);
+#define X(TR, rt, ct, kb)                                                         \
+    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb)        \
+        return launch_cell_fused<TR, rt, ct, kb>(a, stream);
+    RNN_WF_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int B, int H,
+                                 void* ring, unsigned* flags, size_t nflags, hipStream_t stream) {
+    const size_t n = (size_t)LP * D * B * H;
+    const size_t m = n > nflags ? n : nflags;
+    const unsigned blocks = (unsigned)((m + 255) / 256);
+    if (dtype == DT_BF16)
+        wavefront_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, B, H, ring, flags, nflags);
+    else
+        wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, B, H, ring, flags, nflags);
+    return hipGetLastError();
+}
+
+}  // namespace rnn

@@ -1,0 +1,131 @@
+"""Thin ctypes binding of the C ABI declared in include/rnn.h.
+
+The functions below have the names and argument order of the C entry points and do argument
+marshalling only (tensor -> device pointer); every step of the forward pass runs in the HIP
+library.  There is no fallback: if the compiled library is missing, loading fails loudly.
+PyTorch is used for device memory and streams, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librnn_mi355x.so")
+
+RNN_LSTM, RNN_GRU = 0, 1
+RNN_F32, RNN_BF16 = 0, 1
+RNN_OK, RNN_EINVAL, RNN_EUNSUPPORTED, RNN_ENOMEM, RNN_EDEVICE = 0, 1, 2, 3, 4
+RNN_PLAN_AUTO, RNN_PLAN_CELLWISE, RNN_PLAN_WAVEFRONT = 0, 1, 2
+
+EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_model_reserve",
+           "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
+           "rnn_status_string")
+
+_lib = None
+
+
+class RnnError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__("%s: %s (status %d)" % (what, rnn_status_string(status), status))
+        self.status = status
+
+
+def load_library() -> ctypes.CDLL:
+    """Load librnn_mi355x.so (built by paper_2307_11339_amd._build or __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("HIP library not built: %s is missing; run `python __graft_entry__.py build` "
+                          "(there is no CPU fallback)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.rnn_model_create.restype = ci
+    lib.rnn_model_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp), ci]
+    lib.rnn_model_destroy.restype = None
+    lib.rnn_model_destroy.argtypes = [vp]
+    lib.rnn_model_set_plan.restype = ci
+    lib.rnn_model_set_plan.argtypes = [vp, ci]
+    lib.rnn_model_reserve.restype = ci
+    lib.rnn_model_reserve.argtypes = [vp, ci, ci]
+    lib.rnn_forward.restype = ci
+    lib.rnn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp]
+    lib.rnn_input_projection.restype = ci
+    lib.rnn_input_projection.argtypes = [vp, ci, vp, vp, ci, vp]
+    lib.rnn_model_check.restype = ci
+    lib.rnn_model_check.argtypes = [vp]
+    lib.rnn_model_device_bytes.restype = ctypes.c_size_t
+    lib.rnn_model_device_bytes.argtypes = [vp]
+    lib.rnn_status_string.restype = ctypes.c_char_p
+    lib.rnn_status_string.argtypes = [ci]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device or host address of a tensor / array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"]
+        return t.ctypes.data
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    return t.data_ptr()
+
+
+def rnn_status_string(status: int) -> str:
+    return load_library().rnn_status_string(int(status)).decode()
+
+
+def rnn_model_create(cell: int, num_layers: int, input_size: int, hidden_size: int,
+                     num_directions: int, dtype: int, weights: Sequence, weights_on_device: int) -> int:
+    """weights: L*D*4 tensors/arrays/None in order (l, d, {W_ih, W_hh, b_ih, b_hh}).  Returns the handle."""
+    lib = load_library()
+    n = num_layers * num_directions * 4
+    assert len(weights) == n
+    arr = (ctypes.c_void_p * n)(*[_ptr(w) for w in weights])
+    out = ctypes.c_void_p()
+    rc = lib.rnn_model_create(ctypes.byref(out), cell, num_layers, input_size, hidden_size,
+                              num_directions, dtype, arr, weights_on_device)
+    if rc != RNN_OK:
+        raise RnnError(rc, "rnn_model_create")
+    return out.value
+
+
+def rnn_model_destroy(model: Optional[int]) -> None:
+    load_library().rnn_model_destroy(model)
+
+
+def rnn_model_set_plan(model: int, plan: int) -> int:
+    return load_library().rnn_model_set_plan(model, plan)
+
+
+def rnn_model_reserve(model: int, T: int, B: int) -> int:
+    return load_library().rnn_model_reserve(model, T, B)
+
+
+def rnn_forward(model: int, x, lengths, h0, c0, y, hT, cT, T: int, B: int, stream=None) -> int:
+    """Arguments as in include/rnn.h; tensors are passed by device pointer.  `stream` is a
+    torch.cuda.Stream, a raw hipStream_t value, or None for the default stream."""
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    return load_library().rnn_forward(model, _ptr(x), _ptr(lengths), _ptr(h0), _ptr(c0), _ptr(y),
+                                      _ptr(hT), _ptr(cT), T, B, s)
+
+
+def rnn_input_projection(model: int, layer: int, inp, gx, rows: int, stream=None) -> int:
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    return load_library().rnn_input_projection(model, layer, _ptr(inp), _ptr(gx), rows, s)
+
+
+def rnn_model_check(model: int) -> int:
+    return load_library().rnn_model_check(model)
+
+
+def rnn_model_device_bytes(model: int) -> int:
+    return int(load_library().rnn_model_device_bytes(model))

@@ -1,0 +1,232 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Tolerances (max-abs over y, hT, cT): 1e-4 for fp32 models, 2e-2 for bf16 models with fp32
+accumulation; padded positions of y must be +0.0 bit patterns.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = {0: 1e-4, 1: 2e-2}
+
+
+def _say(msg):
+    sys.stdout.write(msg + "\n")
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2307_11339_amd import harness, rnn, workloads
+    rnn.load_library()  # fails loudly when the HIP library has not been built
+    return harness, rnn, workloads
+
+
+def _check(harness, wl, io, ref, rows=None, tol=None):
+    """Compare device results with oracle results ref = (y, hT, cT); rows = batch rows that ref covers."""
+    c = wl.cfg
+    tol = TOL[c.dtype] if tol is None else tol
+    y, hT, cT, ybits = harness.results(io)
+    ry, rh, rc = ref
+    if rows is not None:
+        y, hT, ybits = y[:, rows], hT[:, rows], ybits[:, rows]
+        cT = cT[:, rows] if cT is not None else None
+        lengths = None if wl.lengths is None else wl.lengths[rows]
+    else:
+        lengths = wl.lengths
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(hT))
+    err_y = float(np.max(np.abs(y - ry)))
+    err_h = float(np.max(np.abs(hT - rh)))
+    err_c = float(np.max(np.abs(cT - rc))) if (rc is not None and cT is not None) else 0.0
+    _say("    max-abs error y %.3e hT %.3e cT %.3e (tolerance %.0e)" % (err_y, err_h, err_c, tol))
+    assert err_y <= tol and err_h <= tol and err_c <= tol
+    if lengths is not None:
+        for j, n in enumerate(lengths):
+            assert np.all(ybits[int(n):, j] == 0), "padded positions must be +0.0 bit patterns"
+    return max(err_y, err_h, err_c)
+
+
+SMALL = [
+    # name, cell, L, D, I, H, T, B, dtype, ragged lengths, h0
+    ("lstm_bf16_3layer", 0, 3, 1, 64, 128, 9, 5, 1, True, True),
+    ("gru_bf16_2layer", 1, 2, 1, 72, 256, 7, 19, 1, True, True),
+    ("lstm_bf16_bidir", 0, 2, 2, 40, 128, 11, 37, 1, True, True),
+    ("gru_bf16_bidir", 1, 2, 2, 64, 128, 6, 3, 1, True, False),
+    ("lstm_f32_4layer", 0, 4, 1, 20, 64, 10, 3, 0, True, True),
+    ("gru_f32_bidir", 1, 2, 2, 12, 32, 8, 18, 0, True, True),
+    ("lstm_f32_wide", 0, 1, 1, 64, 128, 5, 70, 0, False, False),
+    ("lstm_bf16_oddshape", 0, 2, 1, 24, 72, 5, 4, 1, True, True),   # H not a multiple of 128: cellwise only
+    ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
+]
+
+
+def _small_workload(W, spec):
+    name, cell, L, D, I, H, T, B, dtype, ragged, use_h0 = spec
+    cfg = W.Config(name, cell, L=L, D=D, I=I, H=H, T=T, B=B, dtype=dtype,
+                   seed=W.BASE_SEED + 1000 + sum(map(ord, name)), h0_std=0.5 if use_h0 else 0.0,
+                   len_min=1 if ragged else None)
+    wl = W.make_workload(cfg, zero_pad_x=False)   # padding content must not matter
+    if use_h0 and cell == 0:
+        rng = np.random.default_rng(cfg.seed + 7)
+        wl.c0 = rng.uniform(-1, 1, size=(L * D, B, H)).astype(np.float32)
+    return wl
+
+
+@pytest.mark.parametrize("plan", ["cellwise", "wavefront"])
+@pytest.mark.parametrize("spec", SMALL, ids=[s[0] for s in SMALL])
+def test_small_shapes(gpu, oracle, spec, plan):
+    harness, rnn, W = gpu
+    wl = _small_workload(W, spec)
+    _say("\n  case %s plan %s cfg %s" % (spec[0], plan, wl.cfg))
+    pid = rnn.RNN_PLAN_CELLWISE if plan == "cellwise" else rnn.RNN_PLAN_WAVEFRONT
+    try:
+        model = harness.DeviceModel(wl, plan=pid)
+    except rnn.RnnError as e:
+        assert plan == "wavefront" and e.status == rnn.RNN_EUNSUPPORTED and spec[0] == "lstm_bf16_oddshape"
+        return
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    ref = oracle.forward_workload(wl, nthreads=8)
+    _check(harness, wl, io, ref)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    # a second call on the same model gives identical bits (fixed reduction order, flags reset)
+    y1 = io.y.clone()
+    harness.forward(model, io)
+    import torch
+    torch.cuda.synchronize()
+    assert torch.equal(y1, io.y)
+    model.close()
+
+
+def test_null_optionals_and_device_weights(gpu, oracle):
+    harness, rnn, W = gpu
+    wl = _small_workload(W, SMALL[0])
+    wl.h0 = None; wl.c0 = None; wl.lengths = None
+    for plan in (rnn.RNN_PLAN_CELLWISE, rnn.RNN_PLAN_WAVEFRONT):
+        model = harness.DeviceModel(wl, plan=plan, weights_on_device=True)
+        io = harness.DeviceIO(wl, want_state=False)
+        harness.forward(model, io)
+        ref = oracle.forward_workload(wl, nthreads=8)
+        y, _, _, _ = harness.results(io)
+        assert np.max(np.abs(y - ref[0])) <= TOL[wl.cfg.dtype]
+        model.close()
+
+
+def test_chained_calls_equal_one_call(gpu):
+    """hT/cT of one call fed as h0/c0 of the next reproduce the single long call bit for bit."""
+    import torch
+    harness, rnn, W = gpu
+    cfg = W.Config("chain", 0, L=2, D=1, I=64, H=128, T=12, B=4, dtype=1, seed=W.BASE_SEED + 77)
+    wl = W.make_workload(cfg)
+    for plan in (rnn.RNN_PLAN_CELLWISE, rnn.RNN_PLAN_WAVEFRONT):
+        model = harness.DeviceModel(wl, plan=plan)
+        io = harness.DeviceIO(wl)
+        harness.forward(model, io)
+        torch.cuda.synchronize()
+        k = 5
+        ya = torch.empty((k, cfg.B, cfg.H), dtype=torch.bfloat16, device="cuda")
+        yb = torch.empty((cfg.T - k, cfg.B, cfg.H), dtype=torch.bfloat16, device="cuda")
+        h1, c1 = torch.empty_like(io.hT), torch.empty_like(io.cT)
+        h2, c2 = torch.empty_like(io.hT), torch.empty_like(io.cT)
+        xa, xb = io.x[:k].contiguous(), io.x[k:].contiguous()
+        assert rnn.rnn_forward(model.handle, xa, None, None, None, ya, h1, c1, k, cfg.B, torch.cuda.current_stream()) == 0
+        assert rnn.rnn_forward(model.handle, xb, None, h1, c1, yb, h2, c2, cfg.T - k, cfg.B, torch.cuda.current_stream()) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(torch.cat([ya, yb]), io.y)
+        assert torch.equal(h2, io.hT) and torch.equal(c2, io.cT)
+        model.close()
+
+
+def test_input_projection(gpu, oracle):
+    import torch
+    harness, rnn, W = gpu
+    for dtype, cell, rows, I, H, D in ((1, 0, 300, 72, 128, 2), (0, 1, 70, 20, 32, 1), (1, 1, 2100, 256, 128, 1)):
+        cfg = W.Config("proj", cell, L=1, D=D, I=I, H=H, T=rows, B=1, dtype=dtype, seed=W.BASE_SEED + 55)
+        wl = W.make_workload(cfg)
+        model = harness.DeviceModel(wl)
+        x = harness.to_device_storage(wl.x.reshape(rows, I), dtype)
+        gx = torch.full((rows, D, H, 4), 9.0, device="cuda")
+        assert rnn.rnn_input_projection(model.handle, 0, x, gx, rows, torch.cuda.current_stream()) == 0
+        torch.cuda.synchronize()
+        got = gx.cpu().numpy().astype(np.float64)
+        G = cfg.G
+        for d in range(D):
+            P = oracle.projection(wl.x.reshape(rows, I), wl.weight(0, d, 0)).reshape(rows, G, H)
+            exp = np.zeros((rows, H, 4))
+            for s in range(G):
+                exp[:, :, s] = P[:, s, :]          # LSTM i,f,g,o / GRU r,z,n -> slots 0..G-1
+            err = np.max(np.abs(got[:, d] - exp))
+            _say("    projection dtype %d rows %d error %.3e" % (dtype, rows, err))
+            assert err <= 1e-4     # exact products, fp32 accumulation over at most 256 terms
+        model.close()
+
+
+def test_error_codes(gpu):
+    import torch
+    harness, rnn, W = gpu
+    wl = _small_workload(W, SMALL[0])
+    model = harness.DeviceModel(wl)
+    io = harness.DeviceIO(wl)
+    c = wl.cfg
+    assert rnn.rnn_forward(model.handle, None, None, None, None, io.y, None, None, c.T, c.B, None) == rnn.RNN_EINVAL
+    assert rnn.rnn_forward(model.handle, io.x, None, None, None, None, None, None, c.T, c.B, None) == rnn.RNN_EINVAL
+    assert rnn.rnn_forward(model.handle, io.x, None, None, None, io.y, None, None, 0, c.B, None) == rnn.RNN_EINVAL
+    assert rnn.rnn_forward(None, io.x, None, None, None, io.y, None, None, c.T, c.B, None) == rnn.RNN_EINVAL
+    assert rnn.rnn_model_set_plan(model.handle, 99) == rnn.RNN_EINVAL
+    assert rnn.rnn_model_device_bytes(model.handle) > 0
+    with pytest.raises(rnn.RnnError):
+        rnn.rnn_model_create(5, 1, 8, 8, 1, 0, [np.zeros(1, np.float32)] * 4, 0)
+    with pytest.raises(rnn.RnnError):
+        rnn.rnn_model_create(0, 1, 8, 6, 1, 1, [np.zeros(1, np.uint16)] * 4, 0)   # H % 8 != 0 for bf16
+    model.close()
+
+
+# ------------------------------------------------------------------ the five named workloads
+def _run_named(gpu, oracle, name, plan, sample=None):
+    harness, rnn, W = gpu
+    wl = W.make_workload(W.CONFIGS[name])
+    _say("\n  workload %s plan %d" % (name, plan))
+    model = harness.DeviceModel(wl, plan=plan)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    import torch
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    if sample is None:
+        ref = oracle.forward_workload(wl, nthreads=16)
+        _check(harness, wl, io, ref)
+    else:
+        rows = np.asarray(sample)
+        ref = oracle.forward_workload(wl.take_batch(rows), nthreads=16)
+        _check(harness, wl, io, ref, rows=rows)
+    model.close()
+    return io
+
+
+@pytest.mark.parametrize("plan", [1, 2], ids=["cellwise", "wavefront"])
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_named_full(gpu, oracle, name, plan):
+    _run_named(gpu, oracle, name, plan)
+
+
+@pytest.mark.parametrize("plan", [1, 2], ids=["cellwise", "wavefront"])
+def test_C4_sampled_sequences(gpu, oracle, plan):
+    """Full-size C4 on the GPU; the oracle recomputes 6 of the 64 sequences (sequences are
+    independent), including the shortest and the longest."""
+    harness, rnn, W = gpu
+    wl = W.make_workload(W.CONFIGS["C4"])
+    rows = sorted({int(np.argmin(wl.lengths)), int(np.argmax(wl.lengths)), 0, 17, 40, 63})
+    _run_named(gpu, oracle, "C4", plan, sample=rows)
+
+
+def test_C5_sampled_sequences(gpu, oracle):
+    """Full-size C5 (the throughput workload, in the launch configuration the benchmark times);
+    the oracle recomputes 3 of the 256 sequences through all 8 layers and 512 steps."""
+    _run_named(gpu, oracle, "C5", 0, sample=[0, 131, 255])

@@ -461,3 +461,17 @@ def test_rejects_bad_lengths(oracle):
     for bad in ([0, 1], [4, 1]):
         with pytest.raises(ValueError):
             oracle.forward(LSTM, 1, 1, 1, 1, ws, x, lengths=np.array(bad, dtype=np.int32))
+
+
+def test_projection_is_a_matrix_product(oracle):
+    rng = np.random.default_rng(16)
+    a = rng.standard_normal((7, 5))
+    w = rng.standard_normal((6, 5))
+    np.testing.assert_allclose(oracle.projection(a, w), a @ w.T, rtol=0, atol=1e-14)
+    # the projection plus the recurrent part is what the cell sees: a one-step LSTM from zero
+    # state with o, i saturated open and f closed gives h = tanh(tanh(P_g))
+    H, I = 3, 5
+    wi = np.zeros((4 * H, I)); wi[2 * H:3 * H] = w[:H]
+    bi = np.zeros(4 * H); bi[:H] = 40; bi[H:2 * H] = -40; bi[3 * H:] = 40
+    y, _, _ = oracle.forward(LSTM, 1, 1, I, H, [wi, np.zeros((4 * H, H)), bi, None], a[:, None, :])
+    np.testing.assert_allclose(y[:, 0], np.tanh(np.tanh(oracle.projection(a, w[:H]))), atol=1e-14)
