@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the stacked-RNN forward pass on one MI355X.
+
+A "step" is one rnn_forward of the whole workload batch (projection of every layer plus the
+persistent recurrent kernel over all time steps), inputs resident in HBM.  The headline workload
+is C5 (8-layer LSTM, input = hidden = 1024, 512 steps, 256 sequences, bf16 with fp32 accumulation);
+the other named workloads are reported in the "workloads" field of the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--no-extra] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3        # MI355X fp32 vector
+LDS_BYTES_PER_CLK_CU = 128.0   # LDS read bandwidth used for the per-step bound
+CLOCK_GHZ = 2.4
+TICK_HZ = 100e6                # device wall clock used by the step ticks
+
+
+def log(msg: str) -> None:
+    sys.stderr.write(msg + "\n")
+    sys.stderr.flush()
+
+
+def algorithmic_flops(cfg):
+    """(projection flops per layer list, recurrent flops per layer) counting 2*M*K*N only."""
+    rows = cfg.T * cfg.B
+    proj = [2.0 * rows * cfg.layer_input(l) * cfg.D * cfg.G * cfg.H for l in range(cfg.L)]
+    rec = [2.0 * rows * cfg.H * cfg.D * cfg.G * cfg.H for _ in range(cfg.L)]
+    return proj, rec
+
+
+def time_workload(name: str, steps: int, warmup: int, per_call: int = 0, ticks: bool = False):
+    import torch
+    from paper_2307_11339_amd import harness, rnn, workloads as W
+
+    cfg = W.CONFIGS[name]
+    t0 = time.time()
+    wl = W.make_workload(cfg)
+    model = harness.DeviceModel(wl)
+    io = harness.DeviceIO(wl)
+    assert rnn.rnn_model_reserve(model.handle, cfg.T, cfg.B) == rnn.RNN_OK
+    log("[bench] %s: inputs generated and uploaded in %.1f s" % (name, time.time() - t0))
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        harness.forward(model, io, stream)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+
+    # timed region: exactly `steps` forwards, kernel events on the launch stream
+    rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_KERNELS)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(steps):
+        harness.forward(model, io, stream)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_start) * 1e3 / steps
+    _, proj_ms, proj_n = rnn.rnn_model_profile_read(model.handle, rnn.RNN_KERNEL_PROJECTION)
+    _, rec_ms, rec_n = rnn.rnn_model_profile_read(model.handle, rnn.RNN_KERNEL_RECURRENT)
+    rnn.rnn_model_set_profiling(model.handle, 0)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+
+    out = {
+        "ms_per_step": ms_per_step,
+        "seq_per_s": cfg.B / (ms_per_step * 1e-3),
+        "projection": {"launches_per_step": proj_n / steps, "avg_ms": proj_ms / max(proj_n, 1)},
+        "recurrent": {"launches_per_step": rec_n / steps, "avg_ms": rec_ms / max(rec_n, 1)},
+        "device_bytes": rnn.rnn_model_device_bytes(model.handle),
+    }
+    if per_call > 0:  # per-call latency distribution, each call waited for
+        lat = []
+        for _ in range(per_call):
+            a = time.perf_counter()
+            harness.forward(model, io, stream)
+            torch.cuda.synchronize()
+            lat.append((time.perf_counter() - a) * 1e3)
+        lat.sort()
+        out["p50_ms"] = statistics.median(lat)
+        out["p90_ms"] = lat[int(0.9 * (len(lat) - 1))]
+    if ticks:
+        import numpy as np
+        rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_STEP_TICKS)
+        harness.forward(model, io, stream)
+        torch.cuda.synchronize()
+        n = cfg.L * cfg.D * cfg.T
+        rc, tk = rnn.rnn_model_read_step_ticks(model.handle, n)
+        rnn.rnn_model_set_profiling(model.handle, 0)
+        if rc == rnn.RNN_OK and tk.min() > 0:
+            tk = tk.reshape(cfg.L * cfg.D, cfg.T).astype(np.int64)
+            d = np.diff(tk[-1]) / TICK_HZ * 1e6           # top layer: steady-state wavefront
+            out["step_us_p50"] = float(np.median(d))
+            out["grid_us"] = float((tk.max() - tk.min()) / TICK_HZ * 1e6)
+    model.close()
+    return cfg, out
+
+
+def cpu_baseline(name: str, n_seq: int):
+    """The oracle as it stands, timed on the host cores for a bounded sample of the workload."""
+    import numpy as np
+    from oracle import rnn_oracle
+    from paper_2307_11339_amd import workloads as W
+
+    cfg = W.CONFIGS[name]
+    wl = W.make_workload(cfg)
+    rows = np.linspace(0, cfg.B - 1, num=min(n_seq, cfg.B)).astype(int)
+    sub = wl.take_batch(rows)
+    threads = min(16, os.cpu_count() or 1)
+    rnn_oracle.build()
+    t0 = time.perf_counter()
+    rnn_oracle.forward_workload(sub, nthreads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "sequences/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of the %d sequences of %s through all %d layers and %d steps, fp64, %.1f s"
+                      % (len(rows), cfg.B, name, cfg.L, cfg.T, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C5")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this library runs on one GPU; --gpus %d is not supported "
+                         "(batch sharding across GPUs needs no kernel change, see DESIGN.md)\n" % args.gpus)
+        return 2
+
+    import torch
+    from paper_2307_11339_amd import rnn
+    rnn.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    cfg, main_res = time_workload(args.workload, args.steps, args.warmup)
+    proj_flops, rec_flops = algorithmic_flops(cfg)
+    # dominant kernel = the class with the larger share of the step
+    proj_total = main_res["projection"]["avg_ms"] * main_res["projection"]["launches_per_step"]
+    rec_total = main_res["recurrent"]["avg_ms"] * main_res["recurrent"]["launches_per_step"]
+    bf16 = cfg.dtype == 1
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_TFLOPS
+
+    def tflops(flops_per_step, kern):
+        n = max(kern["launches_per_step"], 1e-9)
+        return (flops_per_step / n) / (kern["avg_ms"] * 1e-3) / 1e12 if kern["avg_ms"] > 0 else 0.0
+
+    proj_tf = tflops(sum(proj_flops), main_res["projection"])
+    rec_tf = tflops(sum(rec_flops), main_res["recurrent"])
+    dominant = "recurrent" if rec_total >= proj_total else "projection"
+    ach = rec_tf if dominant == "recurrent" else proj_tf
+    roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(ach / peak, 4), "traffic": None, "kernel": dominant,
+                "avg_ms": round(main_res[dominant]["avg_ms"], 4)}
+
+    line = {
+        "metric": "RNN forward sequences/sec",
+        "value": round(main_res["seq_per_s"], 2),
+        "unit": "sequences/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d-layer %s %s, input %d, hidden %d, seq len %d, batch %d"
+                               % (cfg.name, cfg.L, "bidirectional" if cfg.D == 2 else "unidirectional",
+                                  "LSTM" if cfg.cell == 0 else "GRU", cfg.I, cfg.H, cfg.T, cfg.B)},
+        "roofline": roofline,
+        "kernels": {
+            "projection": {"avg_ms": round(main_res["projection"]["avg_ms"], 4),
+                           "launches_per_step": main_res["projection"]["launches_per_step"],
+                           "tflops": round(proj_tf, 2), "frac_of_mfma_peak": round(proj_tf / peak, 4)},
+            "recurrent": {"avg_ms": round(main_res["recurrent"]["avg_ms"], 4),
+                          "launches_per_step": main_res["recurrent"]["launches_per_step"],
+                          "tflops": round(rec_tf, 2), "frac_of_mfma_peak": round(rec_tf / peak, 4)},
+        },
+        "device_bytes": main_res["device_bytes"],
+    }
+
+    if not args.no_extra:
+        extra = {}
+        for name in ("C1", "C2", "C3", "C4"):
+            if name == args.workload:
+                continue
+            c, r = time_workload(name, steps=50, warmup=5, per_call=50, ticks=True)
+            e = {"seq_per_s": round(r["seq_per_s"], 1), "ms_per_call": round(r["ms_per_step"], 4),
+                 "p50_ms": round(r["p50_ms"], 4), "p90_ms": round(r["p90_ms"], 4),
+                 "recurrent_avg_ms": round(r["recurrent"]["avg_ms"], 4),
+                 "projection_avg_ms": round(r["projection"]["avg_ms"], 4)}
+            if "step_us_p50" in r:
+                e["step_us_p50"] = round(r["step_us_p50"], 3)
+                e["grid_us"] = round(r["grid_us"], 1)
+            if name == "C3":
+                # W_hh slice of one workgroup (64 gate rows x 1024 x 2 B) read once per step from LDS
+                bound_us = (64 * 1024 * 2) / (LDS_BYTES_PER_CLK_CU * CLOCK_GHZ * 1e9) * 1e6
+                e["lds_bound_us_per_step"] = round(bound_us, 3)
+                if "step_us_p50" in e:
+                    e["step_over_lds_bound"] = round(e["step_us_p50"] / bound_us, 2)
+            extra[name] = e
+        line["workloads"] = extra
+
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=2)
+
+    print(json.dumps(line))
+    sys.stdout.flush()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -131,6 +131,29 @@ int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const f
 int rnn_input_projection(rnn_model* model, int layer, const void* in, float* gx, int rows,
                          void* stream);
 
+/* Kernel classes for profiling. */
+enum rnn_kernel { RNN_KERNEL_PROJECTION = 0, RNN_KERNEL_RECURRENT = 1 };
+enum rnn_profile_flags { RNN_PROFILE_KERNELS = 1, RNN_PROFILE_STEP_TICKS = 2 };
+
+/* Measurement aids for the two kernels that dominate the forward pass (projection over all
+ * time steps; persistent recurrent kernel), the quantities the paper's profiler collects per
+ * operator (Section 4.1, "profile the model to get the operator execution time").
+ *   flags & RNN_PROFILE_KERNELS     later forwards bracket every projection and every persistent
+ *                                   launch with HIP events on the caller's stream;
+ *   flags & RNN_PROFILE_STEP_TICKS  the persistent kernel stores the device wall clock (100 MHz)
+ *                                   at which each (layer, direction, step) was published.
+ * Calling it (with any flags, 0 = off) also discards the events recorded so far. */
+int rnn_model_set_profiling(rnn_model* model, int flags);
+
+/* After the caller has synchronised the stream: total milliseconds and number of launches of
+ * kernel class `kind` (rnn_kernel) recorded since the last rnn_model_set_profiling.  Host pointers. */
+int rnn_model_profile_read(rnn_model* model, int kind, double* total_ms, long long* launches);
+
+/* After the caller has synchronised the stream: copy the step clocks of the last persistent
+ * forward to host memory, `count` = L*D*T values in order (layer, direction, step s); the
+ * backward direction's step s is time T-1-s. */
+int rnn_model_read_step_ticks(rnn_model* model, uint64_t* ticks, size_t count);
+
 /* After the stream has been synchronised: RNN_OK, or RNN_EDEVICE if a workgroup of the last
  * persistent forward gave up waiting for a step flag (its outputs are then undefined). */
 int rnn_model_check(rnn_model* model);

@@ -45,6 +45,12 @@ struct rnn_model {
     size_t workspace_bytes = 0;
     bool want_ticks = false;
 
+    // optional profiling: HIP events around the kernels of each class
+    bool profiling = false;
+    struct ProfSlot { hipEvent_t a, b; int kind; };
+    std::vector<ProfSlot> prof;      // event pairs, created once and reused
+    size_t prof_used = 0;
+
     int layer_input(int l) const { return l == 0 ? I : D * H; }
 };
 
@@ -169,6 +175,28 @@ float elem_to_f32(const void* base, size_t i, int dtype) {
     return ((const float*)base)[i];
 }
 
+constexpr size_t PROF_MAX_SLOTS = 1 << 14;
+
+// Record the start of a profiled launch; returns the slot index or -1 when profiling is off.
+int prof_begin(rnn_model* m, int kind, hipStream_t st) {
+    if (!m->profiling || m->prof_used >= PROF_MAX_SLOTS) return -1;
+    if (m->prof_used == m->prof.size()) {
+        rnn_model::ProfSlot s;
+        if (hipEventCreate(&s.a) != hipSuccess) { (void)hipGetLastError(); return -1; }
+        if (hipEventCreate(&s.b) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(s.a); return -1; }
+        s.kind = kind;
+        m->prof.push_back(s);
+    }
+    const int i = (int)m->prof_used++;
+    m->prof[i].kind = kind;
+    (void)hipEventRecord(m->prof[i].a, st);
+    return i;
+}
+
+void prof_end(rnn_model* m, int slot, hipStream_t st) {
+    if (slot >= 0) (void)hipEventRecord(m->prof[slot].b, st);
+}
+
 #define HIP_TRY(expr)                       \
     do {                                    \
         if ((expr) != hipSuccess) {         \
@@ -189,8 +217,10 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
         const void* in = (l == 0) ? x : m->ybuf[l - 1].p;
         void* out = (l == m->L - 1) ? y : m->ybuf[l].p;
         const int K = m->layer_input(l);
+        const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l].p, K, (float*)m->gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
+        prof_end(m, ps, st);
         for (int s = 0; s < T; ++s) {
             for (int d = 0; d < m->D; ++d) {
                 const int g = l * m->D + d;
@@ -222,8 +252,10 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
         const int K = m->layer_input(l0);
+        int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
+        prof_end(m, ps, st);
         const size_t nflags = (size_t)LP * m->D * plan.ncb * T;
         HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, B, m->H, m->ring.p,
                                       (unsigned*)m->flags.p, nflags, st));
@@ -248,7 +280,9 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         a.status = (unsigned*)m->status.p;
         a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
         a.spin_limit = 1u << 22;
+        ps = prof_begin(m, RNN_KERNEL_RECURRENT, st);
         HIP_TRY(launch_wavefront(a, st));
+        prof_end(m, ps, st);
     }
     return RNN_OK;
 }
@@ -373,7 +407,6 @@ int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, 
         rnn_model_destroy(m);
         return rc;
     }
-    m->want_ticks = getenv("RNN_DEBUG_TICKS") != nullptr;
     *out = m;
     return RNN_OK;
 }
@@ -385,6 +418,7 @@ void rnn_model_destroy(rnn_model* m) {
     for (auto& b : m->whh) dev_free(b);
     for (auto& b : m->bias) dev_free(b);
     dev_free(m->status);
+    for (auto& e : m->prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     delete m;
 }
 
@@ -431,6 +465,39 @@ int rnn_input_projection(rnn_model* m, int layer, const void* in, float* gx, int
     const int N = m->D * SLOTS * m->H;
     HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[layer].p, K, gx, N, rows, N, K,
                            (hipStream_t)stream));
+    return RNN_OK;
+}
+
+int rnn_model_set_profiling(rnn_model* m, int flags) {
+    if (!m || flags < 0 || flags > 3) return RNN_EINVAL;
+    m->profiling = (flags & RNN_PROFILE_KERNELS) != 0;
+    m->want_ticks = (flags & RNN_PROFILE_STEP_TICKS) != 0;
+    m->prof_used = 0;
+    return RNN_OK;
+}
+
+int rnn_model_profile_read(rnn_model* m, int kind, double* total_ms, long long* launches) {
+    if (!m || !total_ms || !launches) return RNN_EINVAL;
+    if (kind != RNN_KERNEL_PROJECTION && kind != RNN_KERNEL_RECURRENT) return RNN_EINVAL;
+    double sum = 0.0;
+    long long n = 0;
+    for (size_t i = 0; i < m->prof_used; ++i) {
+        if (m->prof[i].kind != kind) continue;
+        float ms = 0.0f;
+        HIP_TRY(hipEventSynchronize(m->prof[i].b));
+        HIP_TRY(hipEventElapsedTime(&ms, m->prof[i].a, m->prof[i].b));
+        sum += ms;
+        ++n;
+    }
+    *total_ms = sum;
+    *launches = n;
+    return RNN_OK;
+}
+
+int rnn_model_read_step_ticks(rnn_model* m, uint64_t* ticks, size_t count) {
+    if (!m || !ticks) return RNN_EINVAL;
+    if (!m->ticks.p || count * sizeof(uint64_t) > m->ticks.bytes) return RNN_EINVAL;
+    HIP_TRY(hipMemcpy(ticks, m->ticks.p, count * sizeof(uint64_t), hipMemcpyDeviceToHost));
     return RNN_OK;
 }
 

@@ -15,11 +15,15 @@
 // vector straight from global memory; partial sums meet in LDS, then every (unit, sequence)
 // pair is finished by one fixed lane that keeps c and h of that pair in registers.
 //
-// Steps are published through one counter per (layer, direction, column block, step):
-// a workgroup that has written its part of h_t adds 1 (after a device-scope release); readers
-// poll until the counter equals the number of row blocks, then acquire.  Every wait is bounded:
-// a wave that exhausts its poll budget raises the status word and stops waiting, so the grid
-// always drains.
+// Steps are published through one counter per (layer, direction, column block, step): a
+// workgroup that has written its part of h_t adds 1; readers poll until the counter equals the
+// number of row blocks.  Everything that one workgroup writes and another reads during the
+// launch (h of the current step, layer outputs, counters) is accessed with device-scope
+// accesses that bypass the per-XCD caches, and a writer waits for its stores to be acknowledged
+// before the counter is bumped; no bulk cache write-back or invalidate is needed, which matters
+// because those cost tens of microseconds per step when every wave issues them.  Every wait is
+// bounded: a wave that exhausts its poll budget raises the status word and stops waiting, so
+// the grid always drains.
 #include "common.h"
 #include "kernels.h"
 
@@ -30,6 +34,20 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
+// Device-scope (cross-XCD coherent) accesses for data exchanged between workgroups in flight.
+__device__ inline uint64_t ld_dev_u64(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline uint32_t ld_dev_u32(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_dev_u64(void* p, uint64_t v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_dev_u32(void* p, uint32_t v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 struct TraitsBf16 {
     typedef bf16_t elem;
     typedef bf16x8 frag;
@@ -37,8 +55,33 @@ struct TraitsBf16 {
     // lane -> first K element of its fragment inside a KW block
     static __device__ inline int koff(int lane) { return 8 * (lane >> 4); }
     static __device__ inline frag load(const elem* p) { return *reinterpret_cast<const frag*>(p); }
+    static __device__ inline frag load_dev(const elem* p) {
+        union { uint64_t u[2]; frag f; } v;
+        v.u[0] = ld_dev_u64(p);
+        v.u[1] = ld_dev_u64(p + 4);
+        return v.f;
+    }
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
+    // n+48 (same sequence n) as two 8-byte device-scope stores issued by lane n.
+    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                          elem* out_dst) {
+        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
+        const int n = lane & 15;
+        const uint32_t v0 = (uint32_t)__shfl(mine, n);
+        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
+        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
+        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
+        if (valid && lane < 16) {
+            const uint64_t st = (uint64_t)(v0 & 0xFFFFu) | ((uint64_t)(v1 & 0xFFFFu) << 16) |
+                                ((uint64_t)(v2 & 0xFFFFu) << 32) | ((uint64_t)(v3 & 0xFFFFu) << 48);
+            const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
+                                ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
+            st_dev_u64(state_dst, st);
+            st_dev_u64(out_dst, ov);
+        }
     }
     static __device__ inline elem store_val(float h, float& kept) {
         const bf16_t b = f32_to_bf16(h);
@@ -54,8 +97,17 @@ struct TraitsF32 {
     static constexpr int KW = 4;
     static __device__ inline int koff(int lane) { return lane >> 4; }
     static __device__ inline frag load(const elem* p) { return *p; }
+    static __device__ inline frag load_dev(const elem* p) { return __uint_as_float(ld_dev_u32(p)); }
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    // every lane stores its own unit; state_dst / out_dst point at unit 4*(tile row) of sequence n
+    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                          elem* out_dst) {
+        if (valid) {
+            st_dev_u32(state_dst + (lane >> 4), __float_as_uint(state));
+            st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
+        }
     }
     static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
     static __device__ inline elem zero() { return 0.0f; }
@@ -81,8 +133,45 @@ __device__ inline bool wait_flag(unsigned* flag, unsigned target, unsigned* stat
         }
         __builtin_amdgcn_s_sleep(1);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // later loads must not be hoisted above the poll; they are device-scope loads themselves, so
+    // no cache invalidate is needed
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     return true;
+}
+
+// acc[rt][ct] += W[rt][:] (resident fragments) x activations.  src[ct] points at this lane's
+// first K element of sequence column ct; fragment kb lies kb*KW elements further.  The loads of
+// one chunk are issued back to back and the next chunk is requested before the MFMAs of the
+// current one, so a step pays one memory round trip here, not one per fragment.
+template <class TR, int RT, int CT, int KB>
+__device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
+                                const typename TR::elem* const (&src)[CT], f32x4 (&acc)[RT][CT]) {
+    typedef typename TR::frag frag;
+    constexpr int KC = (CT >= 4 && KB > 4) ? 4 : KB;  // fragments per chunk and column tile
+    constexpr int NCH = KB / KC;
+    static_assert(KB % KC == 0, "chunking must divide KB");
+    frag buf[2][KC][CT];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) buf[0][kc][ct] = TR::load_dev(src[ct] + kc * TR::KW);
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        if (ch + 1 < NCH) {
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    buf[(ch + 1) & 1][kc][ct] = TR::load_dev(src[ct] + ((ch + 1) * KC + kc) * TR::KW);
+        }
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[rt][ct] = TR::mfma(wreg[rt][ch * KC + kc], buf[ch & 1][kc][ct], acc[rt][ct]);
+    }
 }
 
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
@@ -116,10 +205,11 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
 
     // ---- resident weights: A operand fragments ---------------------------------------------
     frag wh[RT][KB];
-    frag wx[FUSED ? RT : 1][FUSED ? KB : 1];
+    frag wx[RT][KB];  // only live when FUSED
     {
         const elem* whh = static_cast<const elem*>(p.whh[g]);
-        const elem* wih = static_cast<const elem*>(p.wih[g]);
+        // a layer without a fused projection never uses wx; it loads W_hh again to stay branch-free
+        const elem* wih = fused ? static_cast<const elem*>(p.wih[g]) : whh;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
@@ -127,10 +217,7 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
             for (int kb = 0; kb < KB; ++kb) {
                 const int k = w * kq + kb * KW + TR::koff(lane);
                 wh[rt][kb] = TR::load(whh + row * H + k);
-                if (FUSED) {
-                    if (fused) wx[rt][kb] = TR::load(wih + row * H + k);
-                    else wx[rt][kb] = wh[rt][kb];
-                }
+                if (FUSED) wx[rt][kb] = TR::load(wih + row * H + k);
             }
         }
     }
@@ -200,36 +287,20 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
         if (FUSED) {
             if (fused) {  // x_t = h_t of the layer below
                 wait_flag(below_flags + s, target, p.status, p.spin_limit, aborted);
+                const elem* src[CT];
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) {
-                    frag xb[CT];
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct)
-                        xb[ct] = TR::load(below + ((size_t)t * B + bcol[ct]) * H + kbase + kb * KW);
-#pragma unroll
-                    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                        for (int ct = 0; ct < CT; ++ct)
-                            acc[rt][ct] = TR::mfma(wx[rt][kb], xb[ct], acc[rt][ct]);
-                }
+                for (int ct = 0; ct < CT; ++ct) src[ct] = below + ((size_t)t * B + bcol[ct]) * H + kbase;
+                mma_part<TR, RT, CT, KB>(wx, src, acc);
             }
         }
 
         if (s > 0) wait_flag(my_flags + (s - 1), target, p.status, p.spin_limit, aborted);
         {
             const elem* hprev = ring + (size_t)((s + 1) & 1) * B * H;  // slot of step s-1
+            const elem* src[CT];
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                frag hb[CT];
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    hb[ct] = TR::load(hprev + (size_t)bcol[ct] * H + kbase + kb * KW);
-#pragma unroll
-                for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct)
-                        acc[rt][ct] = TR::mfma(wh[rt][kb], hb[ct], acc[rt][ct]);
-            }
+            for (int ct = 0; ct < CT; ++ct) src[ct] = hprev + (size_t)bcol[ct] * H + kbase;
+            mma_part<TR, RT, CT, KB>(wh, src, acc);
         }
 
         // partial sums of the four K quarters meet in LDS
@@ -244,7 +315,8 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int j = w + 4 * o;
-            if (j < NTILE && col_reg[o] < B) {
+            if (j < NTILE) {  // uniform per wave
+                const bool valid = col_reg[o] < B;
                 f32x4 a = red[(0 * NTILE + j) * 64 + lane];
 #pragma unroll
                 for (int q = 1; q < 4; ++q) {
@@ -253,27 +325,33 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
                 }
                 a += gx_reg[o];
                 a += bias_reg[o];
-                const bool active = t < len_reg[o];
-                const size_t oidx = ((size_t)t * B + col_reg[o]) * out_ld + (size_t)d * H + unit_reg[o];
+                const bool active = valid && t < len_reg[o];
+                float c_new = c_reg[o];
+                const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
+                const float hn = cell_update<CELL>(pre, h_reg[o], c_new);
+                float kept = h_reg[o];
                 if (active) {
-                    const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
-                    const float hn = cell_update<CELL>(pre, h_reg[o], c_reg[o]);
-                    const elem hv = TR::store_val(hn, h_reg[o]);
-                    out[oidx] = hv;
-                    hcur[(size_t)col_reg[o] * H + unit_reg[o]] = hv;
-                } else {
-                    float kept;
-                    out[oidx] = TR::zero();
-                    hcur[(size_t)col_reg[o] * H + unit_reg[o]] = TR::store_val(h_reg[o], kept);
+                    c_reg[o] = c_new;
+                    (void)TR::store_val(hn, kept);
+                    h_reg[o] = kept;
                 }
+                float unused;
+                const elem state_v = TR::store_val(h_reg[o], unused);   // held value when inactive
+                const elem out_v = active ? state_v : TR::zero();
+                // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
+                const int unit0 = unit_reg[o] - (lane >> 4);
+                const int colc = valid ? col_reg[o] : 0;
+                TR::publish(state_v, out_v, valid, lane, hcur + (size_t)colc * H + unit0,
+                            out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
             }
         }
 
-        // publish: every writer releases at device scope, then one thread bumps the counter
-        __threadfence();
+        // publish: wait until this wave's stores are acknowledged, meet the other waves, then one
+        // thread bumps the step counter
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-            __hip_atomic_fetch_add(my_flags + s, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(my_flags + s, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (p.ticks && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
         }
     }

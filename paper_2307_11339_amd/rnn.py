@@ -20,10 +20,13 @@ RNN_LSTM, RNN_GRU = 0, 1
 RNN_F32, RNN_BF16 = 0, 1
 RNN_OK, RNN_EINVAL, RNN_EUNSUPPORTED, RNN_ENOMEM, RNN_EDEVICE = 0, 1, 2, 3, 4
 RNN_PLAN_AUTO, RNN_PLAN_CELLWISE, RNN_PLAN_WAVEFRONT = 0, 1, 2
+RNN_KERNEL_PROJECTION, RNN_KERNEL_RECURRENT = 0, 1
+RNN_PROFILE_KERNELS, RNN_PROFILE_STEP_TICKS = 1, 2
 
 EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_model_reserve",
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
-           "rnn_status_string")
+           "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
+           "rnn_model_read_step_ticks")
 
 _lib = None
 
@@ -62,6 +65,12 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_device_bytes.argtypes = [vp]
     lib.rnn_status_string.restype = ctypes.c_char_p
     lib.rnn_status_string.argtypes = [ci]
+    lib.rnn_model_set_profiling.restype = ci
+    lib.rnn_model_set_profiling.argtypes = [vp, ci]
+    lib.rnn_model_profile_read.restype = ci
+    lib.rnn_model_profile_read.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_longlong)]
+    lib.rnn_model_read_step_ticks.restype = ci
+    lib.rnn_model_read_step_ticks.argtypes = [vp, vp, ctypes.c_size_t]
     _lib = lib
     return lib
 
@@ -129,3 +138,22 @@ def rnn_model_check(model: int) -> int:
 
 def rnn_model_device_bytes(model: int) -> int:
     return int(load_library().rnn_model_device_bytes(model))
+
+
+def rnn_model_set_profiling(model: int, flags: int) -> int:
+    return load_library().rnn_model_set_profiling(model, flags)
+
+
+def rnn_model_profile_read(model: int, kind: int):
+    """Returns (status, total_ms, launches)."""
+    ms = ctypes.c_double(0.0)
+    n = ctypes.c_longlong(0)
+    rc = load_library().rnn_model_profile_read(model, kind, ctypes.byref(ms), ctypes.byref(n))
+    return rc, ms.value, n.value
+
+
+def rnn_model_read_step_ticks(model: int, count: int):
+    """Returns (status, uint64 array of `count` device clock values)."""
+    out = np.zeros(count, dtype=np.uint64)
+    rc = load_library().rnn_model_read_step_ticks(model, out.ctypes.data, count)
+    return rc, out
