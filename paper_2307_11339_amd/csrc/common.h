@@ -34,10 +34,13 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
 
 __device__ inline float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
 
-__device__ inline float sigmoid_f(float a) { return __frcp_rn(1.0f + __expf(-a)); }
+// v_rcp_f32 and v_exp_f32 are accurate to about 1 ulp, far inside the parity tolerances
+__device__ inline float sigmoid_f(float a) { return __builtin_amdgcn_rcpf(1.0f + __expf(-a)); }
 
 // tanh(a) = 1 - 2 / (exp(2a) + 1); saturates cleanly to +-1 when exp overflows or underflows
-__device__ inline float tanh_f(float a) { return 1.0f - 2.0f * __frcp_rn(__expf(2.0f * a) + 1.0f); }
+__device__ inline float tanh_f(float a) {
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * a) + 1.0f);
+}
 
 // One cell update from the four slot pre-activations (bias already added).
 // Returns the new h (not yet rounded to the storage type); c is updated in place (LSTM only).

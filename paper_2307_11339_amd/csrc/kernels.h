@@ -51,23 +51,37 @@ struct WavefrontArgs {
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
     const float* gx;             // projection of layer l0: [T*B, D, H, 4]
     void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type
-    void* ring;                  // [LP*D, 2, B, H] storage type: h of the previous / current step
+    void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state
+                                 // after step s; every address is written once per launch
     const float* h0;             // [L*D, B, H] or NULL
     const float* c0;
     float* hT;                   // [L*D, B, H] or NULL
     float* cT;
     const int32_t* lengths;      // [B] or NULL
-    unsigned* flags;             // [LP*D, ncb, T] step counters, zero on entry
+    uint64_t* flagv;             // [LP*D, T, ncb, nrb] flag words {epoch, step}, never cleared
     unsigned* status;            // [1]: set to 1 if a workgroup gave up waiting
     unsigned long long* ticks;   // NULL, or [LP*D, T] device clock when a step was published
     unsigned spin_limit;         // polls before a wait is abandoned
+    uint64_t* lseq;              // tag-in-data kernel only: [LP*D, T+1, B, row_words] tagged words
+    uint32_t epoch;              // tag value of this launch (never 0), both kernels
 };
 // Returns hipErrorInvalidValue when no kernel variant exists for (dtype, RT, CT, H).
 hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream);
 // True when launch_wavefront has a variant for this combination.
 bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool fused);
-// Prepare ring slot 1 (the state "before step 0") from h0 and clear the step flags.
-hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int B, int H,
-                                 void* ring, unsigned* flags, size_t nflags, hipStream_t stream);
+// Workgroups per CU the variants with this CT are compiled for (1 or 2).
+int wavefront_variant_occupancy(int CT);
+// Write slot 0 of the state sequence (the state "before step 0") from h0.
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+                                 int H, void* hseq, hipStream_t stream);
+
+// ---- persistent wavefront kernel, tag-in-data variant for CT == 1 (wavefront_ll.hip) --------
+hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream);
+bool wavefront_ll_variant_exists(int dtype, int RT, int H);
+// Write slot 0 of the tagged state sequences (h0, tagged with `epoch`).
+hipError_t launch_wavefront_ll_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+                                    int H, uint64_t* lseq, uint32_t epoch, hipStream_t stream);
+// 8-byte words needed for `groups` (layer, direction) state sequences.
+size_t wavefront_ll_words(int dtype, int groups, int T, int B, int H);
 
 }  // namespace rnn

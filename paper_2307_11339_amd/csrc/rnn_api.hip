@@ -40,7 +40,9 @@ struct rnn_model {
 
     // workspace, sized for (T_res, B_res)
     int T_res = 0, B_res = 0;
-    DevBuf gx, ring, flags, status, h_f32, c_f32, h_st, gh, ticks;
+    DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
+    DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
+    uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
     std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
     size_t workspace_bytes = 0;
     bool want_ticks = false;
@@ -76,10 +78,11 @@ void dev_free(DevBuf& b) {
 }
 
 void free_workspace(rnn_model* m) {
-    dev_free(m->gx); dev_free(m->ring); dev_free(m->flags); dev_free(m->h_f32);
+    dev_free(m->gx); dev_free(m->hseq); dev_free(m->flags); dev_free(m->h_f32);
     dev_free(m->c_f32); dev_free(m->h_st); dev_free(m->gh); dev_free(m->ticks);
     for (auto& b : m->ybuf) dev_free(b);
     m->ybuf.clear();
+    dev_free(m->lseq);
     m->workspace_bytes = 0;
     m->T_res = m->B_res = 0;
 }
@@ -100,8 +103,11 @@ int alloc_workspace(rnn_model* m, int T, int B) {
     get(m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
     m->ybuf.resize(m->L > 1 ? m->L - 1 : 0);
     for (auto& b : m->ybuf) get(b, rows * m->D * m->H * m->esize);
-    get(m->ring, state * 2 * m->esize);
-    get(m->flags, (size_t)m->L * m->D * FLAG_COLBLOCKS_MAX * T * sizeof(unsigned));
+    get(m->hseq, state * (size_t)(T + 1) * m->esize);
+    // one flag word per (layer, direction, step, workgroup of that group); at most num_cus
+    // workgroups per launch
+    get(m->flags, (size_t)m->L * m->D * T * (size_t)(m->num_cus > 256 ? m->num_cus : 256) * sizeof(uint64_t));
+    if (rc == RNN_OK && hipMemset(m->flags.p, 0, m->flags.bytes) != hipSuccess) rc = RNN_EDEVICE;
     get(m->h_f32, state * sizeof(float));
     get(m->c_f32, state * sizeof(float));
     get(m->h_st, state * m->esize);
@@ -117,7 +123,7 @@ int alloc_workspace(rnn_model* m, int T, int B) {
 }
 
 // Choose how the grid of cells is laid over the compute units for batch size B.
-bool choose_wavefront(const rnn_model* m, int B, Plan& plan) {
+bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     if (m->H % 4 != 0) return false;
     const int row_tiles = m->H / 4;
     const int col_tiles = (B + 15) / 16;
@@ -130,9 +136,14 @@ bool choose_wavefront(const rnn_model* m, int B, Plan& plan) {
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
             const int RT = cand[c][0], CT = cand[c][1];
             if (row_tiles % RT) continue;
-            if (!wavefront_variant_exists(m->dtype, RT, CT, m->H, LP > 1)) continue;
+            const bool have = (CT == 1) ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
+                                        : wavefront_variant_exists(m->dtype, RT, CT, m->H, LP > 1);
+            if (!have) continue;
             const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
-            if (nrb * ncb > budget || ncb > FLAG_COLBLOCKS_MAX) continue;
+            // the tag-in-data kernel addresses two state sequences with 32-bit byte offsets
+            if (CT == 1 && wavefront_ll_words(m->dtype, 2, T, B, m->H) * 8 >= ((size_t)1 << 31)) continue;
+            const int occ = (CT == 1) ? 1 : wavefront_variant_occupancy(CT);
+            if (nrb * ncb > budget * occ || ncb > FLAG_COLBLOCKS_MAX) continue;
             const int cost = RT * CT;
             if (best < 0 || cost < best_cost || (cost == best_cost && RT > best_rt)) {
                 best = c; best_cost = cost; best_rt = RT;
@@ -151,12 +162,12 @@ bool choose_wavefront(const rnn_model* m, int B, Plan& plan) {
     return false;
 }
 
-int resolve_plan(const rnn_model* m, int B, Plan& plan) {
+int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
     if (m->requested_plan == RNN_PLAN_CELLWISE) {
         plan = Plan();
         return RNN_OK;
     }
-    if (choose_wavefront(m, B, plan)) return RNN_OK;
+    if (choose_wavefront(m, T, B, plan)) return RNN_OK;
     if (m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     plan = Plan();
     return RNN_OK;
@@ -244,6 +255,21 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
     return RNN_OK;
 }
 
+// Make sure the tagged state sequences hold `words` 8-byte words.  Fresh memory is cleared once:
+// tag 0 is never used by a launch.
+int ensure_lseq(rnn_model* m, size_t words) {
+    const size_t bytes = words * sizeof(uint64_t);
+    if (m->lseq.bytes >= bytes) return RNN_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    m->workspace_bytes -= m->lseq.bytes;
+    dev_free(m->lseq);
+    const int rc = dev_alloc(m->lseq, bytes);
+    if (rc != RNN_OK) return rc;
+    m->workspace_bytes += bytes;
+    HIP_TRY(hipMemset(m->lseq.p, 0, bytes));
+    return RNN_OK;
+}
+
 int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
                       const float* h0, const float* c0, void* y, float* hT, float* cT, int T,
                       int B, hipStream_t st) {
@@ -256,9 +282,18 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
         prof_end(m, ps, st);
-        const size_t nflags = (size_t)LP * m->D * plan.ncb * T;
-        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, B, m->H, m->ring.p,
-                                      (unsigned*)m->flags.p, nflags, st));
+        const bool tagged = plan.CT == 1;
+        if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
+            if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
+            HIP_TRY(hipMemsetAsync(m->flags.p, 0, m->flags.bytes, st));
+            m->epoch = 1;
+        }
+        if (tagged) {
+            HIP_TRY(launch_wavefront_ll_init(m->dtype, h0, l0, LP, m->D, T, B, m->H,
+                                             (uint64_t*)m->lseq.p, m->epoch, st));
+        } else {
+            HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, m->H, m->hseq.p, st));
+        }
         WavefrontArgs a;
         memset(&a, 0, sizeof(a));
         a.cell = m->cell; a.dtype = m->dtype;
@@ -274,14 +309,17 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
             a.out[ll] = (l == m->L - 1) ? y : m->ybuf[l].p;
         }
         a.gx = (const float*)m->gx.p;
-        a.ring = m->ring.p;
+        a.hseq = m->hseq.p;
         a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
-        a.flags = (unsigned*)m->flags.p;
+        a.flagv = (uint64_t*)m->flags.p;
         a.status = (unsigned*)m->status.p;
         a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
         a.spin_limit = 1u << 22;
+        a.lseq = (uint64_t*)m->lseq.p;
+        a.epoch = m->epoch;
         ps = prof_begin(m, RNN_KERNEL_RECURRENT, st);
-        HIP_TRY(launch_wavefront(a, st));
+        if (tagged) HIP_TRY(launch_wavefront_ll(a, st));
+        else HIP_TRY(launch_wavefront(a, st));
         prof_end(m, ps, st);
     }
     return RNN_OK;
@@ -428,7 +466,7 @@ int rnn_model_set_plan(rnn_model* m, int plan) {
         return RNN_EINVAL;
     if (plan == RNN_PLAN_WAVEFRONT) {
         Plan p;
-        if (!choose_wavefront(m, 1, p)) return RNN_EUNSUPPORTED;
+        if (!choose_wavefront(m, 1, 1, p)) return RNN_EUNSUPPORTED;
     }
     m->requested_plan = plan;
     return RNN_OK;
@@ -439,7 +477,12 @@ int rnn_model_reserve(rnn_model* m, int T, int B) {
     if (T <= m->T_res && B <= m->B_res) return RNN_OK;
     if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return RNN_EDEVICE; }
     const int Tn = T > m->T_res ? T : m->T_res, Bn = B > m->B_res ? B : m->B_res;
-    return alloc_workspace(m, Tn, Bn);
+    int rc = alloc_workspace(m, Tn, Bn);
+    if (rc != RNN_OK) return rc;
+    Plan plan;
+    if (resolve_plan(m, Tn, Bn, plan) == RNN_OK && plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1)
+        rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, Tn, Bn, m->H));
+    return rc;
 }
 
 int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
@@ -449,10 +492,14 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     int rc = rnn_model_reserve(m, T, B);
     if (rc != RNN_OK) return rc;
     Plan plan;
-    rc = resolve_plan(m, B, plan);
+    rc = resolve_plan(m, T, B, plan);
     if (rc != RNN_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
+    if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1) {
+        rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H));
+        if (rc != RNN_OK) return rc;
+    }
     if (plan.kind == RNN_PLAN_WAVEFRONT)
         return forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
     return forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);

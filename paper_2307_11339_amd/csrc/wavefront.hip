@@ -15,126 +15,60 @@
 // vector straight from global memory; partial sums meet in LDS, then every (unit, sequence)
 // pair is finished by one fixed lane that keeps c and h of that pair in registers.
 //
-// Steps are published through one counter per (layer, direction, column block, step): a
-// workgroup that has written its part of h_t adds 1; readers poll until the counter equals the
-// number of row blocks.  Everything that one workgroup writes and another reads during the
-// launch (h of the current step, layer outputs, counters) is accessed with device-scope
-// accesses that bypass the per-XCD caches, and a writer waits for its stores to be acknowledged
-// before the counter is bumped; no bulk cache write-back or invalidate is needed, which matters
-// because those cost tens of microseconds per step when every wave issues them.  Every wait is
-// bounded: a wave that exhausts its poll budget raises the status word and stops waiting, so
-// the grid always drains.
-#include "common.h"
-#include "kernels.h"
+// Steps are published through a vector of flag words per (layer, direction, column block, step),
+// one 8-byte word per row block: a workgroup that has written its part of h_t stores
+// {launch epoch, step} into its own word; a reader loads the whole vector with one instruction
+// (one lane per row block) and polls until every word carries this launch's epoch.  (A shared
+// counter bumped with atomic adds serialises the row blocks on one address and was measured at
+// more than twice the cost.)  The epoch changes with every launch, so flags are never cleared.
+// No bulk cache write-back or invalidate is used (every wave issuing one per step costs tens of
+// microseconds).  Instead:
+//   - everything a workgroup writes for others (h_t, layer outputs) goes out with device-scope
+//     write-through stores, and the writer waits for their acknowledgement before its flag word
+//     is stored;
+//   - every exchanged address is written exactly once per launch (the state of step s has its
+//     own slot, layer outputs are indexed by t) and is read only after its flag vector is
+//     complete, and a cache line never spans two sequences.  A reader's caches therefore cannot
+//     hold a stale copy, so activations are read with ordinary cached loads and the workgroups
+//     of one XCD share them through that XCD's L2.
+// Every wait is bounded: a wave that exhausts its poll budget raises the status word and stops
+// waiting, so the grid always drains.
+#include "wf_traits.h"
 
 namespace rnn {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-
 namespace {
 
-// Device-scope (cross-XCD coherent) accesses for data exchanged between workgroups in flight.
-__device__ inline uint64_t ld_dev_u64(const void* p) {
-    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline uint32_t ld_dev_u32(const void* p) {
-    return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline void st_dev_u64(void* p, uint64_t v) {
-    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline void st_dev_u32(void* p, uint32_t v) {
-    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-struct TraitsBf16 {
-    typedef bf16_t elem;
-    typedef bf16x8 frag;
-    static constexpr int KW = 32;  // K elements consumed by one MFMA
-    // lane -> first K element of its fragment inside a KW block
-    static __device__ inline int koff(int lane) { return 8 * (lane >> 4); }
-    static __device__ inline frag load(const elem* p) { return *reinterpret_cast<const frag*>(p); }
-    static __device__ inline frag load_dev(const elem* p) {
-        union { uint64_t u[2]; frag f; } v;
-        v.u[0] = ld_dev_u64(p);
-        v.u[1] = ld_dev_u64(p + 4);
-        return v.f;
-    }
-    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-    }
-    // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
-    // n+48 (same sequence n) as two 8-byte device-scope stores issued by lane n.
-    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
-                                          elem* out_dst) {
-        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
-        const int n = lane & 15;
-        const uint32_t v0 = (uint32_t)__shfl(mine, n);
-        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
-        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
-        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
-        if (valid && lane < 16) {
-            const uint64_t st = (uint64_t)(v0 & 0xFFFFu) | ((uint64_t)(v1 & 0xFFFFu) << 16) |
-                                ((uint64_t)(v2 & 0xFFFFu) << 32) | ((uint64_t)(v3 & 0xFFFFu) << 48);
-            const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
-                                ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
-            st_dev_u64(state_dst, st);
-            st_dev_u64(out_dst, ov);
-        }
-    }
-    static __device__ inline elem store_val(float h, float& kept) {
-        const bf16_t b = f32_to_bf16(h);
-        kept = bf16_to_f32(b);
-        return b;
-    }
-    static __device__ inline elem zero() { return 0; }
-};
-
-struct TraitsF32 {
-    typedef float elem;
-    typedef float frag;
-    static constexpr int KW = 4;
-    static __device__ inline int koff(int lane) { return lane >> 4; }
-    static __device__ inline frag load(const elem* p) { return *p; }
-    static __device__ inline frag load_dev(const elem* p) { return __uint_as_float(ld_dev_u32(p)); }
-    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
-        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-    }
-    // every lane stores its own unit; state_dst / out_dst point at unit 4*(tile row) of sequence n
-    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
-                                          elem* out_dst) {
-        if (valid) {
-            st_dev_u32(state_dst + (lane >> 4), __float_as_uint(state));
-            st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
-        }
-    }
-    static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
-    static __device__ inline elem zero() { return 0.0f; }
-};
-
-// Wait until *flag >= target.  Lane 0 polls; the verdict is shared through a scalar register.
-// Returns false when the wait was abandoned (budget exhausted or another workgroup gave up).
-__device__ inline bool wait_flag(unsigned* flag, unsigned target, unsigned* status,
-                                 unsigned spin_limit, bool& aborted) {
+// Wait until all `nrb` flag words at `row` carry `epoch` (nrb <= 256: up to four words per lane,
+// loaded together).  Returns false when the wait was abandoned (poll budget exhausted, or another
+// workgroup gave up).
+__device__ inline bool wait_flags(const uint64_t* row, int nrb, int lane, uint32_t epoch,
+                                  unsigned* status, unsigned spin_limit, bool& aborted) {
     if (aborted) return false;
     unsigned spins = 0;
+    const int i0 = min(lane, nrb - 1), i1 = min(lane + 64, nrb - 1), i2 = min(lane + 128, nrb - 1),
+              i3 = min(lane + 192, nrb - 1);
     for (;;) {
-        const unsigned v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v >= target) break;
-        ++spins;
-        if ((spins & 1023u) == 0u) {
-            const unsigned st = __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool ok;
+        if (nrb <= 64) {
+            ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
+        } else {
+            const uint64_t a = ld_dev_u64(row + i0), b = ld_dev_u64(row + i1), c = ld_dev_u64(row + i2),
+                           d = ld_dev_u64(row + i3);
+            ok = (uint32_t)(a >> 32) == epoch && (uint32_t)(b >> 32) == epoch &&
+                 (uint32_t)(c >> 32) == epoch && (uint32_t)(d >> 32) == epoch;
+        }
+        if (__all(ok)) break;
+        if ((++spins & 1023u) == 0u) {
+            const unsigned st = ld_dev_u32(status);
             if (st != 0u || spins >= spin_limit) {
-                __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                st_dev_u32(status, 1u);
                 aborted = true;
                 return false;
             }
         }
-        __builtin_amdgcn_s_sleep(1);
     }
-    // later loads must not be hoisted above the poll; they are device-scope loads themselves, so
-    // no cache invalidate is needed
+    // later loads must not be hoisted above the poll
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     return true;
 }
@@ -143,18 +77,23 @@ __device__ inline bool wait_flag(unsigned* flag, unsigned target, unsigned* stat
 // first K element of sequence column ct; fragment kb lies kb*KW elements further.  The loads of
 // one chunk are issued back to back and the next chunk is requested before the MFMAs of the
 // current one, so a step pays one memory round trip here, not one per fragment.
+// Register slot kb holds K block (kb + rot) mod KB: workgroups that read the same activations
+// at the same moment start at different K blocks, which spreads them over the L2 channels.
 template <class TR, int RT, int CT, int KB>
 __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
-                                const typename TR::elem* const (&src)[CT], f32x4 (&acc)[RT][CT]) {
+                                const typename TR::elem* const (&src)[CT], f32x4 (&acc)[RT][CT],
+                                int rot) {
     typedef typename TR::frag frag;
     constexpr int KC = (CT >= 4 && KB > 4) ? 4 : KB;  // fragments per chunk and column tile
     constexpr int NCH = KB / KC;
     static_assert(KB % KC == 0, "chunking must divide KB");
+    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
     frag buf[2][KC][CT];
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) buf[0][kc][ct] = TR::load_dev(src[ct] + kc * TR::KW);
+        for (int ct = 0; ct < CT; ++ct)
+            buf[0][kc][ct] = TR::load(src[ct] + ((kc + rot) & (KB - 1)) * TR::KW);
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         if (ch + 1 < NCH) {
@@ -162,7 +101,8 @@ __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
             for (int kc = 0; kc < KC; ++kc)
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
-                    buf[(ch + 1) & 1][kc][ct] = TR::load_dev(src[ct] + ((ch + 1) * KC + kc) * TR::KW);
+                    buf[(ch + 1) & 1][kc][ct] =
+                        TR::load(src[ct] + (((ch + 1) * KC + kc + rot) & (KB - 1)) * TR::KW);
         }
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc)
@@ -174,8 +114,13 @@ __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
     }
 }
 
+// Workgroups per CU a variant is compiled for.  (Two workgroups per CU with tiles of 32
+// sequences were measured slower than one with 64: the step is bound by synchronisation and by
+// L2 traffic, and doubling the number of workgroups raises both.)
+constexpr int variant_occupancy(int /*CT*/) { return 1; }
+
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
-__global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
+__global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
     constexpr int KW = TR::KW;
@@ -188,10 +133,7 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
     const int lane = tid & 63;
     const int w = tid >> 6;
 
-    // Workgroups are handed to the 8 XCDs round-robin; renumber them so that the workgroups of
-    // one (layer, direction, column block) chain sit on as few XCDs as possible.
-    int v = blockIdx.x;
-    if ((gridDim.x & 7) == 0) v = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int v = xcd_contiguous_id();
     const int wpg = p.nrb * p.ncb;
     const int g = v / wpg;                          // local (layer, direction) index
     if (g >= p.LP * p.D) return;
@@ -202,6 +144,10 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
     const bool fused = FUSED && ll > 0;
     const int H = p.H, B = p.B, T = p.T;
     const int kq = H / 4;                           // K range of one wave inside each part
+
+    // per-workgroup rotation of the K blocks and of the column tiles (see mma_part)
+    const int rot_k = rb & (KB - 1);
+    const int rot_c = (rb / KB) % CT;
 
     // ---- resident weights: A operand fragments ---------------------------------------------
     frag wh[RT][KB];
@@ -215,7 +161,7 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
-                const int k = w * kq + kb * KW + TR::koff(lane);
+                const int k = w * kq + ((kb + rot_k) & (KB - 1)) * KW + TR::koff(lane);
                 wh[rt][kb] = TR::load(whh + row * H + k);
                 if (FUSED) wx[rt][kb] = TR::load(wih + row * H + k);
             }
@@ -232,7 +178,7 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
         const int j = w + 4 * o;                    // tile index = rt * CT + ct
         const int rt = j / CT, ct = j - rt * CT;
         const int unit = (rb * RT + rt) * 4 + (lane >> 4);
-        const int col = (cb * CT + ct) * 16 + (lane & 15);
+        const int col = (cb * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
         unit_reg[o] = unit;
         col_reg[o] = col;
         c_reg[o] = 0.0f;
@@ -252,15 +198,18 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
     // computed from a duplicate of the last sequence and never stored)
     int bcol[CT];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct) bcol[ct] = min((cb * CT + ct) * 16 + (lane & 15), B - 1);
+    for (int ct = 0; ct < CT; ++ct)
+        bcol[ct] = min((cb * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
 
-    elem* ring = static_cast<elem*>(p.ring) + (size_t)g * 2 * B * H;
+    elem* hseq = static_cast<elem*>(p.hseq) + (size_t)g * (T + 1) * B * H;
     elem* out = static_cast<elem*>(p.out[ll]);
     const elem* below = fused ? static_cast<const elem*>(p.out[ll - 1]) : nullptr;
     const int out_ld = p.D * H;
-    unsigned* my_flags = p.flags + ((size_t)g * p.ncb + cb) * T;
-    unsigned* below_flags = fused ? p.flags + ((size_t)(g - p.D) * p.ncb + cb) * T : nullptr;
-    const unsigned target = (unsigned)p.nrb;
+    // flag word of (group, step, column block, row block): ((g*T + s)*ncb + cb)*nrb + rb
+    const size_t flag_step = (size_t)p.ncb * p.nrb;
+    uint64_t* my_flags = p.flagv + ((size_t)g * T * p.ncb + cb) * p.nrb;
+    const uint64_t* below_flags = fused ? p.flagv + ((size_t)(g - p.D) * T * p.ncb + cb) * p.nrb : nullptr;
+    const uint32_t epoch = p.epoch;
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
 
@@ -286,21 +235,22 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
 
         if (FUSED) {
             if (fused) {  // x_t = h_t of the layer below
-                wait_flag(below_flags + s, target, p.status, p.spin_limit, aborted);
+                wait_flags(below_flags + s * flag_step, p.nrb, lane, epoch, p.status, p.spin_limit, aborted);
                 const elem* src[CT];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) src[ct] = below + ((size_t)t * B + bcol[ct]) * H + kbase;
-                mma_part<TR, RT, CT, KB>(wx, src, acc);
+                mma_part<TR, RT, CT, KB>(wx, src, acc, rot_k);
             }
         }
 
-        if (s > 0) wait_flag(my_flags + (s - 1), target, p.status, p.spin_limit, aborted);
+        if (s > 0)
+            wait_flags(my_flags + (s - 1) * flag_step, p.nrb, lane, epoch, p.status, p.spin_limit, aborted);
         {
-            const elem* hprev = ring + (size_t)((s + 1) & 1) * B * H;  // slot of step s-1
+            const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
             const elem* src[CT];
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) src[ct] = hprev + (size_t)bcol[ct] * H + kbase;
-            mma_part<TR, RT, CT, KB>(wh, src, acc);
+            mma_part<TR, RT, CT, KB>(wh, src, acc, rot_k);
         }
 
         // partial sums of the four K quarters meet in LDS
@@ -311,7 +261,7 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
                 red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
         __syncthreads();
 
-        elem* hcur = ring + (size_t)(s & 1) * B * H;
+        elem* hcur = hseq + (size_t)(s + 1) * B * H;
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int j = w + 4 * o;
@@ -347,11 +297,11 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
         }
 
         // publish: wait until this wave's stores are acknowledged, meet the other waves, then one
-        // thread bumps the step counter
+        // thread stores this row block's flag word
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-            __hip_atomic_fetch_add(my_flags + s, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            st_dev_u64(my_flags + s * flag_step + rb, ((uint64_t)epoch << 32) | (uint32_t)s);
             if (p.ticks && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
         }
     }
@@ -368,18 +318,17 @@ __global__ __launch_bounds__(256) void wavefront_kernel(WavefrontArgs p) {
 }
 
 template <int DT>
-__global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, int B, int H,
-                                      void* ring, unsigned* flags, size_t nflags) {
+__global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, int T, int B, int H,
+                                      void* hseq) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nflags) flags[i] = 0u;
     const size_t per = (size_t)B * H;
     const size_t n = (size_t)LP * D * per;
     if (i < n) {
         const size_t g = i / per, rem = i - g * per;
         const float h = h0 ? h0[((size_t)l0 * D) * per + i] : 0.0f;
-        const size_t dst = (g * 2 + 1) * per + rem;  // slot 1 holds "step -1"
-        if (DT == DT_BF16) ((bf16_t*)ring)[dst] = f32_to_bf16(h);
-        else ((float*)ring)[dst] = h;
+        const size_t dst = g * (size_t)(T + 1) * per + rem;  // slot 0 = state before step 0
+        if (DT == DT_BF16) ((bf16_t*)hseq)[dst] = f32_to_bf16(h);
+        else ((float*)hseq)[dst] = h;
     }
 }
 
@@ -393,6 +342,19 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
+    // every workgroup must be resident at once: check what the hardware can hold
+    static int max_grid = 0;
+    if (max_grid == 0) {
+        int dev = 0, per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern),
+                                                         256, smem) != hipSuccess)
+            return hipErrorInvalidValue;
+        const int want = variant_occupancy(CT);
+        max_grid = prop.multiProcessorCount * (per_cu < want ? per_cu : want);
+    }
+    if (grid > max_grid) return hipErrorInvalidValue;
     kern<<<dim3(grid), dim3(256), smem, stream>>>(a);
     return hipGetLastError();
 }
@@ -409,11 +371,9 @@ hipError_t launch_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
 
 // (dtype, RT, CT, KB) combinations that are compiled.  KB = H / (4 * KW).
 #define RNN_WF_VARIANTS(X)                                                        \
-    X(TraitsBf16, 1, 1, 1) X(TraitsBf16, 1, 1, 2) X(TraitsBf16, 1, 1, 4) X(TraitsBf16, 1, 1, 8) \
-    X(TraitsBf16, 4, 1, 4) X(TraitsBf16, 4, 1, 8)                                 \
-    X(TraitsBf16, 1, 4, 4) X(TraitsBf16, 4, 4, 4) X(TraitsBf16, 4, 4, 8)          \
-    X(TraitsF32, 1, 1, 2) X(TraitsF32, 1, 1, 4) X(TraitsF32, 1, 1, 8)             \
-    X(TraitsF32, 2, 1, 8) X(TraitsF32, 1, 4, 4)
+    X(TraitsBf16, 1, 4, 1) X(TraitsBf16, 1, 4, 2) X(TraitsBf16, 1, 4, 4)          \
+    X(TraitsBf16, 4, 4, 4) X(TraitsBf16, 4, 4, 8)                                 \
+    X(TraitsF32, 1, 4, 2) X(TraitsF32, 1, 4, 4) X(TraitsF32, 1, 4, 8)
 
 template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
@@ -421,7 +381,8 @@ template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
 }  // namespace
 
-bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool /*fused*/) {
+bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool fused) {
+    if (fused && variant_occupancy(CT) > 1) return false;  // no room for W_ih at two workgroups per CU
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (H % (4 * kw) != 0) return false;
     const int KB = H / (4 * kw);
@@ -431,6 +392,8 @@ bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool /*fused*/) 
 #undef X
     return false;
 }
+
+int wavefront_variant_occupancy(int CT) { return variant_occupancy(CT); }
 
 hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
     const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
@@ -444,15 +407,14 @@ hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int B, int H,
-                                 void* ring, unsigned* flags, size_t nflags, hipStream_t stream) {
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+                                 int H, void* hseq, hipStream_t stream) {
     const size_t n = (size_t)LP * D * B * H;
-    const size_t m = n > nflags ? n : nflags;
-    const unsigned blocks = (unsigned)((m + 255) / 256);
+    const unsigned blocks = (unsigned)((n + 255) / 256);
     if (dtype == DT_BF16)
-        wavefront_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, B, H, ring, flags, nflags);
+        wavefront_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, hseq);
     else
-        wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, B, H, ring, flags, nflags);
+        wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, hseq);
     return hipGetLastError();
 }
 

@@ -1,0 +1,422 @@
+// Persistent wavefront kernel for small batches: the step synchronisation rides on the data.
+//
+// Same decomposition as wavefront.hip (one workgroup group per (layer, direction) of the
+// unrolled cell grid, paper Section 2.2; weights resident in registers as MFMA A operands; four
+// waves split K), for workgroups that own a single tile of 16 sequences.  At batch sizes like
+// these a step is a few hundred nanoseconds of arithmetic, so the cost of a step is the number
+// of device-memory round trips on its critical path.  Counters need about four (write h, wait
+// for the acknowledgement, bump the counter, see the counter, read h).  Here every 8-byte word
+// of the exchanged state carries its own tag:
+//       word = { payload: two bf16 values (or one fp32 value), tag: 32-bit launch epoch }
+// A producer simply stores the words; a consumer loads the words it needs and retries until
+// all their tags equal the epoch of this launch.  8-byte accesses are single-copy atomic, so a
+// word is either old (tag differs) or complete.  The state sequence has one slot per step
+// (slot 0 = h0, slot s+1 = state after step s), each word is written once per launch, and the
+// epoch changes with every launch, so nothing has to be cleared between launches.  Critical
+// path per step: the store becoming visible, one probe and one load round trip; no counters,
+// no store acknowledgement wait, and a single workgroup barrier (for the partial-sum exchange,
+// which is double buffered).
+//
+// For a unidirectional stack the layer above reads the same state sequence as its x_t: where a
+// sequence is still running the state is the layer's output, and where it is padded the cell
+// above is inactive as well and ignores its input.
+// Every wait is bounded (poll budget, shared status word), so the grid always drains.
+#include "wf_traits.h"
+
+namespace rnn {
+namespace {
+
+struct LLBf16 : TraitsBf16 {
+    static constexpr int WORDS_PER_KW = 16;  // 32 bf16 values = 16 tagged words
+    static __device__ inline int row_words(int H) { return H / 2; }
+    static __device__ inline int word_of(int k) { return k >> 1; }
+    // fragment of 8 consecutive K values = the payloads of 4 tagged words, staged in LDS
+    static __device__ inline frag frag_from_lds(const uint32_t* p) {
+        union { u32x4 u; frag f; } v;
+        v.u = *reinterpret_cast<const u32x4*>(p);
+        return v.f;
+    }
+    // lanes n, n+16, n+32, n+48 hold units unit0..unit0+3 of sequence n; lane n writes them
+    static __device__ inline void ll_publish(elem state, elem outv, bool valid, bool write_out,
+                                             int lane, uint32_t epoch, uint64_t* state_dst,
+                                             elem* out_dst) {
+        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
+        const int n = lane & 15;
+        const uint32_t v0 = (uint32_t)__shfl(mine, n);
+        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
+        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
+        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
+        if (valid && lane < 16) {
+            const uint64_t tag = (uint64_t)epoch << 32;
+            st_dev_u64(state_dst, tag | (v0 & 0xFFFFu) | ((v1 & 0xFFFFu) << 16));
+            st_dev_u64(state_dst + 1, tag | (v2 & 0xFFFFu) | ((v3 & 0xFFFFu) << 16));
+            if (write_out) {
+                const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
+                                    ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
+                *reinterpret_cast<uint64_t*>(out_dst) = ov;
+            }
+        }
+    }
+};
+
+struct LLF32 : TraitsF32 {
+    static constexpr int WORDS_PER_KW = 4;
+    static __device__ inline int row_words(int H) { return H; }
+    static __device__ inline int word_of(int k) { return k; }
+    static __device__ inline frag frag_from_lds(const uint32_t* p) { return __uint_as_float(*p); }
+    static __device__ inline void ll_publish(elem state, elem outv, bool valid, bool write_out,
+                                             int lane, uint32_t epoch, uint64_t* state_dst,
+                                             elem* out_dst) {
+        if (valid) {
+            st_dev_u64(state_dst + (lane >> 4), ((uint64_t)epoch << 32) | __float_as_uint(state));
+            if (write_out) out_dst[lane >> 4] = outv;
+        }
+    }
+};
+
+// One wave fetches the tagged words of its K quarter for all sequences of its column block
+// (ncol rows of QW words), checks the tags and leaves the payloads in its own LDS staging area
+// [col][QW + pad] as plain dwords.  Every lane loads 16 bytes (two tagged words) per
+// instruction, so batch 1 with 1024 hidden units needs a single load instruction per source.
+// Device-scope buffer loads (sc1): they see other workgroups' write-through stores and the
+// compiler can keep many of them in flight.  `base` is the byte offset, inside the buffer
+// resource, of word 0 of this wave's quarter for column 0 of the block; row_bytes separates
+// consecutive sequences.  Returns whether every tag equals `epoch`.
+template <int QW>
+__device__ inline bool ll_fetch(__amdgpu_buffer_rsrc_t rsrc, uint32_t base, uint32_t row_bytes, int ncol,
+                                int lane, uint32_t epoch, uint32_t* stage) {
+    constexpr int NI_MAX = (16 * QW + 127) / 128;       // load instructions for a full column block
+    constexpr int STRIDE = QW + 4;                      // padded staging row (dwords)
+    const int total = ncol * QW;                        // tagged words wanted by this wave
+    u32x4 v[NI_MAX];
+#pragma unroll
+    for (int i = 0; i < NI_MAX; ++i) {
+        const int f = i * 128 + 2 * lane;               // first of this lane's two words
+        if (i * 128 < total) {                          // uniform
+            const int c = f / QW, wd = f % QW;
+            // lanes past the end re-read the last pair (in bounds, result unused)
+            const uint32_t off = (f < total) ? base + (uint32_t)c * row_bytes + (uint32_t)wd * 8u
+                                             : base + (uint32_t)(ncol - 1) * row_bytes + (uint32_t)(QW - 2) * 8u;
+            v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 16 /* sc1 */);
+        }
+    }
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < NI_MAX; ++i) {
+        const int f = i * 128 + 2 * lane;
+        if (i * 128 < total && f < total) {
+            const int c = f / QW, wd = f % QW;
+            ok = ok && v[i][1] == epoch && v[i][3] == epoch;
+            *reinterpret_cast<uint2*>(stage + c * STRIDE + wd) = make_uint2(v[i][0], v[i][2]);
+        }
+    }
+    return __all(ok);
+}
+
+// acc[rt] += W[rt][:] x (activations of one source), the source being tagged state words.
+// When the source needs more than one load instruction, waiting is done on a single probe
+// instruction whose lanes sample the first word of every producer tile (4 hidden units written
+// by one wave of one workgroup) over the sequences of the block; the full fetch follows and is
+// repeated until every tag matches.
+template <class TR, int RT, int KB>
+__device__ inline void ll_mma(const typename TR::frag (&wreg)[RT][KB], uint32_t base,
+                              __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol, int lane,
+                              uint32_t probe_rel, uint32_t* stage, f32x4 (&acc)[RT], uint32_t epoch,
+                              unsigned* status, unsigned spin_limit, bool& aborted) {
+    constexpr int QW = KB * TR::WORDS_PER_KW;           // tagged words per sequence in one K quarter
+    constexpr int STRIDE = QW + 4;
+    unsigned spins = 0;
+    auto give_up = [&]() {  // called now and then while waiting
+        const unsigned st = ld_dev_u32(status);
+        if (st != 0u || spins >= spin_limit) {
+            st_dev_u32(status, 1u);
+            aborted = true;
+        }
+    };
+    if (ncol * QW > 128) {
+        while (!aborted) {
+            const uint2 a = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, base + probe_rel, 0, 16));
+            if (__all(a.y == epoch)) break;
+            if ((++spins & 255u) == 0u) give_up();
+        }
+    }
+    for (;;) {
+        const bool ok = ll_fetch<QW>(rsrc, base, row_bytes, ncol, lane, epoch, stage);
+        if (ok || aborted) break;
+        if ((++spins & 63u) == 0u) give_up();
+    }
+    // B operand fragments from the staging area: lane (n, q) reads sequence min(n, ncol-1)
+    const uint32_t* mine = stage + min(lane & 15, ncol - 1) * STRIDE + TR::word_of(TR::koff(lane));
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        const typename TR::frag f = TR::frag_from_lds(mine + kb * TR::WORDS_PER_KW);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wreg[rt][kb], f, acc[rt]);
+    }
+}
+
+template <class TR, int CELL, int RT, int KB, bool FUSED>
+__global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
+    typedef typename TR::elem elem;
+    typedef typename TR::frag frag;
+    constexpr int KW = TR::KW;
+    constexpr int NOWN = (RT + 3) / 4;               // tiles finished by one wave
+    constexpr int QW = KB * TR::WORDS_PER_KW;        // tagged words per sequence and K quarter
+    constexpr int STAGE_DW = 16 * (QW + 4);          // staging dwords per wave: 16 sequence rows
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    // partial sums [2 (step parity)][4 waves][RT][64 lanes], then the per-wave staging areas
+    f32x4* red = reinterpret_cast<f32x4*>(smem_raw);
+    uint32_t* stage = reinterpret_cast<uint32_t*>(smem_raw + (size_t)2 * 4 * RT * 64 * sizeof(f32x4)) +
+                      (threadIdx.x >> 6) * STAGE_DW;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+    const int v = xcd_contiguous_id();
+    const int wpg = p.nrb * p.ncb;
+    const int g = v / wpg;
+    if (g >= p.LP * p.D) return;
+    const int r = v - g * wpg;
+    const int cb = r / p.nrb, rb = r - cb * p.nrb;
+    const int ll = g / p.D, d = g - ll * p.D;
+    const int l = p.l0 + ll;
+    const bool fused = FUSED && ll > 0;
+    const bool write_out = (ll == p.LP - 1);         // only the last layer of a launch is read later
+    const int H = p.H, B = p.B, T = p.T;
+    const int kq = H / 4;
+    const uint32_t epoch = p.epoch;
+
+    frag wh[RT][KB];
+    frag wx[RT][KB];  // only live when FUSED
+    {
+        const elem* whh = static_cast<const elem*>(p.whh[g]);
+        const elem* wih = fused ? static_cast<const elem*>(p.wih[g]) : whh;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const int k = w * kq + kb * KW + TR::koff(lane);
+                wh[rt][kb] = TR::load(whh + row * H + k);
+                if (FUSED) wx[rt][kb] = TR::load(wih + row * H + k);
+            }
+        }
+    }
+
+    float c_reg[NOWN], h_reg[NOWN];
+    f32x4 bias_reg[NOWN];
+    int unit_reg[NOWN];
+    const int col = cb * 16 + (lane & 15);
+    const bool valid = col < B;
+    const int colc = valid ? col : B - 1;            // clamped: loads stay in bounds
+    const int len = valid ? (p.lengths ? min(max(p.lengths[col], 0), T) : T) : 0;
+    const size_t state_row = (size_t)(l * p.D + d) * B;
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) {
+        const int rt = w + 4 * o;
+        const int unit = (rb * RT + rt) * 4 + (lane >> 4);
+        unit_reg[o] = unit;
+        c_reg[o] = 0.0f;
+        h_reg[o] = 0.0f;
+        bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (rt < RT && valid) {
+            const size_t si = (state_row + col) * H + unit;
+            if (p.h0) h_reg[o] = p.h0[si];
+            if (p.c0) c_reg[o] = p.c0[si];
+            bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+        }
+    }
+
+    const int row_words = TR::row_words(H);
+    const size_t seq_words = (size_t)(T + 1) * B * row_words;
+    uint64_t* lseq = p.lseq + (size_t)g * seq_words;
+    // one buffer resource over the state sequences of this group and (when fused) of the layer
+    // below it, which lies directly before it (D == 1); offsets are bytes inside that window
+    const uint64_t* window = fused ? lseq - seq_words : lseq;
+    const uint32_t own_off = fused ? (uint32_t)(seq_words * 8) : 0u;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint64_t*>(window), 0, (int)((fused ? 2 : 1) * seq_words * 8), 0x00020000);
+    const uint32_t row_bytes = (uint32_t)row_words * 8u;
+    const int ncol = min(16, B - cb * 16);
+    // byte offset (inside a slot) of word 0 of this wave's K quarter for column 0 of the block
+    const uint32_t quarter_off = ((uint32_t)(cb * 16) * row_words + TR::word_of(w * kq)) * 8u;
+    uint32_t probe_rel;  // probe word of this lane relative to quarter_off
+    {
+        const int ntile = kq / 4;                               // producer tiles in this K quarter
+        const int ti = lane % ntile, ci = (lane / ntile) % ncol;
+        probe_rel = (uint32_t)ci * row_bytes + (uint32_t)TR::word_of(ti * 4) * 8u;
+    }
+    const uint32_t slot_bytes = (uint32_t)B * row_bytes;
+    elem* out = static_cast<elem*>(p.out[ll]);
+    const int out_ld = p.D * H;
+    bool aborted = false;
+
+    for (int s = 0; s < T; ++s) {
+        const int t = d ? (T - 1 - s) : s;
+
+        f32x4 gx_reg[NOWN];
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            gx_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (!fused && (w + 4 * o) < RT && valid)
+                gx_reg[o] = *reinterpret_cast<const f32x4*>(
+                    p.gx + ((((size_t)t * B + col) * p.D + d) * H + unit_reg[o]) * SLOTS);
+        }
+
+        f32x4 acc[RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+        // A fused layer first consumes x_t = state of the layer below after its step s (slot s+1
+        // of that sequence; t == s when D == 1), then h_{t-1} of its own layer (slot s).  In steady
+        // state the layer trails the one below by a fixed offset: it waits for x_t, while its own
+        // h_{t-1} has been there for a while, so the x part stays off the recurrent critical path.
+        if (FUSED && fused)
+            ll_mma<TR, RT, KB>(wx, (uint32_t)(s + 1) * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
+                               probe_rel, stage, acc, epoch, p.status, p.spin_limit, aborted);
+        ll_mma<TR, RT, KB>(wh, own_off + (uint32_t)s * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
+                           probe_rel, stage, acc, epoch, p.status, p.spin_limit, aborted);
+
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) red[(((s & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+        __syncthreads();
+
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int rt = w + 4 * o;
+            if (rt < RT) {  // uniform per wave
+                f32x4 a = red[(((s & 1) * 4 + 0) * RT + rt) * 64 + lane];
+#pragma unroll
+                for (int q = 1; q < 4; ++q) a += red[(((s & 1) * 4 + q) * RT + rt) * 64 + lane];
+                a += gx_reg[o];
+                a += bias_reg[o];
+                const bool active = valid && t < len;
+                float c_new = c_reg[o];
+                const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
+                const float hn = cell_update<CELL>(pre, h_reg[o], c_new);
+                if (active) {
+                    float kept;
+                    (void)TR::store_val(hn, kept);
+                    c_reg[o] = c_new;
+                    h_reg[o] = kept;
+                }
+                float unused;
+                const elem state_v = TR::store_val(h_reg[o], unused);  // held value when inactive
+                const elem out_v = active ? state_v : TR::zero();
+                const int unit0 = unit_reg[o] - (lane >> 4);
+                TR::ll_publish(state_v, out_v, valid, write_out, lane, epoch,
+                               lseq + ((size_t)(s + 1) * B + colc) * row_words + TR::word_of(unit0),
+                               out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
+            }
+        }
+        if (p.ticks && tid == 0 && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
+    }
+
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) {
+        if ((w + 4 * o) < RT && valid) {
+            const size_t si = (state_row + col) * H + unit_reg[o];
+            if (p.hT) p.hT[si] = h_reg[o];
+            if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[o];
+        }
+    }
+}
+
+// slot 0 of every state sequence of the launch = h0 (rounded to the storage type), tagged
+template <int DT>
+__global__ void wavefront_ll_init_kernel(const float* h0, int l0, int LP, int D, int T, int B, int H,
+                                         uint64_t* lseq, uint32_t epoch) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one tagged word each
+    const int row_words = (DT == DT_BF16) ? H / 2 : H;
+    const size_t per = (size_t)B * row_words;
+    const size_t n = (size_t)LP * D * per;
+    if (i >= n) return;
+    const size_t g = i / per, rem = i - g * per;
+    const size_t b = rem / row_words, wd = rem - b * row_words;
+    const float* src = h0 ? h0 + (((size_t)l0 * D + g) * B + b) * H : nullptr;
+    uint32_t payload;
+    if (DT == DT_BF16) {
+        const float a = src ? src[2 * wd] : 0.0f, c = src ? src[2 * wd + 1] : 0.0f;
+        payload = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(c) << 16);
+    } else {
+        payload = __float_as_uint(src ? src[wd] : 0.0f);
+    }
+    lseq[g * (size_t)(T + 1) * per + rem] = ((uint64_t)epoch << 32) | payload;
+}
+
+template <class TR, int CELL, int RT, int KB, bool FUSED>
+hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
+    const int grid = a.LP * a.D * a.nrb * a.ncb;
+    constexpr int QW = KB * TR::WORDS_PER_KW;
+    const size_t smem = (size_t)2 * 4 * RT * 64 * sizeof(f32x4) + (size_t)4 * 16 * (QW + 4) * sizeof(uint32_t);
+    auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, FUSED>;
+    if (smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    kern<<<dim3(grid), dim3(256), smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+template <class TR, int RT, int KB>
+hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
+    const bool fused = a.LP > 1;
+    if (a.cell == CELL_LSTM)
+        return fused ? launch_ll_variant<TR, CELL_LSTM, RT, KB, true>(a, stream)
+                     : launch_ll_variant<TR, CELL_LSTM, RT, KB, false>(a, stream);
+    return fused ? launch_ll_variant<TR, CELL_GRU, RT, KB, true>(a, stream)
+                 : launch_ll_variant<TR, CELL_GRU, RT, KB, false>(a, stream);
+}
+
+// (dtype traits, RT, KB) combinations that are compiled; KB = H / (4 * KW), CT is always 1.
+#define RNN_LL_VARIANTS(X)                                                       \
+    X(LLBf16, 1, 1) X(LLBf16, 1, 2) X(LLBf16, 1, 4) X(LLBf16, 1, 8)               \
+    X(LLBf16, 2, 4) X(LLBf16, 2, 8) X(LLBf16, 4, 4) X(LLBf16, 4, 8)               \
+    X(LLF32, 1, 2) X(LLF32, 1, 4) X(LLF32, 1, 8) X(LLF32, 2, 4) X(LLF32, 2, 8)
+
+template <class TR> struct LLDtOf;
+template <> struct LLDtOf<LLBf16> { static constexpr int value = DT_BF16; };
+template <> struct LLDtOf<LLF32> { static constexpr int value = DT_F32; };
+
+}  // namespace
+
+bool wavefront_ll_variant_exists(int dtype, int RT, int H) {
+    const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (H % (4 * kw) != 0) return false;
+    const int KB = H / (4 * kw);
+#define X(TR, rt, kb) \
+    if (LLDtOf<TR>::value == dtype && RT == rt && KB == kb) return true;
+    RNN_LL_VARIANTS(X)
+#undef X
+    return false;
+}
+
+hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream) {
+    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (a.H % (4 * kw) != 0 || a.CT != 1) return hipErrorInvalidValue;
+    const int KB = a.H / (4 * kw);
+#define X(TR, rt, kb)                                                 \
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb)       \
+        return launch_ll_cell_fused<TR, rt, kb>(a, stream);
+    RNN_LL_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_wavefront_ll_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+                                    int H, uint64_t* lseq, uint32_t epoch, hipStream_t stream) {
+    const size_t n = (size_t)LP * D * B * (dtype == DT_BF16 ? H / 2 : H);
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    if (dtype == DT_BF16)
+        wavefront_ll_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, lseq, epoch);
+    else
+        wavefront_ll_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, lseq, epoch);
+    return hipGetLastError();
+}
+
+size_t wavefront_ll_words(int dtype, int groups, int T, int B, int H) {
+    return (size_t)groups * (size_t)(T + 1) * B * (dtype == DT_BF16 ? H / 2 : H);
+}
+
+}  // namespace rnn

@@ -1,0 +1,103 @@
+// Pieces shared by the two persistent kernels (counter-synchronised and tag-in-data):
+// device-scope access helpers and the per-dtype MFMA traits.
+#pragma once
+
+#include "common.h"
+#include "kernels.h"
+
+namespace rnn {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// Device-scope (cross-XCD coherent) accesses for data exchanged between workgroups in flight.
+__device__ inline uint64_t ld_dev_u64(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline uint32_t ld_dev_u32(const void* p) {
+    return __hip_atomic_load(reinterpret_cast<const uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_dev_u64(void* p, uint64_t v) {
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_dev_u32(void* p, uint32_t v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct TraitsBf16 {
+    typedef bf16_t elem;
+    typedef bf16x8 frag;
+    static constexpr int KW = 32;  // K elements consumed by one MFMA
+    // lane -> first K element of its fragment inside a KW block
+    static __device__ inline int koff(int lane) { return 8 * (lane >> 4); }
+    static __device__ inline frag load(const elem* p) { return *reinterpret_cast<const frag*>(p); }
+    static __device__ inline frag load_dev(const elem* p) {
+        union { uint64_t u[2]; frag f; } v;
+        v.u[0] = ld_dev_u64(p);
+        v.u[1] = ld_dev_u64(p + 4);
+        return v.f;
+    }
+    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
+    // n+48 (same sequence n) as two 8-byte device-scope stores issued by lane n.
+    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                          elem* out_dst) {
+        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
+        const int n = lane & 15;
+        const uint32_t v0 = (uint32_t)__shfl(mine, n);
+        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
+        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
+        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
+        if (valid && lane < 16) {
+            const uint64_t st = (uint64_t)(v0 & 0xFFFFu) | ((uint64_t)(v1 & 0xFFFFu) << 16) |
+                                ((uint64_t)(v2 & 0xFFFFu) << 32) | ((uint64_t)(v3 & 0xFFFFu) << 48);
+            const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
+                                ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
+            st_dev_u64(state_dst, st);
+            st_dev_u64(out_dst, ov);
+        }
+    }
+    static __device__ inline elem store_val(float h, float& kept) {
+        const bf16_t b = f32_to_bf16(h);
+        kept = bf16_to_f32(b);
+        return b;
+    }
+    static __device__ inline elem zero() { return 0; }
+};
+
+struct TraitsF32 {
+    typedef float elem;
+    typedef float frag;
+    static constexpr int KW = 4;
+    static __device__ inline int koff(int lane) { return lane >> 4; }
+    static __device__ inline frag load(const elem* p) { return *p; }
+    static __device__ inline frag load_dev(const elem* p) { return __uint_as_float(ld_dev_u32(p)); }
+    static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    // every lane stores its own unit; state_dst / out_dst point at unit 4*(tile row) of sequence n
+    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                          elem* out_dst) {
+        if (valid) {
+            st_dev_u32(state_dst + (lane >> 4), __float_as_uint(state));
+            st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
+        }
+    }
+    static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
+    static __device__ inline elem zero() { return 0.0f; }
+};
+
+
+// Renumber workgroups so that consecutive ids share an XCD (the dispatcher hands workgroups to
+// the 8 XCDs round-robin): the workgroups of one (layer, direction, column block) chain then sit
+// on as few XCDs as possible.
+__device__ inline int xcd_contiguous_id() {
+    int v = blockIdx.x;
+    if ((gridDim.x & 7) == 0) v = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    return v;
+}
+
+}  // namespace rnn
