@@ -44,8 +44,9 @@ struct WavefrontArgs {
     int T, B, H, D;
     int L_total;                 // layers of the model (for the hT / cT row index)
     int l0, LP;                  // this launch runs layers [l0, l0 + LP)
-    int RT, CT;                  // 16-row tiles and 16-column tiles per workgroup
-    int nrb, ncb;                // row blocks and column blocks per (layer, direction)
+    int RT, CT;                  // 16-row tiles per workgroup, 16-column tiles per chain
+    int NCH;                     // chains (independent column blocks) per workgroup, 1 or 2
+    int nrb, ncb;                // row blocks and chains (column blocks) per (layer, direction)
     const void* whh[WF_MAX_LAYERS * 2];   // packed W_hh per (local layer, direction): [4H, H]
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
@@ -65,10 +66,10 @@ struct WavefrontArgs {
     uint64_t* lseq;              // tag-in-data kernel only: [LP*D, T+1, B, row_words] tagged words
     uint32_t epoch;              // tag value of this launch (never 0), both kernels
 };
-// Returns hipErrorInvalidValue when no kernel variant exists for (dtype, RT, CT, H).
+// Returns hipErrorInvalidValue when no kernel variant exists for (dtype, RT, CT, NCH, H).
 hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream);
 // True when launch_wavefront has a variant for this combination.
-bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool fused);
+bool wavefront_variant_exists(int dtype, int RT, int CT, int NCH, int H, bool fused);
 // Workgroups per CU the variants with this CT are compiled for (1 or 2).
 int wavefront_variant_occupancy(int CT);
 // Write slot 0 of the state sequence (the state "before step 0") from h0.

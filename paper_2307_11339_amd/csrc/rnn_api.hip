@@ -22,7 +22,7 @@ struct DevBuf {
 
 struct Plan {
     int kind = RNN_PLAN_CELLWISE;   // resolved plan (never AUTO)
-    int LP = 1, RT = 1, CT = 1, nrb = 0, ncb = 0;
+    int LP = 1, RT = 1, CT = 1, NCH = 1, nrb = 0, ncb = 0;
 };
 
 }  // namespace
@@ -128,25 +128,29 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     const int row_tiles = m->H / 4;
     const int col_tiles = (B + 15) / 16;
     const int lp_max = (m->D == 1) ? (m->L < WF_MAX_LAYERS ? m->L : WF_MAX_LAYERS) : 1;
-    static const int cand[][2] = {{1, 1}, {2, 1}, {4, 1}, {1, 4}, {4, 4}};
+    // {row tiles, column tiles per chain, chains per workgroup}
+    static const int cand[][3] = {{1, 1, 1}, {2, 1, 1}, {4, 1, 1}, {1, 4, 1}, {4, 2, 2}, {4, 4, 1}};
     for (int launches = (m->L + lp_max - 1) / lp_max; launches <= m->L; ++launches) {
         const int LP = (m->L + launches - 1) / launches;
         const int budget = m->num_cus / (LP * m->D);
-        int best = -1, best_cost = 0, best_rt = 0;
+        int best = -1, best_cost = 0, best_rt = 0, best_nch = 0;
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
-            const int RT = cand[c][0], CT = cand[c][1];
+            const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
             if (row_tiles % RT) continue;
             const bool have = (CT == 1) ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
-                                        : wavefront_variant_exists(m->dtype, RT, CT, m->H, LP > 1);
+                                        : wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1);
             if (!have) continue;
             const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
+            if (ncb % NCH) continue;
             // the tag-in-data kernel addresses two state sequences with 32-bit byte offsets
             if (CT == 1 && wavefront_ll_words(m->dtype, 2, T, B, m->H) * 8 >= ((size_t)1 << 31)) continue;
             const int occ = (CT == 1) ? 1 : wavefront_variant_occupancy(CT);
-            if (nrb * ncb > budget * occ || ncb > FLAG_COLBLOCKS_MAX) continue;
-            const int cost = RT * CT;
-            if (best < 0 || cost < best_cost || (cost == best_cost && RT > best_rt)) {
-                best = c; best_cost = cost; best_rt = RT;
+            if (nrb * (ncb / NCH) > budget * occ || ncb > FLAG_COLBLOCKS_MAX) continue;
+            // work per workgroup and step; at equal work prefer interleaved chains, then taller tiles
+            const int cost = RT * CT * NCH;
+            if (best < 0 || cost < best_cost || (cost == best_cost && NCH > best_nch) ||
+                (cost == best_cost && NCH == best_nch && RT > best_rt)) {
+                best = c; best_cost = cost; best_rt = RT; best_nch = NCH;
             }
         }
         if (best >= 0) {
@@ -154,6 +158,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             plan.LP = LP;
             plan.RT = cand[best][0];
             plan.CT = cand[best][1];
+            plan.NCH = cand[best][2];
             plan.nrb = row_tiles / plan.RT;
             plan.ncb = (col_tiles + plan.CT - 1) / plan.CT;
             return true;
@@ -298,7 +303,7 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         memset(&a, 0, sizeof(a));
         a.cell = m->cell; a.dtype = m->dtype;
         a.T = T; a.B = B; a.H = m->H; a.D = m->D; a.L_total = m->L;
-        a.l0 = l0; a.LP = LP; a.RT = plan.RT; a.CT = plan.CT; a.nrb = plan.nrb; a.ncb = plan.ncb;
+        a.l0 = l0; a.LP = LP; a.RT = plan.RT; a.CT = plan.CT; a.NCH = plan.NCH; a.nrb = plan.nrb; a.ncb = plan.ncb;
         for (int ll = 0; ll < LP; ++ll) {
             const int l = l0 + ll;
             for (int d = 0; d < m->D; ++d) {

@@ -73,45 +73,31 @@ __device__ inline bool wait_flags(const uint64_t* row, int nrb, int lane, uint32
     return true;
 }
 
-// acc[rt][ct] += W[rt][:] (resident fragments) x activations.  src[ct] points at this lane's
-// first K element of sequence column ct; fragment kb lies kb*KW elements further.  The loads of
-// one chunk are issued back to back and the next chunk is requested before the MFMAs of the
-// current one, so a step pays one memory round trip here, not one per fragment.
-// Register slot kb holds K block (kb + rot) mod KB: workgroups that read the same activations
-// at the same moment start at different K blocks, which spreads them over the L2 channels.
+// Activation fragments of one part (h_{t-1} or x_t) for CT column tiles: buf[kb][ct].  src[ct]
+// points at this lane's first K element of the sequence in column tile ct.  Register slot kb
+// holds K block (kb + rot) mod KB: workgroups that read the same activations at the same
+// moment start at different K blocks, which spreads them over the L2 channels.  All loads are
+// issued back to back, so a part costs one memory round trip, not one per fragment.
+template <class TR, int CT, int KB>
+__device__ inline void load_part(const typename TR::elem* const (&src)[CT], int rot,
+                                 typename TR::frag (&buf)[KB][CT]) {
+    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) buf[kb][ct] = TR::load(src[ct] + ((kb + rot) & (KB - 1)) * TR::KW);
+}
+
+// acc[rt][ct] += W[rt][:] (resident fragments) x the loaded activation fragments
 template <class TR, int RT, int CT, int KB>
 __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
-                                const typename TR::elem* const (&src)[CT], f32x4 (&acc)[RT][CT],
-                                int rot) {
-    typedef typename TR::frag frag;
-    constexpr int KC = (CT >= 4 && KB > 4) ? 4 : KB;  // fragments per chunk and column tile
-    constexpr int NCH = KB / KC;
-    static_assert(KB % KC == 0, "chunking must divide KB");
-    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
-    frag buf[2][KC][CT];
+                                const typename TR::frag (&buf)[KB][CT], f32x4 (&acc)[RT][CT]) {
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc)
+    for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-            buf[0][kc][ct] = TR::load(src[ct] + ((kc + rot) & (KB - 1)) * TR::KW);
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-        if (ch + 1 < NCH) {
-#pragma unroll
-            for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    buf[(ch + 1) & 1][kc][ct] =
-                        TR::load(src[ct] + (((ch + 1) * KC + kc + rot) & (KB - 1)) * TR::KW);
-        }
-#pragma unroll
-        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-            for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    acc[rt][ct] = TR::mfma(wreg[rt][ch * KC + kc], buf[ch & 1][kc][ct], acc[rt][ct]);
-    }
+            for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wreg[rt][kb], buf[kb][ct], acc[rt][ct]);
 }
 
 // Workgroups per CU a variant is compiled for.  (Two workgroups per CU with tiles of 32
@@ -119,13 +105,22 @@ __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
 // L2 traffic, and doubling the number of workgroups raises both.)
 constexpr int variant_occupancy(int /*CT*/) { return 1; }
 
-template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
+// A workgroup owns RT*4 hidden units for NCH chains of CT*16 sequences each.  Chains are
+// independent recurrences, so with NCH = 2 the workgroup alternates between them: once the
+// matrix work of chain c has consumed the activation registers, the flags of the other chain
+// (published half an iteration ago) are checked and its activations are requested; they travel
+// while chain c runs its reduction, gates and publication.  Part of the flag wait and of the
+// L2 round trip of the activations leaves the critical path this way.  (Requesting even
+// earlier, before the matrix work, was measured slower: the flags are then only just being
+// written and the wait is paid in full.  The store acknowledgement wait at the end of chain c
+// also covers the loads in flight, which bounds what can be hidden.)
+template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
     constexpr int KW = TR::KW;
-    constexpr int NTILE = RT * CT;                 // 16x16 output tiles per workgroup
-    constexpr int NOWN = (NTILE + 3) / 4;          // tiles finished by one wave
+    constexpr int NTILE = RT * CT;                 // 16x16 output tiles per chain
+    constexpr int NOWN = (NTILE + 3) / 4;          // tiles of a chain finished by one wave
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
 
@@ -134,18 +129,19 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const int w = tid >> 6;
 
     const int v = xcd_contiguous_id();
-    const int wpg = p.nrb * p.ncb;
+    const int ngrp = p.ncb / NCH;                   // column block groups (ncb counts chains)
+    const int wpg = p.nrb * ngrp;
     const int g = v / wpg;                          // local (layer, direction) index
     if (g >= p.LP * p.D) return;
     const int r = v - g * wpg;
-    const int cb = r / p.nrb, rb = r - cb * p.nrb;
+    const int cbg = r / p.nrb, rb = r - cbg * p.nrb;
     const int ll = g / p.D, d = g - ll * p.D;
     const int l = p.l0 + ll;
     const bool fused = FUSED && ll > 0;
     const int H = p.H, B = p.B, T = p.T;
     const int kq = H / 4;                           // K range of one wave inside each part
 
-    // per-workgroup rotation of the K blocks and of the column tiles (see mma_part)
+    // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
     const int rot_k = rb & (KB - 1);
     const int rot_c = (rb / KB) % CT;
 
@@ -169,152 +165,178 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     }
 
     // ---- per-lane state of the (unit, sequence) pairs this lane finishes ---------------------
-    float c_reg[NOWN], h_reg[NOWN];
+    float c_reg[NCH][NOWN], h_reg[NCH][NOWN];
+    int len_reg[NCH][NOWN], col_reg[NCH][NOWN];
     f32x4 bias_reg[NOWN];
-    int len_reg[NOWN], col_reg[NOWN], unit_reg[NOWN];
+    int unit_reg[NOWN];
     const size_t state_row = (size_t)(l * p.D + d) * B;
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) {
         const int j = w + 4 * o;                    // tile index = rt * CT + ct
         const int rt = j / CT, ct = j - rt * CT;
         const int unit = (rb * RT + rt) * 4 + (lane >> 4);
-        const int col = (cb * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
         unit_reg[o] = unit;
-        col_reg[o] = col;
-        c_reg[o] = 0.0f;
-        h_reg[o] = 0.0f;
-        len_reg[o] = 0;
         bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (j < NTILE && col < B) {
-            const size_t si = (state_row + col) * H + unit;
-            if (p.h0) h_reg[o] = p.h0[si];
-            if (p.c0) c_reg[o] = p.c0[si];
-            len_reg[o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
-            bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+        if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int col = ((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
+            col_reg[c][o] = col;
+            c_reg[c][o] = 0.0f;
+            h_reg[c][o] = 0.0f;
+            len_reg[c][o] = 0;
+            if (j < NTILE && col < B) {
+                const size_t si = (state_row + col) * H + unit;
+                if (p.h0) h_reg[c][o] = p.h0[si];
+                if (p.c0) c_reg[c][o] = p.c0[si];
+                len_reg[c][o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
+            }
         }
     }
 
     // B operand columns of this lane (clamped so that loads stay in bounds; columns >= B are
     // computed from a duplicate of the last sequence and never stored)
-    int bcol[CT];
+    int bcol[NCH][CT];
 #pragma unroll
-    for (int ct = 0; ct < CT; ++ct)
-        bcol[ct] = min((cb * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+            bcol[c][ct] = min(((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
 
     elem* hseq = static_cast<elem*>(p.hseq) + (size_t)g * (T + 1) * B * H;
     elem* out = static_cast<elem*>(p.out[ll]);
     const elem* below = fused ? static_cast<const elem*>(p.out[ll - 1]) : nullptr;
     const int out_ld = p.D * H;
-    // flag word of (group, step, column block, row block): ((g*T + s)*ncb + cb)*nrb + rb
+    // flag word of (group, step, chain column block, row block): ((g*T + s)*ncb + cb)*nrb + rb
     const size_t flag_step = (size_t)p.ncb * p.nrb;
-    uint64_t* my_flags = p.flagv + ((size_t)g * T * p.ncb + cb) * p.nrb;
-    const uint64_t* below_flags = fused ? p.flagv + ((size_t)(g - p.D) * T * p.ncb + cb) * p.nrb : nullptr;
+    uint64_t* my_flags = p.flagv + ((size_t)g * T * p.ncb + cbg * NCH) * p.nrb;          // chain 0
+    const uint64_t* below_flags =
+        fused ? p.flagv + ((size_t)(g - p.D) * T * p.ncb + cbg * NCH) * p.nrb : nullptr;
     const uint32_t epoch = p.epoch;
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
 
+    // h_{t-1} fragments of the chain that is processed next
+    frag hbuf[KB][CT];
+    auto fetch_h = [&](int c, int s) {  // wait for step s-1 of chain c, then request its state
+        if (s > 0)
+            wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb, p.nrb, lane, epoch,
+                       p.status, p.spin_limit, aborted);
+        const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
+        const elem* src[CT];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) src[ct] = hprev + (size_t)bcol[c][ct] * H + kbase;
+        load_part<TR, CT, KB>(src, rot_k, hbuf);
+    };
+    if (NCH > 1) fetch_h(0, 0);
+
     for (int s = 0; s < T; ++s) {
         const int t = d ? (T - 1 - s) : s;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            // projection of this step for the pairs this lane finishes (not needed until the
+            // gates; issued first so that the loads fly during the matrix work)
+            f32x4 gx_reg[NOWN];
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o) {
+                gx_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (!fused && (w + 4 * o) < NTILE && col_reg[c][o] < B)
+                    gx_reg[o] = *reinterpret_cast<const f32x4*>(
+                        p.gx + ((((size_t)t * B + col_reg[c][o]) * p.D + d) * H + unit_reg[o]) * SLOTS);
+            }
 
-        // projection of this step for the pairs this lane finishes (not needed until the gates;
-        // issued first so that the loads fly while the wave waits for the flags)
-        f32x4 gx_reg[NOWN];
+            f32x4 acc[RT][CT];
 #pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            gx_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if (!fused && (w + 4 * o) < NTILE && col_reg[o] < B)
-                gx_reg[o] = *reinterpret_cast<const f32x4*>(
-                    p.gx + ((((size_t)t * B + col_reg[o]) * p.D + d) * H + unit_reg[o]) * SLOTS);
-        }
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        f32x4 acc[RT][CT];
+            if (FUSED) {
+                if (fused) {  // x_t = h_t of the layer below
+                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb, p.nrb, lane, epoch,
+                               p.status, p.spin_limit, aborted);
+                    const elem* src[CT];
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                    for (int ct = 0; ct < CT; ++ct) src[ct] = below + ((size_t)t * B + bcol[c][ct]) * H + kbase;
+                    frag xbuf[KB][CT];
+                    load_part<TR, CT, KB>(src, rot_k, xbuf);
+                    mma_part<TR, RT, CT, KB>(wx, xbuf, acc);
+                }
+            }
 
-        if (FUSED) {
-            if (fused) {  // x_t = h_t of the layer below
-                wait_flags(below_flags + s * flag_step, p.nrb, lane, epoch, p.status, p.spin_limit, aborted);
-                const elem* src[CT];
+            if (NCH == 1) fetch_h(0, s);
+            mma_part<TR, RT, CT, KB>(wh, hbuf, acc);
+            if (NCH > 1) {  // request the state the next chain will need
+                if (c + 1 < NCH) fetch_h(c + 1, s);
+                else if (s + 1 < T) fetch_h(0, s + 1);
+            }
+
+            // partial sums of the four K quarters meet in LDS
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) src[ct] = below + ((size_t)t * B + bcol[ct]) * H + kbase;
-                mma_part<TR, RT, CT, KB>(wx, src, acc, rot_k);
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
+            __syncthreads();
+
+            elem* hcur = hseq + (size_t)(s + 1) * B * H;
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o) {
+                const int j = w + 4 * o;
+                if (j < NTILE) {  // uniform per wave
+                    const bool valid = col_reg[c][o] < B;
+                    f32x4 a = red[(0 * NTILE + j) * 64 + lane];
+#pragma unroll
+                    for (int q = 1; q < 4; ++q) {
+                        const f32x4 b = red[(q * NTILE + j) * 64 + lane];
+                        a += b;
+                    }
+                    a += gx_reg[o];
+                    a += bias_reg[o];
+                    const bool active = valid && t < len_reg[c][o];
+                    float c_new = c_reg[c][o];
+                    const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
+                    const float hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
+                    float kept = h_reg[c][o];
+                    if (active) {
+                        c_reg[c][o] = c_new;
+                        (void)TR::store_val(hn, kept);
+                        h_reg[c][o] = kept;
+                    }
+                    float unused;
+                    const elem state_v = TR::store_val(h_reg[c][o], unused);   // held value when inactive
+                    const elem out_v = active ? state_v : TR::zero();
+                    // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
+                    const int unit0 = unit_reg[o] - (lane >> 4);
+                    const int colc = valid ? col_reg[c][o] : 0;
+                    TR::publish(state_v, out_v, valid, lane, hcur + (size_t)colc * H + unit0,
+                                out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
+                }
+            }
+
+            // publish: wait until this wave's stores are acknowledged, meet the other waves, then
+            // one thread stores this row block's flag word
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (tid == 0) {
+                st_dev_u64(my_flags + (size_t)s * flag_step + (size_t)c * p.nrb + rb,
+                           ((uint64_t)epoch << 32) | (uint32_t)s);
+                if (p.ticks && rb == 0 && cbg == 0 && c == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
             }
         }
+    }
 
-        if (s > 0)
-            wait_flags(my_flags + (s - 1) * flag_step, p.nrb, lane, epoch, p.status, p.spin_limit, aborted);
-        {
-            const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
-            const elem* src[CT];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) src[ct] = hprev + (size_t)bcol[ct] * H + kbase;
-            mma_part<TR, RT, CT, KB>(wh, src, acc, rot_k);
-        }
-
-        // partial sums of the four K quarters meet in LDS
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-                red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
-        __syncthreads();
-
-        elem* hcur = hseq + (size_t)(s + 1) * B * H;
+    for (int c = 0; c < NCH; ++c)
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int j = w + 4 * o;
-            if (j < NTILE) {  // uniform per wave
-                const bool valid = col_reg[o] < B;
-                f32x4 a = red[(0 * NTILE + j) * 64 + lane];
-#pragma unroll
-                for (int q = 1; q < 4; ++q) {
-                    const f32x4 b = red[(q * NTILE + j) * 64 + lane];
-                    a += b;
-                }
-                a += gx_reg[o];
-                a += bias_reg[o];
-                const bool active = valid && t < len_reg[o];
-                float c_new = c_reg[o];
-                const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
-                const float hn = cell_update<CELL>(pre, h_reg[o], c_new);
-                float kept = h_reg[o];
-                if (active) {
-                    c_reg[o] = c_new;
-                    (void)TR::store_val(hn, kept);
-                    h_reg[o] = kept;
-                }
-                float unused;
-                const elem state_v = TR::store_val(h_reg[o], unused);   // held value when inactive
-                const elem out_v = active ? state_v : TR::zero();
-                // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
-                const int unit0 = unit_reg[o] - (lane >> 4);
-                const int colc = valid ? col_reg[o] : 0;
-                TR::publish(state_v, out_v, valid, lane, hcur + (size_t)colc * H + unit0,
-                            out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
+            if (j < NTILE && col_reg[c][o] < B) {
+                const size_t si = (state_row + col_reg[c][o]) * H + unit_reg[o];
+                if (p.hT) p.hT[si] = h_reg[c][o];
+                if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[c][o];
             }
         }
-
-        // publish: wait until this wave's stores are acknowledged, meet the other waves, then one
-        // thread stores this row block's flag word
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) {
-            st_dev_u64(my_flags + s * flag_step + rb, ((uint64_t)epoch << 32) | (uint32_t)s);
-            if (p.ticks && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
-        }
-    }
-
-#pragma unroll
-    for (int o = 0; o < NOWN; ++o) {
-        const int j = w + 4 * o;
-        if (j < NTILE && col_reg[o] < B) {
-            const size_t si = (state_row + col_reg[o]) * H + unit_reg[o];
-            if (p.hT) p.hT[si] = h_reg[o];
-            if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[o];
-        }
-    }
 }
 
 template <int DT>
@@ -332,11 +354,12 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
     }
 }
 
-template <class TR, int CELL, int RT, int CT, int KB, bool FUSED>
+template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
-    const int grid = a.LP * a.D * a.nrb * a.ncb;
+    if (a.ncb % NCH != 0) return hipErrorInvalidValue;
+    const int grid = a.LP * a.D * a.nrb * (a.ncb / NCH);
     const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
-    auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED>;
+    auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -359,21 +382,23 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <class TR, int RT, int CT, int KB>
+template <class TR, int RT, int CT, int KB, int NCH>
 hipError_t launch_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     const bool fused = a.LP > 1;
     if (a.cell == CELL_LSTM)
-        return fused ? launch_variant<TR, CELL_LSTM, RT, CT, KB, true>(a, stream)
-                     : launch_variant<TR, CELL_LSTM, RT, CT, KB, false>(a, stream);
-    return fused ? launch_variant<TR, CELL_GRU, RT, CT, KB, true>(a, stream)
-                 : launch_variant<TR, CELL_GRU, RT, CT, KB, false>(a, stream);
+        return fused ? launch_variant<TR, CELL_LSTM, RT, CT, KB, true, NCH>(a, stream)
+                     : launch_variant<TR, CELL_LSTM, RT, CT, KB, false, NCH>(a, stream);
+    return fused ? launch_variant<TR, CELL_GRU, RT, CT, KB, true, NCH>(a, stream)
+                 : launch_variant<TR, CELL_GRU, RT, CT, KB, false, NCH>(a, stream);
 }
 
-// (dtype, RT, CT, KB) combinations that are compiled.  KB = H / (4 * KW).
+// (dtype, RT, CT, KB, NCH) combinations that are compiled.  KB = H / (4 * KW); CT column tiles
+// per chain, NCH chains per workgroup.
 #define RNN_WF_VARIANTS(X)                                                        \
-    X(TraitsBf16, 1, 4, 1) X(TraitsBf16, 1, 4, 2) X(TraitsBf16, 1, 4, 4)          \
-    X(TraitsBf16, 4, 4, 4) X(TraitsBf16, 4, 4, 8)                                 \
-    X(TraitsF32, 1, 4, 2) X(TraitsF32, 1, 4, 4) X(TraitsF32, 1, 4, 8)
+    X(TraitsBf16, 1, 4, 1, 1) X(TraitsBf16, 1, 4, 2, 1) X(TraitsBf16, 1, 4, 4, 1) \
+    X(TraitsBf16, 4, 4, 4, 1) X(TraitsBf16, 4, 4, 8, 1)                           \
+    X(TraitsBf16, 4, 2, 4, 2) X(TraitsBf16, 4, 2, 8, 2)                           \
+    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)
 
 template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
@@ -381,13 +406,13 @@ template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
 }  // namespace
 
-bool wavefront_variant_exists(int dtype, int RT, int CT, int H, bool fused) {
+bool wavefront_variant_exists(int dtype, int RT, int CT, int NCH, int H, bool fused) {
     if (fused && variant_occupancy(CT) > 1) return false;  // no room for W_ih at two workgroups per CU
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (H % (4 * kw) != 0) return false;
     const int KB = H / (4 * kw);
-#define X(TR, rt, ct, kb) \
-    if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb) return true;
+#define X(TR, rt, ct, kb, nch) \
+    if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb && NCH == nch) return true;
     RNN_WF_VARIANTS(X)
 #undef X
     return false;
@@ -399,9 +424,9 @@ hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
     const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
     const int KB = a.H / (4 * kw);
-#define X(TR, rt, ct, kb)                                                         \
-    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb)        \
-        return launch_cell_fused<TR, rt, ct, kb>(a, stream);
+#define X(TR, rt, ct, kb, nch)                                                          \
+    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
+        return launch_cell_fused<TR, rt, ct, kb, nch>(a, stream);
     RNN_WF_VARIANTS(X)
 #undef X
     return hipErrorInvalidValue;
