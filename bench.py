@@ -126,6 +126,19 @@ def cpu_baseline(name: str, n_seq: int):
                       % (len(rows), cfg.B, name, cfg.L, cfg.T, dt)}
 
 
+def recorded_traffic(workload: str, kernel_class: str):
+    """HBM bytes per launch of the dominant kernel from the committed counter runs (profiles/), or
+    None when there is no record for this workload and kernel or the kernel source has changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "traffic_%s_%s.txt" % (workload, kernel_class))
+    try:
+        rec = json.load(open(path))
+        digest = hashlib.sha256(open(os.path.join(ROOT, rec["source"]), "rb").read()).hexdigest()
+        return rec["hbm_bytes_per_launch"] if digest == rec["source_sha256"] else None
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +147,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--no-extra", action="store_true", help="skip the other named workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run a plain device copy of MIB mebibytes five times (reference reading "
+                         "for the HBM byte counters of a profiler) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this library runs on one GPU; --gpus %d is not supported "
@@ -145,6 +161,17 @@ def main() -> int:
     rnn.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration << 20
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": n, "copies": 5}))
+        return 0
 
     cfg, main_res = time_workload(args.workload, args.steps, args.warmup)
     proj_flops, rec_flops = algorithmic_flops(cfg)
@@ -163,7 +190,7 @@ def main() -> int:
     dominant = "recurrent" if rec_total >= proj_total else "projection"
     ach = rec_tf if dominant == "recurrent" else proj_tf
     roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(ach / peak, 4), "traffic": None, "kernel": dominant,
+                "frac": round(ach / peak, 4), "traffic": recorded_traffic(cfg.name, dominant), "kernel": dominant,
                 "avg_ms": round(main_res[dominant]["avg_ms"], 4)}
 
     line = {
