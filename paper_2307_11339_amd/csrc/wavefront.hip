@@ -28,9 +28,13 @@
 //     is stored;
 //   - every exchanged address is written exactly once per launch (the state of step s has its
 //     own slot, layer outputs are indexed by t) and is read only after its flag vector is
-//     complete, and a cache line never spans two sequences.  A reader's caches therefore cannot
-//     hold a stale copy, so activations are read with ordinary cached loads and the workgroups
-//     of one XCD share them through that XCD's L2.
+//     complete, and a cache line never spans two column blocks.  A reader's caches therefore
+//     cannot hold a stale copy, so activations are read with ordinary cached loads and the
+//     workgroups of one XCD share them through that XCD's L2.
+// The state sequence is stored in blocks of 16 hidden units: slot[unit / 16][sequence][unit % 16].
+// A workgroup that owns 16 units then writes whole cache lines (32 bytes per sequence,
+// sequences adjacent), and a fragment load of a wave covers 16 sequences x 32 contiguous bytes
+// per unit block instead of 16 half lines 2 KiB apart.
 // Every wait is bounded: a wave that exhausts its poll budget raises the status word and stops
 // waiting, so the grid always drains.
 #include "wf_traits.h"
@@ -98,6 +102,11 @@ __device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
         for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wreg[rt][kb], buf[kb][ct], acc[rt][ct]);
+}
+
+// Element offset of (hidden unit k, sequence col) inside one slot of the blocked state sequence.
+__device__ inline size_t hseq_off(int k, int col, int B) {
+    return ((size_t)(k >> 4) * B + col) * 16 + (k & 15);
 }
 
 // Workgroups per CU a variant is compiled for.  (Two workgroups per CU with tiles of 32
@@ -223,10 +232,12 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
             wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb, p.nrb, lane, epoch,
                        p.status, p.spin_limit, aborted);
         const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
-        const elem* src[CT];
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) src[ct] = hprev + (size_t)bcol[c][ct] * H + kbase;
-        load_part<TR, CT, KB>(src, rot_k, hbuf);
+        for (int kb = 0; kb < KB; ++kb) {
+            const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(hprev + hseq_off(k, bcol[c][ct], B));
+        }
     };
     if (NCH > 1) fetch_h(0, 0);
 
@@ -309,7 +320,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                     // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
                     const int unit0 = unit_reg[o] - (lane >> 4);
                     const int colc = valid ? col_reg[c][o] : 0;
-                    TR::publish(state_v, out_v, valid, lane, hcur + (size_t)colc * H + unit0,
+                    TR::publish(state_v, out_v, valid, lane, hcur + hseq_off(unit0, colc, B),
                                 out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
                 }
             }
@@ -348,7 +359,9 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
     if (i < n) {
         const size_t g = i / per, rem = i - g * per;
         const float h = h0 ? h0[((size_t)l0 * D) * per + i] : 0.0f;
-        const size_t dst = g * (size_t)(T + 1) * per + rem;  // slot 0 = state before step 0
+        const size_t b = rem / H, u = rem - b * H;
+        // slot 0 = state before step 0, blocked by 16 hidden units
+        const size_t dst = g * (size_t)(T + 1) * per + ((u >> 4) * B + b) * 16 + (u & 15);
         if (DT == DT_BF16) ((bf16_t*)hseq)[dst] = f32_to_bf16(h);
         else ((float*)hseq)[dst] = h;
     }
