@@ -147,6 +147,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const int ll = g / p.D, d = g - ll * p.D;
     const int l = p.l0 + ll;
     const bool fused = FUSED && ll > 0;
+    const bool out_shared = FUSED && ll + 1 < p.LP;  // a fused layer above reads this layer's output
     const int H = p.H, B = p.B, T = p.T;
     const int kq = H / 4;                           // K range of one wave inside each part
 
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                     // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
                     const int unit0 = unit_reg[o] - (lane >> 4);
                     const int colc = valid ? col_reg[c][o] : 0;
-                    TR::publish(state_v, out_v, valid, lane, hcur + hseq_off(unit0, colc, B),
+                    TR::publish(state_v, out_v, valid, out_shared, lane, hcur + hseq_off(unit0, colc, B),
                                 out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
                 }
             }

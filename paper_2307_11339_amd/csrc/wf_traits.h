@@ -43,8 +43,10 @@ struct TraitsBf16 {
     }
     // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
     // n+48 (same sequence n) as two 8-byte device-scope stores issued by lane n.
-    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
-                                          elem* out_dst) {
+    // out_shared: the layer output is read by another workgroup during this launch (a fused layer
+    // above); otherwise it is an ordinary cached store that L2 can merge into whole lines.
+    static __device__ inline void publish(elem state, elem outv, bool valid, bool out_shared, int lane,
+                                          elem* state_dst, elem* out_dst) {
         const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
         const int n = lane & 15;
         const uint32_t v0 = (uint32_t)__shfl(mine, n);
@@ -57,7 +59,8 @@ struct TraitsBf16 {
             const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
                                 ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
             st_dev_u64(state_dst, st);
-            st_dev_u64(out_dst, ov);
+            if (out_shared) st_dev_u64(out_dst, ov);
+            else *reinterpret_cast<uint64_t*>(out_dst) = ov;
         }
     }
     static __device__ inline elem store_val(float h, float& kept) {
@@ -79,11 +82,12 @@ struct TraitsF32 {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
     // every lane stores its own unit; state_dst / out_dst point at unit 4*(tile row) of sequence n
-    static __device__ inline void publish(elem state, elem outv, bool valid, int lane, elem* state_dst,
-                                          elem* out_dst) {
+    static __device__ inline void publish(elem state, elem outv, bool valid, bool out_shared, int lane,
+                                          elem* state_dst, elem* out_dst) {
         if (valid) {
             st_dev_u32(state_dst + (lane >> 4), __float_as_uint(state));
-            st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
+            if (out_shared) st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
+            else out_dst[lane >> 4] = outv;
         }
     }
     static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
