@@ -41,11 +41,18 @@ def algorithmic_flops(cfg):
     return proj, rec
 
 
-def time_workload(name: str, steps: int, warmup: int, per_call: int = 0, ticks: bool = False):
+def W_paper_grid():
+    from paper_2307_11339_amd import workloads as W
+    return W.paper_grid()
+
+
+def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool = False):
+    """name: one of the named workloads, or a workloads.Config."""
     import torch
     from paper_2307_11339_amd import harness, rnn, workloads as W
 
-    cfg = W.CONFIGS[name]
+    cfg = W.CONFIGS[name] if isinstance(name, str) else name
+    name = cfg.name
     t0 = time.time()
     wl = W.make_workload(cfg)
     model = harness.DeviceModel(wl)
@@ -242,6 +249,14 @@ def main() -> int:
                     e["step_over_lds_bound"] = round(e["step_us_p50"] / bound_us, 2)
             extra[name] = e
         line["workloads"] = extra
+
+    if not args.no_extra:
+        # the paper's own model grid (Table 6): <layers, batch, io size, seq len>, fp32 LSTM
+        grid = {}
+        for c in W_paper_grid():
+            _, r = time_workload(c, steps=30, warmup=3, per_call=30)
+            grid[c.name] = {"p50_ms": round(r["p50_ms"], 4), "ms_per_call": round(r["ms_per_step"], 4)}
+        line["paper_grid"] = grid
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=2)

@@ -230,6 +230,23 @@ def test_C4_sampled_sequences(gpu, oracle, plan):
     _run_named(gpu, oracle, "C4", plan, sample=rows)
 
 
+@pytest.mark.parametrize("index", [0, 3, 9])
+def test_paper_grid_models(gpu, oracle, index):
+    """Models of the paper's own evaluation grid (Table 6: <layers, batch, io size, seq len>, here the
+    baseline <12, 8, 64, 96>, the 16-layer and the io-128 variants), fp32, all layers in one launch."""
+    harness, rnn, W = gpu
+    cfg = W.paper_grid()[index]
+    wl = W.make_workload(cfg)
+    _say("\n  paper grid model %s" % cfg.name)
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    ref = oracle.forward_workload(wl, nthreads=8)
+    _check(harness, wl, io, ref)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    model.close()
+
+
 def test_C5_sampled_sequences(gpu, oracle):
     """Full-size C5 (the throughput workload, in the launch configuration the benchmark times);
     the oracle recomputes 3 of the 256 sequences through all 8 layers and 512 steps."""
