@@ -137,14 +137,15 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
             const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
             if (row_tiles % RT) continue;
-            const bool have = (CT == 1) ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
-                                        : wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1);
+            const bool tagged = (CT == 1 && NCH == 1);  // single tile of 16 sequences: tag-in-data kernel
+            const bool have = tagged ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
+                                     : wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1);
             if (!have) continue;
             const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
             if (ncb % NCH) continue;
             // the tag-in-data kernel addresses two state sequences with 32-bit byte offsets
-            if (CT == 1 && wavefront_ll_words(m->dtype, 2, T, B, m->H) * 8 >= ((size_t)1 << 31)) continue;
-            const int occ = (CT == 1) ? 1 : wavefront_variant_occupancy(CT);
+            if (tagged && wavefront_ll_words(m->dtype, 2, T, B, m->H) * 8 >= ((size_t)1 << 31)) continue;
+            const int occ = tagged ? 1 : wavefront_variant_occupancy(CT);
             if (nrb * (ncb / NCH) > budget * occ || ncb > FLAG_COLBLOCKS_MAX) continue;
             // work per workgroup and step; at equal work prefer interleaved chains, then taller tiles
             const int cost = RT * CT * NCH;
@@ -287,7 +288,7 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
         prof_end(m, ps, st);
-        const bool tagged = plan.CT == 1;
+        const bool tagged = plan.CT == 1 && plan.NCH == 1;
         if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
             if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
             HIP_TRY(hipMemsetAsync(m->flags.p, 0, m->flags.bytes, st));
@@ -485,7 +486,8 @@ int rnn_model_reserve(rnn_model* m, int T, int B) {
     int rc = alloc_workspace(m, Tn, Bn);
     if (rc != RNN_OK) return rc;
     Plan plan;
-    if (resolve_plan(m, Tn, Bn, plan) == RNN_OK && plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1)
+    if (resolve_plan(m, Tn, Bn, plan) == RNN_OK && plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 &&
+        plan.NCH == 1)
         rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, Tn, Bn, m->H));
     return rc;
 }
@@ -501,7 +503,7 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     if (rc != RNN_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
-    if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1) {
+    if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 && plan.NCH == 1) {
         rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H));
         if (rc != RNN_OK) return rc;
     }

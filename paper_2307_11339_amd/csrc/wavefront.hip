@@ -122,7 +122,9 @@ constexpr int variant_occupancy(int /*CT*/) { return 1; }
 // L2 round trip of the activations leaves the critical path this way.  (Requesting even
 // earlier, before the matrix work, was measured slower: the flags are then only just being
 // written and the wait is paid in full.  The store acknowledgement wait at the end of chain c
-// also covers the loads in flight, which bounds what can be hidden.)
+// also covers the loads in flight, which bounds what can be hidden.  Four chains of 16
+// sequences were measured slower than two of 32: the fixed cost of a chain step, two barriers,
+// a store acknowledgement and a flag poll, is paid twice as often.)
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
