@@ -44,6 +44,9 @@ struct WavefrontArgs {
     int T, B, H, D;
     int L_total;                 // layers of the model (for the hT / cT row index)
     int l0, LP;                  // this launch runs layers [l0, l0 + LP)
+    int t0;                      // global index of this launch's first time step (all pointers that
+                                 // are indexed by time already point at that step); lengths count
+                                 // from global step 0
     int RT, CT;                  // 16-row tiles per workgroup, 16-column tiles per chain
     int NCH;                     // chains (independent column blocks) per workgroup, 1 or 2
     int nrb, ncb;                // row blocks and chains (column blocks) per (layer, direction)

@@ -135,6 +135,9 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
 
+    // every step of this kernel is on a dependency chain: when a projection kernel shares the CU,
+    // these waves go first
+    __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = tid >> 6;
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                 const size_t si = (state_row + col) * H + unit;
                 if (p.h0) h_reg[c][o] = p.h0[si];
                 if (p.c0) c_reg[c][o] = p.c0[si];
-                len_reg[c][o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
+                len_reg[c][o] = p.lengths ? min(max(p.lengths[col] - p.t0, 0), T) : T;
             }
         }
     }

@@ -169,6 +169,9 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     uint32_t* stage = reinterpret_cast<uint32_t*>(smem_raw + (size_t)2 * 4 * RT * 64 * sizeof(f32x4)) +
                       (threadIdx.x >> 6) * STAGE_DW;
 
+    // every step of this kernel is on a dependency chain: when a projection kernel shares the CU,
+    // these waves go first
+    __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = tid >> 6;
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     const int col = cb * 16 + (lane & 15);
     const bool valid = col < B;
     const int colc = valid ? col : B - 1;            // clamped: loads stay in bounds
-    const int len = valid ? (p.lengths ? min(max(p.lengths[col], 0), T) : T) : 0;
+    const int len = valid ? (p.lengths ? min(max(p.lengths[col] - p.t0, 0), T) : T) : 0;
     const size_t state_row = (size_t)(l * p.D + d) * B;
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) {

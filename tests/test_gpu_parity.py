@@ -66,6 +66,10 @@ SMALL = [
     ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
+    # 3 layers, large batch, 70 steps: one persistent launch per layer and time chunk, projections on a second stream
+    # (checked on 24 sampled sequences; wide enough that a layer needs every compute unit)
+    ("lstm_bf16_pipelined", 0, 2, 1, 64, 512, 40, 512, 1, True, True),
+    ("gru_bf16_pipelined", 1, 3, 1, 64, 512, 33, 512, 1, True, True),
 ]
 
 
@@ -95,8 +99,13 @@ def test_small_shapes(gpu, oracle, spec, plan):
         return
     io = harness.DeviceIO(wl)
     harness.forward(model, io)
-    ref = oracle.forward_workload(wl, nthreads=8)
-    _check(harness, wl, io, ref)
+    if spec[0].endswith("_pipelined"):
+        rows = np.unique(np.linspace(0, wl.cfg.B - 1, 24).astype(int))
+        ref = oracle.forward_workload(wl.take_batch(rows), nthreads=8)
+        _check(harness, wl, io, ref, rows=rows)
+    else:
+        ref = oracle.forward_workload(wl, nthreads=8)
+        _check(harness, wl, io, ref)
     assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
     # a second call on the same model gives identical bits (fixed reduction order, flags reset)
     y1 = io.y.clone()
