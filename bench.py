@@ -259,7 +259,7 @@ def main() -> int:
         line["paper_grid"] = grid
 
     if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=2)
+        line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)
 
     print(json.dumps(line))
     sys.stdout.flush()

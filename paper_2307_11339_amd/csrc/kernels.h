@@ -53,7 +53,10 @@ struct WavefrontArgs {
     const void* whh[WF_MAX_LAYERS * 2];   // packed W_hh per (local layer, direction): [4H, H]
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
-    const float* gx;             // projection of layer l0: [T*B, D, H, 4]
+    const float* gx;             // projection of layer l0: [T*B, D, H, 4] (unused when xin is given)
+    const void* xin;             // NULL, or the finished input of layer l0, [T, B, H] storage type
+                                 // (D = 1, input width H): layer l0 then multiplies it with its
+                                 // resident W_ih inside the kernel instead of reading gx
     void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type
     void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state
                                  // after step s; every address is written once per launch

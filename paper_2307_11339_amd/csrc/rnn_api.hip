@@ -285,7 +285,7 @@ int ensure_lseq(rnn_model* m, size_t words) {
 // gx: projection of layer l0 for those steps; in/out pointers already point at step t0.
 int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int t0, int T, int T_total, int B,
                      const float* gx, void* y, const int32_t* lengths, const float* h0,
-                     const float* c0, float* hT, float* cT, hipStream_t st) {
+                     const float* c0, float* hT, float* cT, hipStream_t st, const void* xin = nullptr) {
     const bool tagged = plan.CT == 1 && plan.NCH == 1;
     if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
         if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
@@ -316,6 +316,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int t0, int
         a.out[ll] = base + (size_t)t0 * row_elems * m->esize;
     }
     a.gx = gx;
+    a.xin = xin;
     a.hseq = m->hseq.p;
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->flags.p;

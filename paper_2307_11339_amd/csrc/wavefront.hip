@@ -43,25 +43,15 @@ namespace rnn {
 
 namespace {
 
-// Wait until all `nrb` flag words at `row` carry `epoch` (nrb <= 256: up to four words per lane,
-// loaded together).  Returns false when the wait was abandoned (poll budget exhausted, or another
-// workgroup gave up).
-__device__ inline bool wait_flags(const uint64_t* row, int nrb, int lane, uint32_t epoch,
+// Wait until the `n` flag words at `row` carry `epoch` (n <= 64, one word per lane).  Returns
+// false when the wait was abandoned (poll budget exhausted, or another workgroup gave up).
+__device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t epoch,
                                   unsigned* status, unsigned spin_limit, bool& aborted) {
     if (aborted) return false;
     unsigned spins = 0;
-    const int i0 = min(lane, nrb - 1), i1 = min(lane + 64, nrb - 1), i2 = min(lane + 128, nrb - 1),
-              i3 = min(lane + 192, nrb - 1);
+    const int i0 = min(lane, n - 1);
     for (;;) {
-        bool ok;
-        if (nrb <= 64) {
-            ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
-        } else {
-            const uint64_t a = ld_dev_u64(row + i0), b = ld_dev_u64(row + i1), c = ld_dev_u64(row + i2),
-                           d = ld_dev_u64(row + i3);
-            ok = (uint32_t)(a >> 32) == epoch && (uint32_t)(b >> 32) == epoch &&
-                 (uint32_t)(c >> 32) == epoch && (uint32_t)(d >> 32) == epoch;
-        }
+        const bool ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
         if (__all(ok)) break;
         if ((++spins & 1023u) == 0u) {
             const unsigned st = ld_dev_u32(status);
@@ -230,12 +220,16 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const uint32_t epoch = p.epoch;
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
+    // A wave reads only its own K quarter of an activation vector, so it waits only for the row
+    // blocks that produce that quarter (a quarter of the flag vector: one cache line at most).
+    const int nfl = p.nrb / 4;
+    const int fl0 = w * nfl;
 
     // h_{t-1} fragments of the chain that is processed next
     frag hbuf[KB][CT];
     auto fetch_h = [&](int c, int s) {  // wait for step s-1 of chain c, then request its state
         if (s > 0)
-            wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb, p.nrb, lane, epoch,
+            wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
                        p.status, p.spin_limit, aborted);
         const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
 #pragma unroll
@@ -270,7 +264,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
 
             if (FUSED) {
                 if (fused) {  // x_t = h_t of the layer below
-                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb, p.nrb, lane, epoch,
+                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
                                p.status, p.spin_limit, aborted);
                     const elem* src[CT];
 #pragma unroll
@@ -375,7 +369,7 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
 
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
-    if (a.ncb % NCH != 0) return hipErrorInvalidValue;
+    if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
     const int grid = a.LP * a.D * a.nrb * (a.ncb / NCH);
     const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
     auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH>;
