@@ -85,6 +85,9 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
         "projection": {"launches_per_step": proj_n / steps, "avg_ms": proj_ms / max(proj_n, 1)},
         "recurrent": {"launches_per_step": rec_n / steps, "avg_ms": rec_ms / max(rec_n, 1)},
         "device_bytes": rnn.rnn_model_device_bytes(model.handle),
+        # per layer: 1 = the input product is a projection launch, 0 = it runs inside the recurrent kernel
+        "projection_launched": [rnn.rnn_model_input_product_placement(model.handle, cfg.T, cfg.B, l)[1]
+                                for l in range(cfg.L)],
     }
     if per_call > 0:  # per-call latency distribution, each call waited for
         lat = []
@@ -192,8 +195,12 @@ def main() -> int:
         n = max(kern["launches_per_step"], 1e-9)
         return (flops_per_step / n) / (kern["avg_ms"] * 1e-3) / 1e12 if kern["avg_ms"] > 0 else 0.0
 
-    proj_tf = tflops(sum(proj_flops), main_res["projection"])
-    rec_tf = tflops(sum(rec_flops), main_res["recurrent"])
+    # an input product that runs inside the recurrent kernel is that kernel's work
+    placed = main_res["projection_launched"]
+    proj_sep = sum(f for f, sep in zip(proj_flops, placed) if sep == 1)
+    proj_in = sum(f for f, sep in zip(proj_flops, placed) if sep != 1)
+    proj_tf = tflops(proj_sep, main_res["projection"])
+    rec_tf = tflops(sum(rec_flops) + proj_in, main_res["recurrent"])
     dominant = "recurrent" if rec_total >= proj_total else "projection"
     ach = rec_tf if dominant == "recurrent" else proj_tf
     roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
@@ -226,6 +233,7 @@ def main() -> int:
                           "tflops": round(rec_tf, 2), "frac_of_mfma_peak": round(rec_tf / peak, 4)},
         },
         "device_bytes": main_res["device_bytes"],
+        "input_product_in_recurrent_kernel": [l for l, sep in enumerate(placed) if sep != 1],
     }
 
     if not args.no_extra:

@@ -158,6 +158,16 @@ int rnn_model_read_step_ticks(rnn_model* model, uint64_t* ticks, size_t count);
  * persistent forward gave up waiting for a step flag (its outputs are then undefined). */
 int rnn_model_check(rnn_model* model);
 
+/* Where the input product W_ih x_t of `layer` is computed for a forward pass of T steps and B
+ * sequences under the current plan: *separate_launch = 1 when it is a projection launch of its own
+ * (RNN_KERNEL_PROJECTION: the product over all steps, hoisted out of the cell), 0 when it runs
+ * inside the recurrent kernel (RNN_KERNEL_RECURRENT), cell by cell, beside the recurrent product
+ * (the paper's cell, Section 2.2, takes x_t and h_{t-1} together).  Host only, no device work;
+ * measurement code uses it to attribute the product's flops to the kernel that performs them.
+ * RNN_EINVAL on a bad handle, layer, size or a NULL result pointer. */
+int rnn_model_input_product_placement(const rnn_model* model, int T, int B, int layer,
+                                      int* separate_launch);
+
 /* Bytes of device memory the model currently holds: repacked weights plus workspace
  * (the quantity the paper's memory model sums per operator, Section 3, Equation 4). */
 size_t rnn_model_device_bytes(const rnn_model* model);

@@ -44,9 +44,6 @@ struct WavefrontArgs {
     int T, B, H, D;
     int L_total;                 // layers of the model (for the hT / cT row index)
     int l0, LP;                  // this launch runs layers [l0, l0 + LP)
-    int t0;                      // global index of this launch's first time step (all pointers that
-                                 // are indexed by time already point at that step); lengths count
-                                 // from global step 0
     int RT, CT;                  // 16-row tiles per workgroup, 16-column tiles per chain
     int NCH;                     // chains (independent column blocks) per workgroup, 1 or 2
     int nrb, ncb;                // row blocks and chains (column blocks) per (layer, direction)
@@ -54,10 +51,13 @@ struct WavefrontArgs {
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
     const float* gx;             // projection of layer l0: [T*B, D, H, 4] (unused when xin is given)
-    const void* xin;             // NULL, or the finished input of layer l0, [T, B, H] storage type
-                                 // (D = 1, input width H): layer l0 then multiplies it with its
-                                 // resident W_ih inside the kernel instead of reading gx
-    void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type
+    const void* xin;             // NULL, or the finished input of layer l0 (D = 1, input width H):
+                                 // layer l0 then multiplies it with its resident W_ih inside the
+                                 // kernel instead of reading gx
+    int xin_blocked;             // 0: xin is [T, B, H]; 1: xin is the state sequence of the layer
+                                 // below from slot 1 on, [T][H/16][B][16]
+    void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type (the kernel of
+                                 // wavefront_x.hip accepts NULL: output not wanted)
     void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state
                                  // after step s; every address is written once per launch
     const float* h0;             // [L*D, B, H] or NULL
@@ -81,6 +81,12 @@ int wavefront_variant_occupancy(int CT);
 // Write slot 0 of the state sequence (the state "before step 0") from h0.
 hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
                                  int H, void* hseq, hipStream_t stream);
+
+// ---- persistent kernel with the input product inside, one layer per launch (wavefront_x.hip) --
+// Needs a.LP == 1, a.D == 1 and a.xin (the finished input sequence, width H); a.gx is not read.
+hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream);
+// True when a variant exists for this combination and its LDS footprint fits the current device.
+bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H);
 
 // ---- persistent wavefront kernel, tag-in-data variant for CT == 1 (wavefront_ll.hip) --------
 hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream);

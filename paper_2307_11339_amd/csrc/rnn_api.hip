@@ -42,10 +42,6 @@ struct rnn_model {
     int T_res = 0, B_res = 0;
     DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
     DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
-    DevBuf gx2;             // second projection buffer of the pipelined schedule (grown on demand)
-    hipStream_t side = nullptr;       // library-owned stream for projections that run beside a
-                                      // recurrent kernel (default priority)
-    std::vector<hipEvent_t> events;   // dependency events of the pipelined schedule
     uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
     std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
     size_t workspace_bytes = 0;
@@ -87,7 +83,6 @@ void free_workspace(rnn_model* m) {
     for (auto& b : m->ybuf) dev_free(b);
     m->ybuf.clear();
     dev_free(m->lseq);
-    dev_free(m->gx2);
     m->workspace_bytes = 0;
     m->T_res = m->B_res = 0;
 }
@@ -281,11 +276,19 @@ int ensure_lseq(rnn_model* m, size_t words) {
     return RNN_OK;
 }
 
-// One persistent launch: layers [l0, l0 + LP) over the T steps that start at global step t0.
-// gx: projection of layer l0 for those steps; in/out pointers already point at step t0.
-int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int t0, int T, int T_total, int B,
+// State sequences of the layers from l0 on (flag-vector kernels): every (layer, direction) owns
+// T + 1 slots of B * H elements, so a layer can read the finished sequence of the layer below.
+void* state_region(rnn_model* m, int l0, int T, int B) {
+    return (char*)m->hseq.p + (size_t)l0 * m->D * (T + 1) * B * m->H * m->esize;
+}
+
+// One persistent launch: layers [l0, l0 + LP) over all T steps.
+// gx: projection of layer l0, or NULL when the layer computes its input product itself, from xin
+// (the caller's x, [T, B, H]) or, with x_from_state, from the state sequence of the layer below.
+int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int B,
                      const float* gx, void* y, const int32_t* lengths, const float* h0,
-                     const float* c0, float* hT, float* cT, hipStream_t st, const void* xin = nullptr) {
+                     const float* c0, float* hT, float* cT, hipStream_t st, const void* xin = nullptr,
+                     bool x_from_state = false) {
     const bool tagged = plan.CT == 1 && plan.NCH == 1;
     if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
         if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
@@ -296,14 +299,13 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int t0, int
         HIP_TRY(launch_wavefront_ll_init(m->dtype, h0, l0, LP, m->D, T, B, m->H,
                                          (uint64_t*)m->lseq.p, m->epoch, st));
     } else {
-        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, m->H, m->hseq.p, st));
+        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, m->H, state_region(m, l0, T, B), st));
     }
-    const size_t row_elems = (size_t)B * m->D * m->H;  // elements of one time step of a layer output
     WavefrontArgs a;
     memset(&a, 0, sizeof(a));
     a.cell = m->cell; a.dtype = m->dtype;
     a.T = T; a.B = B; a.H = m->H; a.D = m->D; a.L_total = m->L;
-    a.l0 = l0; a.LP = LP; a.t0 = t0;
+    a.l0 = l0; a.LP = LP;
     a.RT = plan.RT; a.CT = plan.CT; a.NCH = plan.NCH; a.nrb = plan.nrb; a.ncb = plan.ncb;
     for (int ll = 0; ll < LP; ++ll) {
         const int l = l0 + ll;
@@ -313,33 +315,38 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int t0, int
             a.bias[ll * m->D + d] = (const float*)m->bias[l * m->D + d].p;
         }
         char* base = (char*)((l == m->L - 1) ? y : m->ybuf[l].p);
-        a.out[ll] = base + (size_t)t0 * row_elems * m->esize;
+        a.out[ll] = base;
+        // a layer whose consumer reads the state sequence instead keeps no separate output
+        if (x_from_state && l != m->L - 1) a.out[ll] = nullptr;
     }
     a.gx = gx;
     a.xin = xin;
-    a.hseq = m->hseq.p;
+    if (x_from_state) {  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
+        a.xin = (const char*)state_region(m, l0 - 1, T, B) + (size_t)B * m->H * m->esize;
+        a.xin_blocked = 1;
+    }
+    a.hseq = state_region(m, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->flags.p;
     a.status = (unsigned*)m->status.p;
-    a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T_total + t0 : nullptr;
+    a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
     a.spin_limit = 1u << 22;
     a.lseq = (uint64_t*)m->lseq.p;
     a.epoch = m->epoch;
     const int ps = prof_begin(m, RNN_KERNEL_RECURRENT, st);
     if (tagged) HIP_TRY(launch_wavefront_ll(a, st));
+    else if (a.xin) HIP_TRY(launch_wavefront_x(a, st));
     else HIP_TRY(launch_wavefront(a, st));
     prof_end(m, ps, st);
     return RNN_OK;
 }
 
-int ensure_gx2(rnn_model* m, size_t bytes) {
-    if (m->gx2.bytes >= bytes) return RNN_OK;
-    HIP_TRY(hipDeviceSynchronize());
-    m->workspace_bytes -= m->gx2.bytes;
-    dev_free(m->gx2);
-    const int rc = dev_alloc(m->gx2, bytes);
-    if (rc == RNN_OK) m->workspace_bytes += bytes;
-    return rc;
+// A layer that runs alone in its launch, in one direction, on an input of its own width can do
+// its input product inside the recurrent kernel (wavefront_x.hip) instead of through a projection.
+bool input_product_inside(const rnn_model* m, const Plan& plan, int l) {
+    return plan.kind == RNN_PLAN_WAVEFRONT && plan.LP == 1 && m->D == 1 &&
+           !(plan.CT == 1 && plan.NCH == 1) && m->layer_input(l) == m->H &&
+           wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
 }
 
 int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
@@ -349,83 +356,22 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
     for (int l0 = 0; l0 < m->L; l0 += plan.LP) {
         const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
+        if (input_product_inside(m, plan, l0)) {
+            // the first layer reads the caller's x; a layer above reads the state sequence below it
+            const int rc = launch_recurrent(m, plan, l0, 1, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
+                                            l0 == 0 ? x : nullptr, l0 > 0);
+            if (rc != RNN_OK) return rc;
+            continue;
+        }
         const int K = m->layer_input(l0);
         const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
         prof_end(m, ps, st);
-        const int rc = launch_recurrent(m, plan, l0, LP, 0, T, T, B, (const float*)m->gx.p, y, lengths, h0,
+        const int rc = launch_recurrent(m, plan, l0, LP, T, B, (const float*)m->gx.p, y, lengths, h0,
                                         c0, hT, cT, st);
         if (rc != RNN_OK) return rc;
     }
-    return RNN_OK;
-}
-
-// Pipelined schedule for a unidirectional stack that runs one layer per persistent launch
-// (large batches): time is cut into chunks, every layer runs one persistent launch per chunk,
-// and the projection of layer l+1 for chunk c is launched on a second stream as soon as layer l
-// has finished chunk c.  It then runs beside the recurrent kernels of layer l's later chunks,
-// which leave most of the MFMA and HBM capacity idle (the unrolled grid of the paper's Section
-// 2.2 again, now with the projection as its own vertex).  The state crosses chunk boundaries
-// through the fp32 carry buffers exactly as it crosses two calls of rnn_forward.  Dependencies
-// are events only; every persistent launch is enqueued on the caller's stream, so two
-// persistent kernels never compete for the compute units.
-constexpr int PIPE_MIN_CHUNK = 16;
-
-bool pipelined_applies(const rnn_model* m, const Plan& plan, int T) {
-    return plan.kind == RNN_PLAN_WAVEFRONT && plan.LP == 1 && m->D == 1 && m->L > 1 &&
-           !(plan.CT == 1 && plan.NCH == 1) && T >= 2 * PIPE_MIN_CHUNK;
-}
-
-int forward_pipelined(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
-                      const float* h0, const float* c0, void* y, float* hT, float* cT, int T,
-                      int B, hipStream_t st) {
-    const int N4 = SLOTS * m->H;
-    const int NC = (T >= 4 * PIPE_MIN_CHUNK) ? 4 : 2;  // measured at 512 steps: 2, 3, 4 and 8 chunks are within 4 %
-    const int Tc = (T + NC - 1) / NC;
-    const size_t gx_step = (size_t)B * N4;  // floats of one time step of a projection
-    if (!m->side) HIP_TRY(hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking));
-    const size_t need_ev = (size_t)2 * m->L * NC + 1;
-    while (m->events.size() < need_ev) {
-        hipEvent_t e;
-        HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        m->events.push_back(e);
-    }
-    auto ev_rec = [&](int l, int c) { return m->events[(size_t)(2 * l) * NC + c]; };
-    auto ev_gemm = [&](int l, int c) { return m->events[(size_t)(2 * l + 1) * NC + c]; };
-    float* gxbuf[2] = {(float*)m->gx.p, (float*)m->gx2.p};
-
-    // layer 0 depends on nothing: one projection over all steps on the caller's stream
-    {
-        const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
-        HIP_TRY(launch_gemm_nt(m->dtype, x, m->I, m->wih[0].p, m->I, gxbuf[0], N4, T * B, N4, m->I, st));
-        prof_end(m, ps, st);
-    }
-    for (int l = 0; l < m->L; ++l) {
-        for (int c = 0; c < NC; ++c) {
-            const int t0 = c * Tc, Tn = (t0 + Tc <= T) ? Tc : (T - t0);
-            if (Tn <= 0) break;
-            const bool first = (c == 0), last = (t0 + Tn == T);
-            if (l > 0) HIP_TRY(hipStreamWaitEvent(st, ev_gemm(l, c), 0));
-            const int rc = launch_recurrent(
-                m, plan, l, 1, t0, Tn, T, B, gxbuf[l & 1] + (size_t)t0 * gx_step, y, lengths,
-                first ? h0 : (const float*)m->h_f32.p, first ? c0 : (const float*)m->c_f32.p,
-                last ? hT : (float*)m->h_f32.p, last ? cT : (float*)m->c_f32.p, st);
-            if (rc != RNN_OK) return rc;
-            if (l + 1 < m->L) {  // projection of the next layer for this chunk, beside what follows
-                HIP_TRY(hipEventRecord(ev_rec(l, c), st));
-                HIP_TRY(hipStreamWaitEvent(m->side, ev_rec(l, c), 0));
-                const char* in = (const char*)m->ybuf[l].p + (size_t)t0 * B * m->H * m->esize;
-                const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, m->side);
-                HIP_TRY(launch_gemm_nt(m->dtype, in, m->H, m->wih[l + 1].p, m->H,
-                                       gxbuf[(l + 1) & 1] + (size_t)t0 * gx_step, N4, Tn * B, N4, m->H,
-                                       m->side));
-                prof_end(m, ps, m->side);
-                HIP_TRY(hipEventRecord(ev_gemm(l + 1, c), m->side));
-            }
-        }
-    }
-    // nothing is left on the side stream that the caller's stream has not waited for
     return RNN_OK;
 }
 
@@ -561,8 +507,6 @@ void rnn_model_destroy(rnn_model* m) {
     for (auto& b : m->bias) dev_free(b);
     dev_free(m->status);
     for (auto& e : m->prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
-    for (auto& e : m->events) (void)hipEventDestroy(e);
-    if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
 }
 
@@ -589,8 +533,6 @@ int rnn_model_reserve(rnn_model* m, int T, int B) {
     if (resolve_plan(m, Tn, Bn, plan) != RNN_OK) return rc;
     if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 && plan.NCH == 1)
         rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, Tn, Bn, m->H));
-    if (rc == RNN_OK && pipelined_applies(m, plan, Tn))
-        rc = ensure_gx2(m, (size_t)Tn * Bn * SLOTS * m->H * sizeof(float));
     return rc;
 }
 
@@ -608,11 +550,6 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 && plan.NCH == 1) {
         rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H));
         if (rc != RNN_OK) return rc;
-    }
-    if (pipelined_applies(m, plan, T)) {
-        rc = ensure_gx2(m, (size_t)T * B * SLOTS * m->H * sizeof(float));
-        if (rc != RNN_OK) return rc;
-        return forward_pipelined(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
     }
     if (plan.kind == RNN_PLAN_WAVEFRONT)
         return forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
@@ -667,6 +604,17 @@ int rnn_model_check(rnn_model* m) {
     unsigned st = 0;
     HIP_TRY(hipMemcpy(&st, m->status.p, sizeof(st), hipMemcpyDeviceToHost));
     return st == 0 ? RNN_OK : RNN_EDEVICE;
+}
+
+int rnn_model_input_product_placement(const rnn_model* m, int T, int B, int layer, int* separate_launch) {
+    if (!m || !separate_launch || T < 1 || B < 1 || layer < 0 || layer >= m->L) return RNN_EINVAL;
+    Plan plan;
+    const int rc = resolve_plan(m, T, B, plan);
+    if (rc != RNN_OK) return rc;
+    if (plan.kind != RNN_PLAN_WAVEFRONT) *separate_launch = 1;
+    else if (input_product_inside(m, plan, layer)) *separate_launch = 0;
+    else *separate_launch = (layer % plan.LP == 0) ? 1 : 0;  // layers above the first of a launch are fused
+    return RNN_OK;
 }
 
 size_t rnn_model_device_bytes(const rnn_model* m) {

@@ -43,62 +43,6 @@ namespace rnn {
 
 namespace {
 
-// Wait until the `n` flag words at `row` carry `epoch` (n <= 64, one word per lane).  Returns
-// false when the wait was abandoned (poll budget exhausted, or another workgroup gave up).
-__device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t epoch,
-                                  unsigned* status, unsigned spin_limit, bool& aborted) {
-    if (aborted) return false;
-    unsigned spins = 0;
-    const int i0 = min(lane, n - 1);
-    for (;;) {
-        const bool ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
-        if (__all(ok)) break;
-        if ((++spins & 1023u) == 0u) {
-            const unsigned st = ld_dev_u32(status);
-            if (st != 0u || spins >= spin_limit) {
-                st_dev_u32(status, 1u);
-                aborted = true;
-                return false;
-            }
-        }
-    }
-    // later loads must not be hoisted above the poll
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    return true;
-}
-
-// Activation fragments of one part (h_{t-1} or x_t) for CT column tiles: buf[kb][ct].  src[ct]
-// points at this lane's first K element of the sequence in column tile ct.  Register slot kb
-// holds K block (kb + rot) mod KB: workgroups that read the same activations at the same
-// moment start at different K blocks, which spreads them over the L2 channels.  All loads are
-// issued back to back, so a part costs one memory round trip, not one per fragment.
-template <class TR, int CT, int KB>
-__device__ inline void load_part(const typename TR::elem* const (&src)[CT], int rot,
-                                 typename TR::frag (&buf)[KB][CT]) {
-    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int ct = 0; ct < CT; ++ct) buf[kb][ct] = TR::load(src[ct] + ((kb + rot) & (KB - 1)) * TR::KW);
-}
-
-// acc[rt][ct] += W[rt][:] (resident fragments) x the loaded activation fragments
-template <class TR, int RT, int CT, int KB>
-__device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
-                                const typename TR::frag (&buf)[KB][CT], f32x4 (&acc)[RT][CT]) {
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wreg[rt][kb], buf[kb][ct], acc[rt][ct]);
-}
-
-// Element offset of (hidden unit k, sequence col) inside one slot of the blocked state sequence.
-__device__ inline size_t hseq_off(int k, int col, int B) {
-    return ((size_t)(k >> 4) * B + col) * 16 + (k & 15);
-}
-
 // Workgroups per CU a variant is compiled for.  (Two workgroups per CU with tiles of 32
 // sequences were measured slower than one with 64: the step is bound by synchronisation and by
 // L2 traffic, and doubling the number of workgroups raises both.)
@@ -194,7 +138,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                 const size_t si = (state_row + col) * H + unit;
                 if (p.h0) h_reg[c][o] = p.h0[si];
                 if (p.c0) c_reg[c][o] = p.c0[si];
-                len_reg[c][o] = p.lengths ? min(max(p.lengths[col] - p.t0, 0), T) : T;
+                len_reg[c][o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
             }
         }
     }

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     const int col = cb * 16 + (lane & 15);
     const bool valid = col < B;
     const int colc = valid ? col : B - 1;            // clamped: loads stay in bounds
-    const int len = valid ? (p.lengths ? min(max(p.lengths[col] - p.t0, 0), T) : T) : 0;
+    const int len = valid ? (p.lengths ? min(max(p.lengths[col], 0), T) : T) : 0;
     const size_t state_row = (size_t)(l * p.D + d) * B;
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) {

@@ -1,0 +1,404 @@
+// Persistent kernel for one layer whose input sequence is complete before the launch and has the
+// layer's own width (every layer above the first of a unidirectional stack): the input product
+// W_ih x_t runs inside the recurrent kernel, so the projection never goes through HBM as fp32.
+//
+// Same decomposition and step protocol as the flag-vector kernel (a workgroup owns RT*4 hidden
+// units for NCH chains of CT*16 sequences, the four waves split K, a vector of flag words per
+// step, a write-once blocked state sequence).  What differs:
+//   - the workgroup's W_ih slice lives in LDS next to the partial-sum exchange buffer, laid out
+//     fragment by fragment exactly as the MFMA reads its A operand (each wave reads back only what
+//     it wrote itself); W_hh stays in registers, because the recurrent product is the part of a
+//     step that sits on the dependency chain;
+//   - x_t needs no flags.  Its fragments for the next chain step are requested right after the
+//     state fragments of that chain step (loads return in order: the state is asked for first
+//     because it is consumed first), and they are multiplied at the top of the chain step, where
+//     the state fragments may still be on their way.
+// With the projection kernel's fp32 output (16 bytes per unit and sequence, fetched in scattered
+// 64-byte pieces that the matrix instructions then had to wait for) gone, a step reads 2 bytes per
+// input element instead.
+#include "wf_traits.h"
+
+namespace rnn {
+
+namespace {
+
+template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool XB>
+__global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
+    typedef typename TR::elem elem;
+    typedef typename TR::frag frag;
+    constexpr int KW = TR::KW;
+    constexpr int NTILE = RT * CT;                 // 16x16 output tiles per chain
+    constexpr int NOWN = (NTILE + 3) / 4;          // tiles of a chain finished by one wave
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
+    frag* wxl = reinterpret_cast<frag*>(smem_raw + (size_t)4 * NTILE * 64 * sizeof(f32x4));  // [4][RT][KB][64]
+
+    __builtin_amdgcn_s_setprio(3);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = tid >> 6;
+
+    const int v = xcd_contiguous_id();
+    const int ngrp = p.ncb / NCH;                   // column block groups (ncb counts chains)
+    if (v >= p.nrb * ngrp) return;
+    const int cbg = v / p.nrb, rb = v - cbg * p.nrb;
+    const int l = p.l0;
+    const int H = p.H, B = p.B, T = p.T;
+    const int kq = H / 4;                           // K range of one wave inside each part
+
+    // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
+    const int rot_k = rb & (KB - 1);
+    const int rot_c = (rb / KB) % CT;
+
+    // ---- resident weights: W_hh fragments in registers, W_ih fragments in LDS ------------------
+    frag wh[RT][KB];
+    frag* wx_mine = wxl + (size_t)w * RT * KB * 64 + lane;
+    {
+        const elem* whh = static_cast<const elem*>(p.whh[0]);
+        const elem* wih = static_cast<const elem*>(p.wih[0]);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const int k = w * kq + ((kb + rot_k) & (KB - 1)) * KW + TR::koff(lane);
+                wh[rt][kb] = TR::load(whh + row * H + k);
+                wx_mine[(rt * KB + kb) * 64] = TR::load(wih + row * H + k);
+            }
+        }
+    }
+
+    // ---- per-lane state of the (unit, sequence) pairs this lane finishes ---------------------
+    float c_reg[NCH][NOWN], h_reg[NCH][NOWN];
+    int len_reg[NCH][NOWN], col_reg[NCH][NOWN];
+    f32x4 bias_reg[NOWN];
+    int unit_reg[NOWN];
+    const size_t state_row = (size_t)l * B;
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) {
+        const int j = w + 4 * o;                    // tile index = rt * CT + ct
+        const int rt = j / CT, ct = j - rt * CT;
+        const int unit = (rb * RT + rt) * 4 + (lane >> 4);
+        unit_reg[o] = unit;
+        bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[0] + (size_t)unit * SLOTS);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int col = ((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
+            col_reg[c][o] = col;
+            c_reg[c][o] = 0.0f;
+            h_reg[c][o] = 0.0f;
+            len_reg[c][o] = 0;
+            if (j < NTILE && col < B) {
+                const size_t si = (state_row + col) * H + unit;
+                if (p.h0) h_reg[c][o] = p.h0[si];
+                if (p.c0) c_reg[c][o] = p.c0[si];
+                len_reg[c][o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
+            }
+        }
+    }
+
+    // B operand columns of this lane (clamped so that loads stay in bounds; columns >= B are
+    // computed from a duplicate of the last sequence and never stored)
+    int bcol[NCH][CT];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+            bcol[c][ct] = min(((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
+
+    elem* hseq = static_cast<elem*>(p.hseq);
+    elem* out = static_cast<elem*>(p.out[0]);
+    const elem* xin = static_cast<const elem*>(p.xin);
+    // flag word of (step, chain column block, row block): (s*ncb + cb)*nrb + rb
+    const size_t flag_step = (size_t)p.ncb * p.nrb;
+    uint64_t* my_flags = p.flagv + (size_t)(cbg * NCH) * p.nrb;   // chain 0
+    const uint32_t epoch = p.epoch;
+    bool aborted = false;
+    const int kbase = w * kq + TR::koff(lane);
+    // a wave waits only for the row blocks that produce its own K quarter of the state
+    const int nfl = p.nrb / 4;
+    const int fl0 = w * nfl;
+
+    frag hbuf[KB][CT];   // h_{t-1} fragments of the chain step that is processed next
+    frag xbuf[KB][CT];   // x_t fragments of the chain step that is processed next
+    // Loads are never predicated (the compiler can then count them and waits only for what an
+    // instruction needs); past the last step they re-read the last one.
+    auto poll_h = [&](int c, int s) {  // wait until step s-1 of chain c is published
+        if (s > 0)
+            wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
+                       p.status, p.spin_limit, aborted);
+    };
+    auto load_h = [&](int c, int s, int kb) {  // K block kb of the state after step s-1
+        const elem* hprev = hseq + (size_t)min(s, T - 1) * B * H;
+        const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(hprev + hseq_off(k, bcol[c][ct], B));
+    };
+    auto load_x = [&](int c, int s, int kb) {  // K block kb of x at step s
+        const elem* xs = xin + (size_t)min(s, T - 1) * B * H;
+        const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+            xbuf[kb][ct] = TR::load(xs + (XB ? hseq_off(k, bcol[c][ct], B) : (size_t)bcol[c][ct] * H + k));
+    };
+    // acc += W_ih slice (A fragments from LDS, read one K block ahead of the matrix instructions)
+    // x the x fragments.  With PREFETCH the state fragments of chain step (cn, sn) are requested
+    // between the matrix instructions, one K block per K block.  The scheduling barriers keep the
+    // compiler from sinking each LDS read to its first use and from bunching the loads.
+    auto input_part = [&](f32x4 (&acc)[RT][CT], bool prefetch, int cn, int sn) {
+        frag abuf[2][RT];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) abuf[0][rt] = wx_mine[(rt * KB + 0) * 64];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            if (kb + 1 < KB) {
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) abuf[(kb + 1) & 1][rt] = wx_mine[(rt * KB + kb + 1) * 64];
+            }
+            if (prefetch) load_h(cn, sn, kb);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // x comes from HBM, and every load a wave has in flight holds back the store acknowledgement
+    // it waits for at the end of a chain step (memory operations return in order).  The workgroups
+    // of a column group that share an XCD read the same x lines through the same L2, so wave 0 of
+    // each of them touches a share of the lines two chain steps ahead with one-dword loads; the
+    // fragment loads then hit L2.  Purely a hint: lines nobody touches are simply fetched later.
+    const bool xcd_packed = (gridDim.x & 7) == 0;
+    const int per_xcd = xcd_packed ? min((int)gridDim.x >> 3, p.nrb) : max(p.nrb >> 3, 1);
+    const int pf_idx = xcd_packed ? rb % per_xcd : min(rb >> 3, per_xcd - 1);
+    constexpr int LINE = 128 / (int)sizeof(elem);                 // elements per cache line
+    constexpr int NLINES = CT * 16 * 16 / LINE;                    // lines of a chain per block of 16 units
+    uint32_t pf_off[NCH];   // element offset, inside one step of x, of the line this lane touches
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int col0 = (cbg * NCH + c) * CT * 16;
+        const int line = min(pf_idx + per_xcd * lane, NLINES * (H / 16) - 1);
+        const int per_row = H / LINE;
+        const size_t off = XB ? ((size_t)(line / NLINES) * B + col0) * 16 + (size_t)(line % NLINES) * LINE
+                              : (size_t)min(col0 + line / per_row, B - 1) * H + (size_t)(line % per_row) * LINE;
+        pf_off[c] = (uint32_t)(min(off, (size_t)B * H - 1) & ~(size_t)(LINE - 1));
+    }
+    auto touch_x = [&](int c, int s) -> uint32_t {
+        return *reinterpret_cast<const uint32_t*>(xin + (size_t)min(s, T - 1) * B * H + pf_off[c]);
+    };
+
+    if (NCH > 1) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) load_h(0, 0, kb);
+    }
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) load_x(0, 0, kb);
+
+    for (int s = 0; s < T; ++s) {
+        const int t = s;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            f32x4 acc[RT][CT];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            // the chain step after this one
+            const int cn = (c + 1 < NCH) ? c + 1 : 0;
+            const int sn = (c + 1 < NCH) ? s : s + 1;
+            uint32_t pf = 0;
+
+            if (NCH > 1) {
+                // Recurrent part first: its operands were requested a chain step ago.  The flags
+                // of the next chain step were stored a chain step ago as well, so the poll is
+                // short, and that chain step's state then travels during the input part.
+                mma_part<TR, RT, CT, KB>(wh, hbuf, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                if (sn < T) poll_h(cn, sn);
+                if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
+                input_part(acc, true, cn, sn);
+            } else {
+                // One chain: the flags of the previous step were stored a moment ago, so the input
+                // part goes first and the state is requested as late as possible.
+                input_part(acc, false, 0, 0);
+                poll_h(0, s);
+                if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) load_h(0, s, kb);
+                mma_part<TR, RT, CT, KB>(wh, hbuf, acc);
+            }
+
+            // partial sums of the four K quarters meet in LDS
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
+            __syncthreads();
+
+            elem* hcur = hseq + (size_t)(s + 1) * B * H;
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o) {
+                // the input of the next chain step is requested in NOWN portions between the gate
+                // computations (its registers are free since the input part)
+#pragma unroll
+                for (int kb = (o * KB) / NOWN; kb < ((o + 1) * KB) / NOWN; ++kb) load_x(cn, sn, kb);
+                __builtin_amdgcn_sched_barrier(0);
+                const int j = w + 4 * o;
+                if (j < NTILE) {  // uniform per wave
+                    const bool valid = col_reg[c][o] < B;
+                    f32x4 a = red[(0 * NTILE + j) * 64 + lane];
+#pragma unroll
+                    for (int q = 1; q < 4; ++q) {
+                        const f32x4 b = red[(q * NTILE + j) * 64 + lane];
+                        a += b;
+                    }
+                    a += bias_reg[o];
+                    const bool active = valid && t < len_reg[c][o];
+                    float c_new = c_reg[c][o];
+                    const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
+                    const float hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
+                    float kept = h_reg[c][o];
+                    if (active) {
+                        c_reg[c][o] = c_new;
+                        (void)TR::store_val(hn, kept);
+                        h_reg[c][o] = kept;
+                    }
+                    float unused;
+                    const elem state_v = TR::store_val(h_reg[c][o], unused);   // held value when inactive
+                    const elem out_v = active ? state_v : TR::zero();
+                    // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
+                    const int unit0 = unit_reg[o] - (lane >> 4);
+                    const int colc = valid ? col_reg[c][o] : 0;
+                    TR::publish(state_v, out_v, valid, false, lane, hcur + hseq_off(unit0, colc, B),
+                                out ? out + ((size_t)t * B + colc) * H + unit0 : nullptr);
+                }
+            }
+
+            // publish: wait until this wave's stores are acknowledged, meet the other waves, then
+            // one thread stores this row block's flag word
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("" ::"v"(pf));  // the touched word is not used
+            __syncthreads();
+            if (tid == 0) {
+                st_dev_u64(my_flags + (size_t)s * flag_step + (size_t)c * p.nrb + rb,
+                           ((uint64_t)epoch << 32) | (uint32_t)s);
+                if (p.ticks && rb == 0 && cbg == 0 && c == 0) p.ticks[s] = wall_clock64();
+            }
+        }
+    }
+
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int j = w + 4 * o;
+            if (j < NTILE && col_reg[c][o] < B) {
+                const size_t si = (state_row + col_reg[c][o]) * H + unit_reg[o];
+                if (p.hT) p.hT[si] = h_reg[c][o];
+                if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[c][o];
+            }
+        }
+}
+
+template <class TR, int RT, int CT, int KB>
+constexpr size_t lds_bytes() {
+    return (size_t)4 * RT * CT * 64 * sizeof(f32x4) + (size_t)4 * RT * KB * 64 * sizeof(typename TR::frag);
+}
+
+int device_lds_limit() {
+    static int limit = -1;
+    if (limit < 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess)
+            limit = v;
+        else
+            limit = 0;
+    }
+    return limit;
+}
+
+template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool XB>
+hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
+    if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
+    const int grid = a.nrb * (a.ncb / NCH);
+    constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
+    if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
+    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, XB>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    // every workgroup must be resident at once: one per compute unit
+    static int max_grid = 0;
+    if (max_grid == 0) {
+        int dev = 0, per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern),
+                                                         256, smem) != hipSuccess)
+            return hipErrorInvalidValue;
+        max_grid = prop.multiProcessorCount * (per_cu < 1 ? per_cu : 1);
+    }
+    if (grid > max_grid) return hipErrorInvalidValue;
+    kern<<<dim3(grid), dim3(256), smem, stream>>>(a);
+    return hipGetLastError();
+}
+
+template <class TR, int RT, int CT, int KB, int NCH>
+hipError_t launch_cell(const WavefrontArgs& a, hipStream_t stream) {
+    if (a.cell == CELL_LSTM)
+        return a.xin_blocked ? launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, true>(a, stream)
+                             : launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, false>(a, stream);
+    return a.xin_blocked ? launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, true>(a, stream)
+                         : launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, false>(a, stream);
+}
+
+// (dtype, RT, CT, KB, NCH) combinations that are compiled: the same shapes as the flag-vector
+// kernel's, so a plan chosen for that kernel can run either.
+#define RNN_WFX_VARIANTS(X)                                                       \
+    X(TraitsBf16, 1, 4, 1, 1) X(TraitsBf16, 1, 4, 2, 1) X(TraitsBf16, 1, 4, 4, 1) \
+    X(TraitsBf16, 4, 4, 4, 1) X(TraitsBf16, 4, 4, 8, 1)                           \
+    X(TraitsBf16, 4, 2, 4, 2) X(TraitsBf16, 4, 2, 8, 2)                           \
+    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)
+
+template <class TR> struct DtOf;
+template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
+template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
+
+}  // namespace
+
+bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H) {
+    const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (H % (4 * kw) != 0) return false;
+    const int KB = H / (4 * kw);
+#define X(TR, rt, ct, kb, nch)                                                               \
+    if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb && NCH == nch)          \
+        return lds_bytes<TR, rt, ct, kb>() <= (size_t)device_lds_limit();
+    RNN_WFX_VARIANTS(X)
+#undef X
+    return false;
+}
+
+hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream) {
+    if (a.LP != 1 || a.D != 1 || a.xin == nullptr) return hipErrorInvalidValue;
+    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
+    const int KB = a.H / (4 * kw);
+#define X(TR, rt, ct, kb, nch)                                                          \
+    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
+        return launch_cell<TR, rt, ct, kb, nch>(a, stream);
+    RNN_WFX_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+}  // namespace rnn

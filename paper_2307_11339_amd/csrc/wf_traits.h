@@ -47,6 +47,7 @@ struct TraitsBf16 {
     // above); otherwise it is an ordinary cached store that L2 can merge into whole lines.
     static __device__ inline void publish(elem state, elem outv, bool valid, bool out_shared, int lane,
                                           elem* state_dst, elem* out_dst) {
+        // out_dst == nullptr: the layer output is not wanted (the consumer reads the state sequence)
         const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
         const int n = lane & 15;
         const uint32_t v0 = (uint32_t)__shfl(mine, n);
@@ -59,8 +60,10 @@ struct TraitsBf16 {
             const uint64_t ov = (uint64_t)(v0 >> 16) | ((uint64_t)(v1 >> 16) << 16) |
                                 ((uint64_t)(v2 >> 16) << 32) | ((uint64_t)(v3 >> 16) << 48);
             st_dev_u64(state_dst, st);
-            if (out_shared) st_dev_u64(out_dst, ov);
-            else *reinterpret_cast<uint64_t*>(out_dst) = ov;
+            if (out_dst) {
+                if (out_shared) st_dev_u64(out_dst, ov);
+                else *reinterpret_cast<uint64_t*>(out_dst) = ov;
+            }
         }
     }
     static __device__ inline elem store_val(float h, float& kept) {
@@ -86,14 +89,72 @@ struct TraitsF32 {
                                           elem* state_dst, elem* out_dst) {
         if (valid) {
             st_dev_u32(state_dst + (lane >> 4), __float_as_uint(state));
-            if (out_shared) st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
-            else out_dst[lane >> 4] = outv;
+            if (out_dst) {
+                if (out_shared) st_dev_u32(out_dst + (lane >> 4), __float_as_uint(outv));
+                else out_dst[lane >> 4] = outv;
+            }
         }
     }
     static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
     static __device__ inline elem zero() { return 0.0f; }
 };
 
+
+// Wait until the `n` flag words at `row` carry `epoch` (n <= 64, one word per lane).  Returns
+// false when the wait was abandoned (poll budget exhausted, or another workgroup gave up).
+__device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t epoch,
+                                  unsigned* status, unsigned spin_limit, bool& aborted) {
+    if (aborted) return false;
+    unsigned spins = 0;
+    const int i0 = min(lane, n - 1);
+    for (;;) {
+        const bool ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
+        if (__all(ok)) break;
+        if ((++spins & 1023u) == 0u) {
+            const unsigned st = ld_dev_u32(status);
+            if (st != 0u || spins >= spin_limit) {
+                st_dev_u32(status, 1u);
+                aborted = true;
+                return false;
+            }
+        }
+    }
+    // later loads must not be hoisted above the poll
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return true;
+}
+
+// Activation fragments of one part (h_{t-1} or x_t) for CT column tiles: buf[kb][ct].  src[ct]
+// points at this lane's first K element of the sequence in column tile ct.  Register slot kb
+// holds K block (kb + rot) mod KB: workgroups that read the same activations at the same
+// moment start at different K blocks, which spreads them over the L2 channels.  All loads are
+// issued back to back, so a part costs one memory round trip, not one per fragment.
+template <class TR, int CT, int KB>
+__device__ inline void load_part(const typename TR::elem* const (&src)[CT], int rot,
+                                 typename TR::frag (&buf)[KB][CT]) {
+    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) buf[kb][ct] = TR::load(src[ct] + ((kb + rot) & (KB - 1)) * TR::KW);
+}
+
+// acc[rt][ct] += W[rt][:] (resident fragments) x the loaded activation fragments
+template <class TR, int RT, int CT, int KB>
+__device__ inline void mma_part(const typename TR::frag (&wreg)[RT][KB],
+                                const typename TR::frag (&buf)[KB][CT], f32x4 (&acc)[RT][CT]) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wreg[rt][kb], buf[kb][ct], acc[rt][ct]);
+}
+
+// Element offset of (hidden unit k, sequence col) inside one slot of the blocked state sequence.
+__device__ inline size_t hseq_off(int k, int col, int B) {
+    return ((size_t)(k >> 4) * B + col) * 16 + (k & 15);
+}
 
 // Renumber workgroups so that consecutive ids share an XCD (the dispatcher hands workgroups to
 // the 8 XCDs round-robin): the workgroups of one (layer, direction, column block) chain then sit

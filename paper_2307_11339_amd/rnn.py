@@ -26,7 +26,7 @@ RNN_PROFILE_KERNELS, RNN_PROFILE_STEP_TICKS = 1, 2
 EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_model_reserve",
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
-           "rnn_model_read_step_ticks")
+           "rnn_model_read_step_ticks", "rnn_model_input_product_placement")
 
 _lib = None
 
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_check.argtypes = [vp]
     lib.rnn_model_device_bytes.restype = ctypes.c_size_t
     lib.rnn_model_device_bytes.argtypes = [vp]
+    lib.rnn_model_input_product_placement.restype = ci
+    lib.rnn_model_input_product_placement.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci)]
     lib.rnn_status_string.restype = ctypes.c_char_p
     lib.rnn_status_string.argtypes = [ci]
     lib.rnn_model_set_profiling.restype = ci
@@ -138,6 +140,13 @@ def rnn_model_check(model: int) -> int:
 
 def rnn_model_device_bytes(model: int) -> int:
     return int(load_library().rnn_model_device_bytes(model))
+
+
+def rnn_model_input_product_placement(model: int, T: int, B: int, layer: int):
+    """Returns (status, separate_launch)."""
+    out = ctypes.c_int(-1)
+    rc = load_library().rnn_model_input_product_placement(model, T, B, layer, ctypes.byref(out))
+    return rc, out.value
 
 
 def rnn_model_set_profiling(model: int, flags: int) -> int:

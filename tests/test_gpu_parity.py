@@ -66,10 +66,14 @@ SMALL = [
     ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
-    # 3 layers, large batch, 70 steps: one persistent launch per layer and time chunk, projections on a second stream
-    # (checked on 24 sampled sequences; wide enough that a layer needs every compute unit)
-    ("lstm_bf16_pipelined", 0, 2, 1, 64, 512, 40, 512, 1, True, True),
-    ("gru_bf16_pipelined", 1, 3, 1, 64, 512, 33, 512, 1, True, True),
+    # Large batch, wide enough that a layer needs every compute unit: one persistent launch per layer.
+    # Layers whose input has the layer's own width compute W_ih x_t inside the recurrent kernel; layers
+    # above the first read the state sequence of the layer below.  Checked on 24 sampled sequences.
+    ("lstm_bf16_inside", 0, 2, 1, 64, 512, 40, 512, 1, True, True),      # first layer projects (I != H)
+    ("gru_bf16_inside", 1, 3, 1, 64, 512, 33, 512, 1, True, True),
+    ("lstm_bf16_inside_sq", 0, 2, 1, 512, 512, 21, 500, 1, True, True),  # I == H: no projection launch; ragged batch tail
+    ("gru_bf16_inside_sq", 1, 2, 1, 512, 512, 17, 512, 1, True, False),
+    ("lstm_f32_inside_sq", 0, 2, 1, 128, 128, 9, 512, 0, True, True),
 ]
 
 
@@ -99,7 +103,7 @@ def test_small_shapes(gpu, oracle, spec, plan):
         return
     io = harness.DeviceIO(wl)
     harness.forward(model, io)
-    if spec[0].endswith("_pipelined"):
+    if "_inside" in spec[0]:
         rows = np.unique(np.linspace(0, wl.cfg.B - 1, 24).astype(int))
         ref = oracle.forward_workload(wl.take_batch(rows), nthreads=8)
         _check(harness, wl, io, ref, rows=rows)
@@ -198,6 +202,31 @@ def test_error_codes(gpu):
         rnn.rnn_model_create(5, 1, 8, 8, 1, 0, [np.zeros(1, np.float32)] * 4, 0)
     with pytest.raises(rnn.RnnError):
         rnn.rnn_model_create(0, 1, 8, 6, 1, 1, [np.zeros(1, np.uint16)] * 4, 0)   # H % 8 != 0 for bf16
+    model.close()
+
+
+def test_input_product_placement(gpu):
+    """Which kernel performs W_ih x_t, per layer, as the library reports it."""
+    harness, rnn, W = gpu
+    by_name = {s[0]: s for s in SMALL}
+    # first layer narrower than the hidden state: it projects, the layer above multiplies inside
+    wl = _small_workload(W, by_name["lstm_bf16_inside"])
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    c = wl.cfg
+    assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l) for l in range(c.L)] == \
+        [(rnn.RNN_OK, 1), (rnn.RNN_OK, 0)]
+    # the same model at batch 2 runs both layers in one launch: the first projects, the second is fused
+    assert [rnn.rnn_model_input_product_placement(model.handle, c.T, 2, l)[1] for l in range(c.L)] == [1, 0]
+    assert rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, c.L)[0] == rnn.RNN_EINVAL
+    assert rnn.rnn_model_input_product_placement(model.handle, 0, c.B, 0)[0] == rnn.RNN_EINVAL
+    model.close()
+    # square first layer: no projection launch at all
+    wl = _small_workload(W, by_name["lstm_bf16_inside_sq"])
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    c = wl.cfg
+    assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l)[1] for l in range(c.L)] == [0, 0]
+    assert rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_CELLWISE) == rnn.RNN_OK
+    assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l)[1] for l in range(c.L)] == [1, 1]
     model.close()
 
 
