@@ -129,24 +129,48 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
                        p.status, p.spin_limit, aborted);
     };
+    // Addresses of the activation loads = uniform base of the step + uniform offset of the K block
+    // + a 32-bit per-lane offset that does not change over the launch (one register per chain and
+    // column tile; full per-load pointers would not fit beside the resident weights).  In the
+    // blocked layout a K block of KW units lies KW * B elements further when KW is a multiple of
+    // 16; otherwise (fp32 fragments of 4 units) the offset is computed per load.
+    constexpr bool LINEAR_K = (KW % 16) == 0;
+    uint32_t hoff[NCH][CT], xoff[NCH][CT];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], B) * sizeof(elem));
+            xoff[c][ct] = XB ? hoff[c][ct] : (uint32_t)(((size_t)bcol[c][ct] * H + kbase) * sizeof(elem));
+        }
+    auto blocked_ptr = [&](const elem* step, int c, int ct, int kb) -> const elem* {
+        const int kr = (kb + rot_k) & (KB - 1);
+        if (LINEAR_K)
+            return reinterpret_cast<const elem*>(reinterpret_cast<const char*>(step) +
+                                                 (size_t)kr * KW * B * sizeof(elem) + hoff[c][ct]);
+        return step + hseq_off(kbase + kr * KW, bcol[c][ct], B);
+    };
     auto load_h = [&](int c, int s, int kb) {  // K block kb of the state after step s-1
         const elem* hprev = hseq + (size_t)min(s, T - 1) * B * H;
-        const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(hprev + hseq_off(k, bcol[c][ct], B));
+        for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(blocked_ptr(hprev, c, ct, kb));
     };
     auto load_x = [&](int c, int s, int kb) {  // K block kb of x at step s
         const elem* xs = xin + (size_t)min(s, T - 1) * B * H;
-        const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-            xbuf[kb][ct] = TR::load(xs + (XB ? hseq_off(k, bcol[c][ct], B) : (size_t)bcol[c][ct] * H + k));
+        for (int ct = 0; ct < CT; ++ct) {
+            if (XB)
+                xbuf[kb][ct] = TR::load(blocked_ptr(xs, c, ct, kb));
+            else
+                xbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
+                    reinterpret_cast<const char*>(xs) + (size_t)((kb + rot_k) & (KB - 1)) * KW * sizeof(elem) +
+                    xoff[c][ct]));
+        }
     };
     // acc += W_ih slice (A fragments from LDS, read one K block ahead of the matrix instructions)
-    // x the x fragments.  With PREFETCH the state fragments of chain step (cn, sn) are requested
-    // between the matrix instructions, one K block per K block.  The scheduling barriers keep the
-    // compiler from sinking each LDS read to its first use and from bunching the loads.
-    auto input_part = [&](f32x4 (&acc)[RT][CT], bool prefetch, int cn, int sn) {
+    // x the x fragments.  The scheduling barriers keep the compiler from sinking each LDS read to
+    // its first use, which would expose the LDS latency once per fragment.
+    auto input_part = [&](f32x4 (&acc)[RT][CT]) {
         frag abuf[2][RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) abuf[0][rt] = wx_mine[(rt * KB + 0) * 64];
@@ -156,13 +180,26 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) abuf[(kb + 1) & 1][rt] = wx_mine[(rt * KB + kb + 1) * 64];
             }
-            if (prefetch) load_h(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // acc += W_hh slice (registers) x the state fragments; the x fragments of chain step (cn, sn),
+    // whose registers the input part has just released, are requested between the matrix
+    // instructions, one K block per K block, so that the loads do not queue up in one burst.
+    auto recurrent_part_prefetching_x = [&](f32x4 (&acc)[RT][CT], int cn, int sn) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
+            load_x(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -213,18 +250,16 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             uint32_t pf = 0;
 
             if (NCH > 1) {
-                // Recurrent part first: its operands were requested a chain step ago.  The flags
-                // of the next chain step were stored a chain step ago as well, so the poll is
-                // short, and that chain step's state then travels during the input part.
-                mma_part<TR, RT, CT, KB>(wh, hbuf, acc);
-                __builtin_amdgcn_sched_barrier(0);
+                // Input part first.  The flags this chain step will poll (those of the chain step
+                // after it, the same chain as the one just published) were stored moments ago and
+                // need about half a microsecond to become visible; both matrix parts run meanwhile.
+                input_part(acc);
+                recurrent_part_prefetching_x(acc, cn, sn);
                 if (sn < T) poll_h(cn, sn);
                 if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
-                input_part(acc, true, cn, sn);
             } else {
-                // One chain: the flags of the previous step were stored a moment ago, so the input
-                // part goes first and the state is requested as late as possible.
-                input_part(acc, false, 0, 0);
+                // One chain: the state is requested as late as possible, after the input part.
+                input_part(acc);
                 poll_h(0, s);
                 if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
 #pragma unroll
@@ -243,10 +278,14 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             elem* hcur = hseq + (size_t)(s + 1) * B * H;
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
-                // the input of the next chain step is requested in NOWN portions between the gate
-                // computations (its registers are free since the input part)
+                // what the next chain step still needs (its state, whose flags have just been seen;
+                // with one chain its input) is requested in NOWN portions between the gate
+                // computations; the registers are free since the matrix parts
 #pragma unroll
-                for (int kb = (o * KB) / NOWN; kb < ((o + 1) * KB) / NOWN; ++kb) load_x(cn, sn, kb);
+                for (int kb = (o * KB) / NOWN; kb < ((o + 1) * KB) / NOWN; ++kb) {
+                    if (NCH > 1) load_h(cn, sn, kb);
+                    else load_x(cn, sn, kb);
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 const int j = w + 4 * o;
                 if (j < NTILE) {  // uniform per wave
@@ -326,6 +365,7 @@ int device_lds_limit() {
 template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool XB>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
+    if ((size_t)a.B * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
     const int grid = a.nrb * (a.ncb / NCH);
     constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
