@@ -192,13 +192,17 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // acc += W_hh slice (registers) x the state fragments; the x fragments of chain step (cn, sn),
     // whose registers the input part has just released, are requested between the matrix
     // instructions, one K block per K block, so that the loads do not queue up in one burst.
-    auto recurrent_part_prefetching_x = [&](f32x4 (&acc)[RT][CT], int cn, int sn) {
+    auto recurrent_part_prefetching_x = [&](f32x4 (&acc)[RT][CT], int cn, int sn, const uint64_t* flag,
+                                            uint64_t& seen) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
+            // half way through, the flag word this lane will poll is requested: by then it has
+            // usually become visible, and its round trip hides behind the remaining instructions
+            if (kb == KB / 2) seen = ld_dev_u64(flag);
             load_x(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -254,8 +258,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 // after it, the same chain as the one just published) were stored moments ago and
                 // need about half a microsecond to become visible; both matrix parts run meanwhile.
                 input_part(acc);
-                recurrent_part_prefetching_x(acc, cn, sn);
-                if (sn < T) poll_h(cn, sn);
+                // flag word of this lane for step sn-1 of chain cn (clamped to a word that exists)
+                const uint64_t* flag = my_flags + (size_t)max(sn - 1, 0) * flag_step + (size_t)cn * p.nrb + fl0 +
+                                       min(lane, nfl - 1);
+                uint64_t seen = 0;
+                recurrent_part_prefetching_x(acc, cn, sn, flag, seen);
+                if (sn > 0 && sn < T && !__all((uint32_t)(seen >> 32) == epoch)) poll_h(cn, sn);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // loads of the state stay below the flag check
                 if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
             } else {
                 // One chain: the state is requested as late as possible, after the input part.
@@ -278,15 +287,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             elem* hcur = hseq + (size_t)(s + 1) * B * H;
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
-                // what the next chain step still needs (its state, whose flags have just been seen;
-                // with one chain its input) is requested in NOWN portions between the gate
-                // computations; the registers are free since the matrix parts
+                if (NCH == 1) {
+                    // one chain: the input of the next step is requested in NOWN portions between
+                    // the gate computations (its registers are free since the input part)
 #pragma unroll
-                for (int kb = (o * KB) / NOWN; kb < ((o + 1) * KB) / NOWN; ++kb) {
-                    if (NCH > 1) load_h(cn, sn, kb);
-                    else load_x(cn, sn, kb);
+                    for (int kb = (o * KB) / NOWN; kb < ((o + 1) * KB) / NOWN; ++kb) load_x(cn, sn, kb);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
                 const int j = w + 4 * o;
                 if (j < NTILE) {  // uniform per wave
                     const bool valid = col_reg[c][o] < B;
@@ -319,8 +326,24 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             }
 
             // publish: wait until this wave's stores are acknowledged, meet the other waves, then
-            // one thread stores this row block's flag word
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // one thread stores this row block's flag word.  With several chains the state of the
+            // next chain step (its flags have been seen) is requested behind the stores: memory
+            // operations complete in order, so waiting until only those KB * CT loads are outstanding
+            // waits for every store, and the loads travel during the wait, the barrier and the input
+            // part of the next chain step.  (The builtin, unlike inline assembly, also tells the
+            // compiler's own wait insertion what has arrived.)
+            asm volatile("" ::: "memory");
+            if (NCH > 1) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) load_h(cn, sn, kb);
+                constexpr int NLD = KB * CT;
+                static_assert(NLD < 64, "vmcnt has six bits");
+                __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+            asm volatile("" ::: "memory");
             asm volatile("" ::"v"(pf));  // the touched word is not used
             __syncthreads();
             if (tid == 0) {
