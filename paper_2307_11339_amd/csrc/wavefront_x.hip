@@ -285,6 +285,15 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             __syncthreads();
 
             elem* hcur = hseq + (size_t)(s + 1) * B * H;
+            // all partial sums of the tiles this wave finishes are read before the first is used
+            // (one LDS round trip instead of one per read)
+            f32x4 part[NOWN][4];
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    part[o][q] = red[(q * NTILE + min(w + 4 * o, NTILE - 1)) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
                 if (NCH == 1) {
@@ -297,12 +306,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 const int j = w + 4 * o;
                 if (j < NTILE) {  // uniform per wave
                     const bool valid = col_reg[c][o] < B;
-                    f32x4 a = red[(0 * NTILE + j) * 64 + lane];
-#pragma unroll
-                    for (int q = 1; q < 4; ++q) {
-                        const f32x4 b = red[(q * NTILE + j) * 64 + lane];
-                        a += b;
-                    }
+                    f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
                     a += bias_reg[o];
                     const bool active = valid && t < len_reg[c][o];
                     float c_new = c_reg[c][o];
@@ -320,8 +324,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
                     const int unit0 = unit_reg[o] - (lane >> 4);
                     const int colc = valid ? col_reg[c][o] : 0;
-                    TR::publish(state_v, out_v, valid, false, lane, hcur + hseq_off(unit0, colc, B),
-                                out ? out + ((size_t)t * B + colc) * H + unit0 : nullptr);
+                    TR::publish_own(state_v, out_v, valid, lane, hcur + hseq_off(unit0, colc, B),
+                                    out ? out + ((size_t)t * B + colc) * H + unit0 : nullptr);
                 }
             }
 

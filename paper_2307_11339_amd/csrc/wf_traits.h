@@ -21,6 +21,9 @@ __device__ inline uint32_t ld_dev_u32(const void* p) {
 __device__ inline void st_dev_u64(void* p, uint64_t v) {
     __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline void st_dev_u16(void* p, uint16_t v) {
+    __hip_atomic_store(reinterpret_cast<uint16_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline void st_dev_u32(void* p, uint32_t v) {
     __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -66,6 +69,15 @@ struct TraitsBf16 {
             }
         }
     }
+    // The same without the cross-lane exchange: every lane stores its own unit (2 bytes); the
+    // lanes of a wave still cover 8 contiguous bytes per sequence.
+    static __device__ inline void publish_own(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                              elem* out_dst) {
+        if (valid) {
+            st_dev_u16(state_dst + (lane >> 4), state);
+            if (out_dst) out_dst[lane >> 4] = outv;
+        }
+    }
     static __device__ inline elem store_val(float h, float& kept) {
         const bf16_t b = f32_to_bf16(h);
         kept = bf16_to_f32(b);
@@ -94,6 +106,10 @@ struct TraitsF32 {
                 else out_dst[lane >> 4] = outv;
             }
         }
+    }
+    static __device__ inline void publish_own(elem state, elem outv, bool valid, int lane, elem* state_dst,
+                                              elem* out_dst) {
+        publish(state, outv, valid, false, lane, state_dst, out_dst);
     }
     static __device__ inline elem store_val(float h, float& kept) { kept = h; return h; }
     static __device__ inline elem zero() { return 0.0f; }
