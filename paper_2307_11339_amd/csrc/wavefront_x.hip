@@ -167,6 +167,27 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     xoff[c][ct]));
         }
     };
+    // wave 0: flag word of the chain step whose stores are still to be acknowledged
+    uint64_t* pend_flag = nullptr;
+    int pend_step = 0, pend_chain = 0;
+    auto store_pending_flag = [&](int loads_behind) {
+        if (pend_flag != nullptr) {
+            if (loads_behind == 0) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            } else {
+                constexpr int NLD = KB * CT;
+                static_assert(NLD < 64, "vmcnt has six bits");
+                __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
+            }
+            asm volatile("" ::: "memory");
+            if (lane == 0) {
+                st_dev_u64(pend_flag, ((uint64_t)epoch << 32) | (uint32_t)pend_step);
+                if (p.ticks && rb == 0 && cbg == 0 && pend_chain == 0) p.ticks[pend_step] = wall_clock64();
+            }
+            pend_flag = nullptr;
+        }
+    };
+
     // acc += W_ih slice (A fragments from LDS, read one K block ahead of the matrix instructions)
     // x the x fragments.  The scheduling barriers keep the compiler from sinking each LDS read to
     // its first use, which would expose the LDS latency once per fragment.
@@ -186,6 +207,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
+            if (NCH > 1 && kb == KB / 4 && w == 0) store_pending_flag(1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -202,7 +224,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
             // half way through, the flag word this lane will poll is requested: by then it has
             // usually become visible, and its round trip hides behind the remaining instructions
-            if (kb == KB / 2) seen = ld_dev_u64(flag);
+            if (kb == (3 * KB) / 4) seen = ld_dev_u64(flag);
             load_x(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -321,42 +343,63 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     float unused;
                     const elem state_v = TR::store_val(h_reg[c][o], unused);   // held value when inactive
                     const elem out_v = active ? state_v : TR::zero();
-                    // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
-                    const int unit0 = unit_reg[o] - (lane >> 4);
-                    const int colc = valid ? col_reg[c][o] : 0;
-                    TR::publish_own(state_v, out_v, valid, lane, hcur + hseq_off(unit0, colc, B),
-                                    out ? out + ((size_t)t * B + colc) * H + unit0 : nullptr);
+                    // Hand the values to wave 0 through LDS: [sequence n][unit u] inside the first
+                    // partial-sum region of this tile, which only this wave has read and only wave 0
+                    // will write again (in the next chain step, after it has read this).
+                    elem* stage = reinterpret_cast<elem*>(red + (size_t)j * 64);
+                    stage[(lane & 15) * 4 + (lane >> 4)] = state_v;
+                    if (out) stage[64 + (lane & 15) * 4 + (lane >> 4)] = out_v;
                 }
             }
 
-            // publish: wait until this wave's stores are acknowledged, meet the other waves, then
-            // one thread stores this row block's flag word.  With several chains the state of the
-            // next chain step (its flags have been seen) is requested behind the stores: memory
-            // operations complete in order, so waiting until only those KB * CT loads are outstanding
-            // waits for every store, and the loads travel during the wait, the barrier and the input
-            // part of the next chain step.  (The builtin, unlike inline assembly, also tells the
-            // compiler's own wait insertion what has arrived.)
+            // Publish.  After the barrier wave 0 alone writes the chain step to memory, 4 units (one
+            // piece) per lane, consecutive lanes consecutive addresses, so whole cache lines leave in
+            // one instruction; it is then the only wave that has to see a store acknowledged.
+            __syncthreads();
+            if (w == 0) {
+                typedef typename TR::piece piece;
+#pragma unroll
+                for (int it = 0; it < NOWN; ++it) {
+                    const int pc = lane + 64 * it;           // piece = (sequence of the chain, tile row)
+                    const int sl = pc / RT, rt = pc - sl * RT;
+                    const int ct = ((sl >> 4) - rot_c + CT) % CT;
+                    const int col = (cbg * NCH + c) * CT * 16 + sl;
+                    const elem* stage = reinterpret_cast<const elem*>(red + (size_t)(rt * CT + ct) * 64) + (sl & 15) * 4;
+                    const int unit0 = (rb * RT + rt) * 4;
+                    if (col < B) {
+                        TR::store_piece_dev(hcur + hseq_off(unit0, col, B), *reinterpret_cast<const piece*>(stage));
+                        if (out)
+                            *reinterpret_cast<piece*>(out + ((size_t)t * B + col) * H + unit0) =
+                                *reinterpret_cast<const piece*>(stage + 64);
+                    }
+                }
+            }
             asm volatile("" ::: "memory");
             if (NCH > 1) {
+                // The state of the next chain step (its flags have been seen) is requested behind the
+                // stores.  Memory operations complete in order, so once only these KB * CT loads are
+                // outstanding every store has been acknowledged; wave 0 checks that half way through
+                // the input part of the next chain step, where it no longer has to wait, and stores
+                // the flag word there.
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) load_h(cn, sn, kb);
-                constexpr int NLD = KB * CT;
-                static_assert(NLD < 64, "vmcnt has six bits");
-                __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
-            } else {
+                pend_flag = my_flags + (size_t)s * flag_step + (size_t)c * p.nrb + rb;
+                pend_step = s;
+                pend_chain = c;
+            } else if (w == 0) {
+                // one chain: the next step polls this flag at once
                 __builtin_amdgcn_s_waitcnt(0x0F70);
+                asm volatile("" ::: "memory");
+                if (lane == 0) {
+                    st_dev_u64(my_flags + (size_t)s * flag_step + rb, ((uint64_t)epoch << 32) | (uint32_t)s);
+                    if (p.ticks && rb == 0 && cbg == 0) p.ticks[s] = wall_clock64();
+                }
             }
-            asm volatile("" ::: "memory");
             asm volatile("" ::"v"(pf));  // the touched word is not used
-            __syncthreads();
-            if (tid == 0) {
-                st_dev_u64(my_flags + (size_t)s * flag_step + (size_t)c * p.nrb + rb,
-                           ((uint64_t)epoch << 32) | (uint32_t)s);
-                if (p.ticks && rb == 0 && cbg == 0 && c == 0) p.ticks[s] = wall_clock64();
-            }
         }
     }
+    if (NCH > 1 && w == 0) store_pending_flag(0);
 
 #pragma unroll
     for (int c = 0; c < NCH; ++c)

@@ -44,6 +44,8 @@ struct TraitsBf16 {
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
     }
+    typedef uint64_t piece;  // 4 consecutive units of one sequence
+    static __device__ inline void store_piece_dev(elem* dst, piece v) { st_dev_u64(dst, v); }
     // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
     // n+48 (same sequence n) as two 8-byte device-scope stores issued by lane n.
     // out_shared: the layer output is read by another workgroup during this launch (a fused layer
@@ -95,6 +97,11 @@ struct TraitsF32 {
     static __device__ inline frag load_dev(const elem* p) { return __uint_as_float(ld_dev_u32(p)); }
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+    struct __attribute__((aligned(16))) piece { uint64_t lo, hi; };  // 4 consecutive units of one sequence
+    static __device__ inline void store_piece_dev(elem* dst, piece v) {
+        st_dev_u64(dst, v.lo);
+        st_dev_u64(dst + 2, v.hi);
     }
     // every lane stores its own unit; state_dst / out_dst point at unit 4*(tile row) of sequence n
     static __device__ inline void publish(elem state, elem outv, bool valid, bool out_shared, int lane,
