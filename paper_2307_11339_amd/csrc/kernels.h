@@ -51,11 +51,10 @@ struct WavefrontArgs {
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
     const float* gx;             // projection of layer l0: [T*B, D, H, 4] (unused when xin is given)
-    const void* xin;             // NULL, or the finished input of layer l0 (D = 1, input width H):
-                                 // layer l0 then multiplies it with its resident W_ih inside the
-                                 // kernel instead of reading gx
-    int xin_blocked;             // 0: xin is [T, B, H]; 1: xin is the state sequence of the layer
-                                 // below from slot 1 on, [T][H/16][B][16]
+    const void* xin;             // NULL, or the finished input of layer l0 (D = 1, input width H) in
+                                 // the layout of a state sequence, [T][H/16][B][16]: layer l0 then
+                                 // multiplies it with its resident W_ih inside the kernel instead
+                                 // of reading gx
     void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type (the kernel of
                                  // wavefront_x.hip accepts NULL: output not wanted)
     void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state
@@ -87,6 +86,9 @@ hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream);
 // True when a variant exists for this combination and its LDS footprint fits the current device.
 bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H);
+// src [T, B, H] -> dst [T][H/16][B][16] (the layout of a state sequence); H % 16 == 0, T <= 65535,
+// one row of 16 sequences must fit 64 KiB of LDS.
+hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int H, hipStream_t stream);
 
 // ---- persistent wavefront kernel, tag-in-data variant for CT == 1 (wavefront_ll.hip) --------
 hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream);

@@ -41,6 +41,7 @@ struct rnn_model {
     // workspace, sized for (T_res, B_res)
     int T_res = 0, B_res = 0;
     DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
+    DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
     DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
     uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
     std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
@@ -83,6 +84,7 @@ void free_workspace(rnn_model* m) {
     for (auto& b : m->ybuf) dev_free(b);
     m->ybuf.clear();
     dev_free(m->lseq);
+    dev_free(m->xblk);
     m->workspace_bytes = 0;
     m->T_res = m->B_res = 0;
 }
@@ -113,6 +115,7 @@ int alloc_workspace(rnn_model* m, int T, int B) {
     get(m->h_st, state * m->esize);
     get(m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
     get(m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    if (m->D == 1 && m->I == m->H) get(m->xblk, rows * m->H * m->esize);
     if (rc != RNN_OK) {
         free_workspace(m);
         return rc;
@@ -284,7 +287,7 @@ void* state_region(rnn_model* m, int l0, int T, int B) {
 
 // One persistent launch: layers [l0, l0 + LP) over all T steps.
 // gx: projection of layer l0, or NULL when the layer computes its input product itself, from xin
-// (the caller's x, [T, B, H]) or, with x_from_state, from the state sequence of the layer below.
+// (blocked like a state sequence) or, with x_from_state, from the state sequence of the layer below.
 int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int B,
                      const float* gx, void* y, const int32_t* lengths, const float* h0,
                      const float* c0, float* hT, float* cT, hipStream_t st, const void* xin = nullptr,
@@ -317,14 +320,12 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         char* base = (char*)((l == m->L - 1) ? y : m->ybuf[l].p);
         a.out[ll] = base;
         // a layer whose consumer reads the state sequence instead keeps no separate output
-        if (x_from_state && l != m->L - 1) a.out[ll] = nullptr;
+        if ((xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
     }
     a.gx = gx;
     a.xin = xin;
-    if (x_from_state) {  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
+    if (x_from_state)  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
         a.xin = (const char*)state_region(m, l0 - 1, T, B) + (size_t)B * m->H * m->esize;
-        a.xin_blocked = 1;
-    }
     a.hseq = state_region(m, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->flags.p;
@@ -343,7 +344,9 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
 
 // A layer that runs alone in its launch, in one direction, on an input of its own width can do
 // its input product inside the recurrent kernel (wavefront_x.hip) instead of through a projection.
-bool input_product_inside(const rnn_model* m, const Plan& plan, int l) {
+bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
+    // the first layer's input is first brought into the layout of a state sequence
+    if (l == 0 && (T > 65535 || (size_t)16 * m->H * m->esize > 64 * 1024)) return false;
     return plan.kind == RNN_PLAN_WAVEFRONT && plan.LP == 1 && m->D == 1 &&
            !(plan.CT == 1 && plan.NCH == 1) && m->layer_input(l) == m->H &&
            wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
@@ -356,10 +359,11 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
     for (int l0 = 0; l0 < m->L; l0 += plan.LP) {
         const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
-        if (input_product_inside(m, plan, l0)) {
-            // the first layer reads the caller's x; a layer above reads the state sequence below it
+        if (input_product_inside(m, plan, l0, T)) {
+            // the first layer reads the caller's x, re-laid out; a layer above reads the state sequence below it
+            if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, m->H, st));
             const int rc = launch_recurrent(m, plan, l0, 1, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
-                                            l0 == 0 ? x : nullptr, l0 > 0);
+                                            l0 == 0 ? m->xblk.p : nullptr, l0 > 0);
             if (rc != RNN_OK) return rc;
             continue;
         }
@@ -612,7 +616,7 @@ int rnn_model_input_product_placement(const rnn_model* m, int T, int B, int laye
     const int rc = resolve_plan(m, T, B, plan);
     if (rc != RNN_OK) return rc;
     if (plan.kind != RNN_PLAN_WAVEFRONT) *separate_launch = 1;
-    else if (input_product_inside(m, plan, layer)) *separate_launch = 0;
+    else if (input_product_inside(m, plan, layer, T)) *separate_launch = 0;
     else *separate_launch = (layer % plan.LP == 0) ? 1 : 0;  // layers above the first of a launch are fused
     return RNN_OK;
 }

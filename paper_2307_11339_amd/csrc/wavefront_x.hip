@@ -22,7 +22,7 @@ namespace rnn {
 
 namespace {
 
-template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool XB>
+template <class TR, int CELL, int RT, int CT, int KB, int NCH>
 __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
@@ -135,13 +135,12 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // blocked layout a K block of KW units lies KW * B elements further when KW is a multiple of
     // 16; otherwise (fp32 fragments of 4 units) the offset is computed per load.
     constexpr bool LINEAR_K = (KW % 16) == 0;
-    uint32_t hoff[NCH][CT], xoff[NCH][CT];
+    uint32_t hoff[NCH][CT];
 #pragma unroll
     for (int c = 0; c < NCH; ++c)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], B) * sizeof(elem));
-            xoff[c][ct] = XB ? hoff[c][ct] : (uint32_t)(((size_t)bcol[c][ct] * H + kbase) * sizeof(elem));
         }
     auto blocked_ptr = [&](const elem* step, int c, int ct, int kb) -> const elem* {
         const int kr = (kb + rot_k) & (KB - 1);
@@ -155,17 +154,10 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(blocked_ptr(hprev, c, ct, kb));
     };
-    auto load_x = [&](int c, int s, int kb) {  // K block kb of x at step s
+    auto load_x = [&](int c, int s, int kb) {  // K block kb of x at step s (same layout as the state)
         const elem* xs = xin + (size_t)min(s, T - 1) * B * H;
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            if (XB)
-                xbuf[kb][ct] = TR::load(blocked_ptr(xs, c, ct, kb));
-            else
-                xbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
-                    reinterpret_cast<const char*>(xs) + (size_t)((kb + rot_k) & (KB - 1)) * KW * sizeof(elem) +
-                    xoff[c][ct]));
-        }
+        for (int ct = 0; ct < CT; ++ct) xbuf[kb][ct] = TR::load(blocked_ptr(xs, c, ct, kb));
     };
     // wave 0: flag word of the chain step whose stores are still to be acknowledged
     uint64_t* pend_flag = nullptr;
@@ -245,9 +237,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     for (int c = 0; c < NCH; ++c) {
         const int col0 = (cbg * NCH + c) * CT * 16;
         const int line = min(pf_idx + per_xcd * lane, NLINES * (H / 16) - 1);
-        const int per_row = H / LINE;
-        const size_t off = XB ? ((size_t)(line / NLINES) * B + col0) * 16 + (size_t)(line % NLINES) * LINE
-                              : (size_t)min(col0 + line / per_row, B - 1) * H + (size_t)(line % per_row) * LINE;
+        const size_t off = ((size_t)(line / NLINES) * B + col0) * 16 + (size_t)(line % NLINES) * LINE;
         pf_off[c] = (uint32_t)(min(off, (size_t)B * H - 1) & ~(size_t)(LINE - 1));
     }
     auto touch_x = [&](int c, int s) -> uint32_t {
@@ -414,6 +404,28 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         }
 }
 
+// [rows of H elements] -> blocked by 16 elements: dst[t][H/16][B][16] from src[t][B][H].  One
+// workgroup moves 16 sequences of one step through LDS, so that it reads whole rows and writes
+// runs of 16 sequences x 16 units (both sides in whole cache lines).  ES = element size in bytes.
+template <int ES>
+__global__ __launch_bounds__(256) void to_blocked_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                          int B, int H) {
+    extern __shared__ uint4 tile[];                 // [16 sequences][U] 16-byte units
+    const int U = H * ES / 16;                      // 16-byte units per row
+    const int t = blockIdx.y, b0 = blockIdx.x * 16;
+    const int nb = min(16, B - b0);
+    for (int i = threadIdx.x; i < nb * U; i += 256) {
+        const int r = i / U, u = i - r * U;
+        tile[r * U + u] = src[((size_t)t * B + b0 + r) * U + u];
+    }
+    __syncthreads();
+    // output order: [block of 16 units][sequence][ES units of 16 bytes]
+    for (int i = threadIdx.x; i < 16 * U; i += 256) {
+        const int q = i % ES, r = (i / ES) % 16, blk = i / (ES * 16);
+        if (r < nb) dst[(((size_t)t * (H / 16) + blk) * B + b0 + r) * ES + q] = tile[r * U + blk * ES + q];
+    }
+}
+
 template <class TR, int RT, int CT, int KB>
 constexpr size_t lds_bytes() {
     return (size_t)4 * RT * CT * 64 * sizeof(f32x4) + (size_t)4 * RT * KB * 64 * sizeof(typename TR::frag);
@@ -432,14 +444,14 @@ int device_lds_limit() {
     return limit;
 }
 
-template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool XB>
+template <class TR, int CELL, int RT, int CT, int KB, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
     if ((size_t)a.B * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
     const int grid = a.nrb * (a.ncb / NCH);
     constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
-    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, XB>;
+    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -465,11 +477,8 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
 
 template <class TR, int RT, int CT, int KB, int NCH>
 hipError_t launch_cell(const WavefrontArgs& a, hipStream_t stream) {
-    if (a.cell == CELL_LSTM)
-        return a.xin_blocked ? launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, true>(a, stream)
-                             : launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, false>(a, stream);
-    return a.xin_blocked ? launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, true>(a, stream)
-                         : launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, false>(a, stream);
+    if (a.cell == CELL_LSTM) return launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH>(a, stream);
+    return launch_variant<TR, CELL_GRU, RT, CT, KB, NCH>(a, stream);
 }
 
 // (dtype, RT, CT, KB, NCH) combinations that are compiled: the same shapes as the flag-vector
@@ -496,6 +505,19 @@ bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H) {
     RNN_WFX_VARIANTS(X)
 #undef X
     return false;
+}
+
+hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int H, hipStream_t stream) {
+    const int es = dtype == DT_BF16 ? 2 : 4;
+    if (H % 16 != 0 || T < 1 || B < 1 || T > 65535) return hipErrorInvalidValue;
+    const size_t smem = (size_t)16 * H * es;
+    if (smem > 64 * 1024) return hipErrorInvalidValue;
+    const dim3 grid((B + 15) / 16, T);
+    if (es == 2)
+        to_blocked_kernel<2><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, H);
+    else
+        to_blocked_kernel<4><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, H);
+    return hipGetLastError();
 }
 
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream) {
