@@ -162,6 +162,10 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // wave 0: flag word of the chain step whose stores are still to be acknowledged
     uint64_t* pend_flag = nullptr;
     int pend_step = 0, pend_chain = 0;
+    // Word touched by the L2 prefetch of x (wave 0).  Nothing uses it, but its register must stay
+    // reserved until the load has returned: the empty asm that "uses" it sits behind a wait that
+    // has covered the load anyway, so that it never causes a wait of its own.
+    uint32_t pf = 0;
     auto store_pending_flag = [&](int loads_behind) {
         if (pend_flag != nullptr) {
             if (loads_behind == 0) {
@@ -172,6 +176,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
             }
             asm volatile("" ::: "memory");
+            asm volatile("" ::"v"(pf));
             if (lane == 0) {
                 st_dev_u64(pend_flag, ((uint64_t)epoch << 32) | (uint32_t)pend_step);
                 if (p.ticks && rb == 0 && cbg == 0 && pend_chain == 0) p.ticks[pend_step] = wall_clock64();
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct)
                     acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
-            if (NCH > 1 && kb == KB / 4 && w == 0) store_pending_flag(1);
+            if (NCH > 1 && kb == KB / 8 && w == 0) store_pending_flag(1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -214,9 +219,11 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
-            // half way through, the flag word this lane will poll is requested: by then it has
-            // usually become visible, and its round trip hides behind the remaining instructions
-            if (kb == (3 * KB) / 4) seen = ld_dev_u64(flag);
+            // a little past half way the flag word this lane will poll is requested: by then it has
+            // usually become visible (measured: earlier and the check fails too often, later and
+            // the word comes back behind too many x fragments), and its round trip hides behind
+            // the remaining instructions
+            if (kb == (5 * KB) / 8) seen = ld_dev_u64(flag);
             load_x(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -263,7 +270,6 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             // the chain step after this one
             const int cn = (c + 1 < NCH) ? c + 1 : 0;
             const int sn = (c + 1 < NCH) ? s : s + 1;
-            uint32_t pf = 0;
 
             if (NCH > 1) {
                 // Input part first.  The flags this chain step will poll (those of the chain step
@@ -368,9 +374,9 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             if (NCH > 1) {
                 // The state of the next chain step (its flags have been seen) is requested behind the
                 // stores.  Memory operations complete in order, so once only these KB * CT loads are
-                // outstanding every store has been acknowledged; wave 0 checks that half way through
-                // the input part of the next chain step, where it no longer has to wait, and stores
-                // the flag word there.
+                // outstanding every store has been acknowledged; wave 0 checks that early in the input
+                // part of the next chain step, where it hardly has to wait any more, and stores the
+                // flag word there.
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) load_h(cn, sn, kb);
@@ -386,7 +392,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     if (p.ticks && rb == 0 && cbg == 0) p.ticks[s] = wall_clock64();
                 }
             }
-            asm volatile("" ::"v"(pf));  // the touched word is not used
+            if (NCH == 1) asm volatile("" ::"v"(pf));
         }
     }
     if (NCH > 1 && w == 0) store_pending_flag(0);
