@@ -263,7 +263,9 @@ def main() -> int:
         grid = {}
         for c in W_paper_grid():
             _, r = time_workload(c, steps=30, warmup=3, per_call=30)
-            grid[c.name] = {"p50_ms": round(r["p50_ms"], 4), "ms_per_call": round(r["ms_per_step"], 4)}
+            # latency and device memory (weights + workspace), the two quantities of the paper's Table 6
+            grid[c.name] = {"p50_ms": round(r["p50_ms"], 4), "ms_per_call": round(r["ms_per_step"], 4),
+                            "device_mb": round(r["device_bytes"] / 1e6, 3)}
         line["paper_grid"] = grid
 
     if not args.no_cpu:

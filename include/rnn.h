@@ -94,8 +94,11 @@ void rnn_model_destroy(rnn_model* model);
  * shape cannot run under that plan. */
 int rnn_model_set_plan(rnn_model* model, int plan);
 
-/* Size the workspace for sequences of up to T steps and B sequences now, so that later
- * rnn_forward calls within these limits allocate nothing.  May synchronise the device. */
+/* Size the workspace now for forwards of T steps and B sequences under the current plan, so that
+ * later rnn_forward calls of that shape allocate nothing.  Only what the plan chosen for (T, B)
+ * touches is allocated (the paper's memory model, Section 3, Equation 4, counts exactly such
+ * temporaries); a call of another shape may be given another plan and then grows the workspace
+ * itself.  Buffers never shrink.  May synchronise the device. */
 int rnn_model_reserve(rnn_model* model, int T, int B);
 
 /*
@@ -113,8 +116,8 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  *   T, B                               steps and sequences in this call (>= 1)
  *   stream                             hipStream_t passed as void* (NULL = the default stream)
  * The call enqueues work on `stream` and returns without waiting; outputs are valid once the
- * stream has reached the end of that work.  It allocates device memory only if T or B exceed
- * what earlier calls or rnn_model_reserve sized the workspace for (then it synchronises).
+ * stream has reached the end of that work.  It allocates device memory only if this shape needs
+ * more workspace than earlier calls or rnn_model_reserve provided (then it synchronises).
  * x and y must not overlap.  Inputs are not validated on the device beyond the clamping above.
  */
 int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,

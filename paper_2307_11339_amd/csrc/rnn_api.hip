@@ -38,8 +38,6 @@ struct rnn_model {
     std::vector<DevBuf> wih, whh, bias;
     size_t weight_bytes = 0;
 
-    // workspace, sized for (T_res, B_res)
-    int T_res = 0, B_res = 0;
     DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
     DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
     DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
@@ -86,44 +84,9 @@ void free_workspace(rnn_model* m) {
     dev_free(m->lseq);
     dev_free(m->xblk);
     m->workspace_bytes = 0;
-    m->T_res = m->B_res = 0;
 }
 
 constexpr int FLAG_COLBLOCKS_MAX = 16;
-
-int alloc_workspace(rnn_model* m, int T, int B) {
-    free_workspace(m);
-    const size_t rows = (size_t)T * B;
-    const size_t state = (size_t)m->L * m->D * B * m->H;
-    int rc = RNN_OK;
-    auto get = [&](DevBuf& b, size_t bytes) {
-        if (rc == RNN_OK) {
-            rc = dev_alloc(b, bytes);
-            if (rc == RNN_OK) m->workspace_bytes += bytes;
-        }
-    };
-    get(m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
-    m->ybuf.resize(m->L > 1 ? m->L - 1 : 0);
-    for (auto& b : m->ybuf) get(b, rows * m->D * m->H * m->esize);
-    get(m->hseq, state * (size_t)(T + 1) * m->esize);
-    // one flag word per (layer, direction, step, workgroup of that group); at most num_cus
-    // workgroups per launch
-    get(m->flags, (size_t)m->L * m->D * T * (size_t)(m->num_cus > 256 ? m->num_cus : 256) * sizeof(uint64_t));
-    if (rc == RNN_OK && hipMemset(m->flags.p, 0, m->flags.bytes) != hipSuccess) rc = RNN_EDEVICE;
-    get(m->h_f32, state * sizeof(float));
-    get(m->c_f32, state * sizeof(float));
-    get(m->h_st, state * m->esize);
-    get(m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
-    get(m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
-    if (m->D == 1 && m->I == m->H) get(m->xblk, rows * m->H * m->esize);
-    if (rc != RNN_OK) {
-        free_workspace(m);
-        return rc;
-    }
-    m->T_res = T;
-    m->B_res = B;
-    return RNN_OK;
-}
 
 // Choose how the grid of cells is laid over the compute units for batch size B.
 bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
@@ -264,18 +227,18 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
     return RNN_OK;
 }
 
-// Make sure the tagged state sequences hold `words` 8-byte words.  Fresh memory is cleared once:
-// tag 0 is never used by a launch.
-int ensure_lseq(rnn_model* m, size_t words) {
-    const size_t bytes = words * sizeof(uint64_t);
-    if (m->lseq.bytes >= bytes) return RNN_OK;
+// Grow a workspace buffer to at least `bytes` (never shrinks).  Growing waits for the device, since
+// work in flight may still use the old buffer.  `zeroed`: fresh memory is cleared once (flag words
+// and tagged words: tag 0 is never used by a launch).
+int grow(rnn_model* m, DevBuf& b, size_t bytes, bool zeroed = false) {
+    if (b.bytes >= bytes) return RNN_OK;
     HIP_TRY(hipDeviceSynchronize());
-    m->workspace_bytes -= m->lseq.bytes;
-    dev_free(m->lseq);
-    const int rc = dev_alloc(m->lseq, bytes);
+    m->workspace_bytes -= b.bytes;
+    dev_free(b);
+    const int rc = dev_alloc(b, bytes);
     if (rc != RNN_OK) return rc;
     m->workspace_bytes += bytes;
-    HIP_TRY(hipMemset(m->lseq.p, 0, bytes));
+    if (zeroed) HIP_TRY(hipMemset(b.p, 0, bytes));
     return RNN_OK;
 }
 
@@ -295,7 +258,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     const bool tagged = plan.CT == 1 && plan.NCH == 1;
     if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
         if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
-        HIP_TRY(hipMemsetAsync(m->flags.p, 0, m->flags.bytes, st));
+        if (m->flags.p) HIP_TRY(hipMemsetAsync(m->flags.p, 0, m->flags.bytes, st));
         m->epoch = 1;
     }
     if (tagged) {
@@ -350,6 +313,44 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
     return plan.kind == RNN_PLAN_WAVEFRONT && plan.LP == 1 && m->D == 1 &&
            !(plan.CT == 1 && plan.NCH == 1) && m->layer_input(l) == m->H &&
            wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
+}
+
+// Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
+// plan touches is allocated (the paper's memory model, Section 3, Equation 4, charges a model with
+// its weights, outputs and temporaries; this is the temporaries part).
+int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
+    const size_t rows = (size_t)T * B;
+    const size_t state = (size_t)m->L * m->D * B * m->H;
+    const bool wavefront = plan.kind == RNN_PLAN_WAVEFRONT;
+    const bool tagged = wavefront && plan.CT == 1 && plan.NCH == 1;
+    bool any_projection = !wavefront;
+    if ((int)m->ybuf.size() < m->L - 1) m->ybuf.resize(m->L - 1);
+    int rc = RNN_OK;
+    for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
+        const bool inside = wavefront && input_product_inside(m, plan, l, T);
+        if (!inside && (!wavefront || l % plan.LP == 0)) any_projection = true;
+        // a layer keeps an output of its own unless its consumer reads its state sequence instead
+        if (l + 1 < m->L && !inside) rc = grow(m, m->ybuf[l], rows * m->D * m->H * m->esize);
+    }
+    if (rc == RNN_OK && any_projection) rc = grow(m, m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
+    if (rc == RNN_OK && wavefront && !tagged) {
+        rc = grow(m, m->hseq, state * (size_t)(T + 1) * m->esize);
+        // one flag word per (layer, direction, step, workgroup of that group); at most num_cus per launch
+        if (rc == RNN_OK)
+            rc = grow(m, m->flags, (size_t)m->L * m->D * T * (size_t)(m->num_cus > 256 ? m->num_cus : 256) * sizeof(uint64_t),
+                      true);
+        if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->xblk, rows * m->H * m->esize);
+    }
+    if (rc == RNN_OK && tagged)
+        rc = grow(m, m->lseq, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H) * sizeof(uint64_t), true);
+    if (rc == RNN_OK && !wavefront) {
+        rc = grow(m, m->h_f32, state * sizeof(float));
+        if (rc == RNN_OK) rc = grow(m, m->c_f32, state * sizeof(float));
+        if (rc == RNN_OK) rc = grow(m, m->h_st, state * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
+    }
+    if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    return rc;
 }
 
 int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
@@ -528,33 +529,23 @@ int rnn_model_set_plan(rnn_model* m, int plan) {
 
 int rnn_model_reserve(rnn_model* m, int T, int B) {
     if (!m || T < 1 || B < 1) return RNN_EINVAL;
-    if (T <= m->T_res && B <= m->B_res) return RNN_OK;
-    if (hipDeviceSynchronize() != hipSuccess) { (void)hipGetLastError(); return RNN_EDEVICE; }
-    const int Tn = T > m->T_res ? T : m->T_res, Bn = B > m->B_res ? B : m->B_res;
-    int rc = alloc_workspace(m, Tn, Bn);
-    if (rc != RNN_OK) return rc;
     Plan plan;
-    if (resolve_plan(m, Tn, Bn, plan) != RNN_OK) return rc;
-    if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 && plan.NCH == 1)
-        rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, Tn, Bn, m->H));
-    return rc;
+    const int rc = resolve_plan(m, T, B, plan);
+    if (rc != RNN_OK) return rc;
+    return prepare_workspace(m, plan, T, B);
 }
 
 int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
                 const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
     if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
     if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
-    int rc = rnn_model_reserve(m, T, B);
-    if (rc != RNN_OK) return rc;
     Plan plan;
-    rc = resolve_plan(m, T, B, plan);
+    int rc = resolve_plan(m, T, B, plan);
+    if (rc != RNN_OK) return rc;
+    rc = prepare_workspace(m, plan, T, B);   // no-op when rnn_model_reserve has seen this shape and plan
     if (rc != RNN_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
-    if (plan.kind == RNN_PLAN_WAVEFRONT && plan.CT == 1 && plan.NCH == 1) {
-        rc = ensure_lseq(m, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H));
-        if (rc != RNN_OK) return rc;
-    }
     if (plan.kind == RNN_PLAN_WAVEFRONT)
         return forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
     return forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);

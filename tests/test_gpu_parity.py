@@ -205,6 +205,38 @@ def test_error_codes(gpu):
     model.close()
 
 
+def test_workspace_follows_the_plan(gpu):
+    """The workspace holds what the plan of the current shape touches; a call of another shape that gets
+    another plan grows it, and going back gives the first result again, bit for bit."""
+    import torch
+    harness, rnn, W = gpu
+    by_name = {s[0]: s for s in SMALL}
+    wl = _small_workload(W, by_name["lstm_bf16_inside_sq"])      # batch 500: one layer per launch, product inside
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io = harness.DeviceIO(wl)
+    c = wl.cfg
+    assert rnn.rnn_model_reserve(model.handle, c.T, c.B) == rnn.RNN_OK
+    bytes_large = rnn.rnn_model_device_bytes(model.handle)
+    # no projection buffer (T*B*4H fp32) and no inter-layer output buffer were allocated for this plan
+    assert bytes_large < c.T * c.B * 4 * c.H * 4
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    y_first = io.y.clone()
+    # the same model on 3 sequences runs both layers in one launch of the tag-in-data kernel
+    small = wl.take_batch(np.arange(3))
+    io_small = harness.DeviceIO(small)
+    harness.forward(model, io_small)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    assert rnn.rnn_model_device_bytes(model.handle) > bytes_large          # grew: projection, tagged sequences
+    # the same sequences under another plan (another kernel, another summation order): equal within the bf16 tolerance
+    assert float((io_small.y.float() - y_first[:, :3].float()).abs().max()) <= 2e-2
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert torch.equal(io.y, y_first)
+    model.close()
+
+
 def test_input_product_placement(gpu):
     """Which kernel performs W_ih x_t, per layer, as the library reports it."""
     harness, rnn, W = gpu
