@@ -86,6 +86,20 @@ int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, 
                      int num_directions, int dtype, const void* const* weights,
                      int weights_on_device);
 
+/* Order of the gate row blocks inside the caller's W_ih, W_hh and bias arrays.
+ *   RNN_ORDER_IFGO_RZN  LSTM i,f,g,o; GRU r,z,n (what rnn_model_create assumes).
+ *   RNN_ORDER_ONNX      LSTM i,o,f,c; GRU z,r,h: the order of the ONNX operator set, the file
+ *                       format the paper's system takes its models in (Section 1; Section 4.1). */
+enum rnn_gate_order { RNN_ORDER_IFGO_RZN = 0, RNN_ORDER_ONNX = 1 };
+
+/* rnn_model_create for weights whose gate row blocks are in `gate_order` (rnn_gate_order); every
+ * other argument, the array list (l, d, {W_ih, W_hh, b_ih, b_hh}) and the error behaviour are those
+ * of rnn_model_create.  Only the order of the row blocks differs; the GRU computed is the same
+ * (reset gate applied after the recurrent product).  RNN_EINVAL for an unknown order. */
+int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
+                             int num_directions, int dtype, const void* const* weights,
+                             int weights_on_device, int gate_order);
+
 /* Free the model, its device weights and its workspace.  NULL is accepted.  The caller must
  * have synchronised any stream that still runs a forward of this model. */
 void rnn_model_destroy(rnn_model* model);

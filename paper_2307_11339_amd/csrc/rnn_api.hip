@@ -146,9 +146,16 @@ int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
 }
 
 // Gate row of the caller's [G*H, K] matrix that feeds slot s of unit u; -1 = no row (zeros).
-int source_row(int cell, bool recurrent, int H, int u, int s) {
-    if (cell == CELL_LSTM) return s * H + u;           // i, f, g, o
-    if (s < 2) return s * H + u;                        // r, z
+// order: rnn_gate_order of the caller's row blocks.
+int source_row(int cell, bool recurrent, int H, int u, int s, int order) {
+    if (cell == CELL_LSTM) {                            // slots i, f, g, o
+        static const int onnx_block[4] = {0, 2, 3, 1};  // ONNX row blocks are i, o, f, c
+        return (order == RNN_ORDER_ONNX ? onnx_block[s] : s) * H + u;
+    }
+    const int r_blk = order == RNN_ORDER_ONNX ? 1 : 0;  // ONNX row blocks are z, r, h
+    const int z_blk = order == RNN_ORDER_ONNX ? 0 : 1;
+    if (s == 0) return r_blk * H + u;
+    if (s == 1) return z_blk * H + u;
     if (s == 2) return recurrent ? -1 : 2 * H + u;      // n_x: input part of the candidate
     return recurrent ? 2 * H + u : -1;                  // n_h: recurrent part of the candidate
 }
@@ -387,7 +394,15 @@ extern "C" {
 int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
                      int num_directions, int dtype, const void* const* weights,
                      int weights_on_device) {
+    return rnn_model_create_ordered(out, cell, num_layers, input_size, hidden_size, num_directions, dtype,
+                                    weights, weights_on_device, RNN_ORDER_IFGO_RZN);
+}
+
+int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
+                             int num_directions, int dtype, const void* const* weights,
+                             int weights_on_device, int gate_order) {
     if (!out || !weights) return RNN_EINVAL;
+    if (gate_order != RNN_ORDER_IFGO_RZN && gate_order != RNN_ORDER_ONNX) return RNN_EINVAL;
     if (cell != RNN_LSTM && cell != RNN_GRU) return RNN_EINVAL;
     if (dtype != RNN_F32 && dtype != RNN_BF16) return RNN_EINVAL;
     if (num_layers < 1 || input_size < 1 || hidden_size < 1) return RNN_EINVAL;
@@ -436,7 +451,7 @@ int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, 
         const size_t rowb = (size_t)K * m->esize;
         for (int u = 0; u < H; ++u)
             for (int sl = 0; sl < SLOTS; ++sl) {
-                const int r = source_row(cell, recurrent, H, u, sl);
+                const int r = source_row(cell, recurrent, H, u, sl, gate_order);
                 unsigned char* d = dst + ((size_t)u * SLOTS + sl) * rowb;
                 if (r < 0) memset(d, 0, rowb);
                 else memcpy(d, s + (size_t)r * rowb, rowb);
@@ -478,8 +493,8 @@ int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, 
             }
             for (int u = 0; u < H; ++u)
                 for (int sl = 0; sl < SLOTS; ++sl) {
-                    const int ri = source_row(cell, false, H, u, sl);
-                    const int rh = source_row(cell, true, H, u, sl);
+                    const int ri = source_row(cell, false, H, u, sl, gate_order);
+                    const int rh = source_row(cell, true, H, u, sl, gate_order);
                     float v = 0.0f;
                     if (ri >= 0) v += elem_to_f32(bi.data(), ri, dtype);
                     if (rh >= 0) v += elem_to_f32(bh.data(), rh, dtype);

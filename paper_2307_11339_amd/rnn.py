@@ -20,13 +20,14 @@ RNN_LSTM, RNN_GRU = 0, 1
 RNN_F32, RNN_BF16 = 0, 1
 RNN_OK, RNN_EINVAL, RNN_EUNSUPPORTED, RNN_ENOMEM, RNN_EDEVICE = 0, 1, 2, 3, 4
 RNN_PLAN_AUTO, RNN_PLAN_CELLWISE, RNN_PLAN_WAVEFRONT = 0, 1, 2
+RNN_ORDER_IFGO_RZN, RNN_ORDER_ONNX = 0, 1
 RNN_KERNEL_PROJECTION, RNN_KERNEL_RECURRENT = 0, 1
 RNN_PROFILE_KERNELS, RNN_PROFILE_STEP_TICKS = 1, 2
 
 EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_model_reserve",
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
-           "rnn_model_read_step_ticks", "rnn_model_input_product_placement")
+           "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered")
 
 _lib = None
 
@@ -49,6 +50,8 @@ def load_library() -> ctypes.CDLL:
     vp, ci = ctypes.c_void_p, ctypes.c_int
     lib.rnn_model_create.restype = ci
     lib.rnn_model_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp), ci]
+    lib.rnn_model_create_ordered.restype = ci
+    lib.rnn_model_create_ordered.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp), ci, ci]
     lib.rnn_model_destroy.restype = None
     lib.rnn_model_destroy.argtypes = [vp]
     lib.rnn_model_set_plan.restype = ci
@@ -106,6 +109,22 @@ def rnn_model_create(cell: int, num_layers: int, input_size: int, hidden_size: i
                               num_directions, dtype, arr, weights_on_device)
     if rc != RNN_OK:
         raise RnnError(rc, "rnn_model_create")
+    return out.value
+
+
+def rnn_model_create_ordered(cell: int, num_layers: int, input_size: int, hidden_size: int,
+                             num_directions: int, dtype: int, weights: Sequence, weights_on_device: int,
+                             gate_order: int) -> int:
+    """rnn_model_create for weights whose gate row blocks are in `gate_order`.  Returns the handle."""
+    lib = load_library()
+    n = num_layers * num_directions * 4
+    assert len(weights) == n
+    arr = (ctypes.c_void_p * n)(*[_ptr(w) for w in weights])
+    out = ctypes.c_void_p()
+    rc = lib.rnn_model_create_ordered(ctypes.byref(out), cell, num_layers, input_size, hidden_size,
+                                      num_directions, dtype, arr, weights_on_device, gate_order)
+    if rc != RNN_OK:
+        raise RnnError(rc, "rnn_model_create_ordered")
     return out.value
 
 

@@ -205,6 +205,39 @@ def test_error_codes(gpu):
     model.close()
 
 
+@pytest.mark.parametrize("cell", [0, 1], ids=["lstm", "gru"])
+def test_onnx_gate_order(gpu, oracle, cell):
+    """Weights whose gate row blocks come in the order of the ONNX operators (LSTM i,o,f,c; GRU z,r,h)
+    give, after rnn_model_create_ordered, what the same weights in i,f,g,o / r,z,n order give: checked
+    against the oracle (which only knows the latter order) and bit for bit against rnn_model_create."""
+    import torch
+    harness, rnn, W = gpu
+    spec = ("order_test", cell, 2, 2, 40, 128, 7, 9, 1, True, True)
+    wl = _small_workload(W, spec)
+    c = wl.cfg
+    H = c.H
+    blocks = [0, 3, 1, 2] if cell == 0 else [1, 0, 2]      # ONNX block j holds our block blocks[j]
+    permuted = []
+    for w in wl.weights:
+        rows = w.reshape(c.G, H, -1) if w.ndim == 2 else w.reshape(c.G, H)
+        permuted.append(np.ascontiguousarray(rows[blocks].reshape(w.shape)))
+    dev = [harness.to_device_storage(w, c.dtype) for w in permuted]
+    handle = rnn.rnn_model_create_ordered(c.cell, c.L, c.I, c.H, c.D, c.dtype, dev, 1, rnn.RNN_ORDER_ONNX)
+    ref_model = harness.DeviceModel(wl)
+    io_ref, io = harness.DeviceIO(wl), harness.DeviceIO(wl)
+    harness.forward(ref_model, io_ref)
+    lengths = io.lengths
+    assert rnn.rnn_forward(handle, io.x, lengths, io.h0, io.c0, io.y, io.hT, io.cT, c.T, c.B, None) == rnn.RNN_OK
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(handle) == rnn.RNN_OK
+    assert torch.equal(io.y, io_ref.y) and torch.equal(io.hT, io_ref.hT)
+    _check(harness, wl, io, oracle.forward_workload(wl, nthreads=8))
+    with pytest.raises(rnn.RnnError):
+        rnn.rnn_model_create_ordered(c.cell, c.L, c.I, c.H, c.D, c.dtype, dev, 1, 7)
+    rnn.rnn_model_destroy(handle)
+    ref_model.close()
+
+
 def test_workspace_follows_the_plan(gpu):
     """The workspace holds what the plan of the current shape touches; a call of another shape that gets
     another plan grows it, and going back gives the first result again, bit for bit."""
