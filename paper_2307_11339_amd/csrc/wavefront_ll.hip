@@ -254,17 +254,28 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     const int out_ld = p.D * H;
     bool aborted = false;
 
-    for (int s = 0; s < T; ++s) {
-        const int t = d ? (T - 1 - s) : s;
-
-        f32x4 gx_reg[NOWN];
+    // Projection of a step for the pairs this lane finishes.  It is requested one step ahead, right
+    // after the last poll of a step: loads return in order, so a request to HBM issued just before a
+    // poll would hold back the poll's result for its whole latency; issued here it has the exchange,
+    // the gates and the publication to travel.  Never predicated (indices are clamped), so that the
+    // compiler can count the loads in flight.
+    f32x4 gx_reg[NOWN];
+    auto fetch_gx = [&](int s) {
+        const int sc = min(s, T - 1);
+        const int tt = d ? (T - 1 - sc) : sc;
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
-            gx_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if (!fused && (w + 4 * o) < RT && valid)
-                gx_reg[o] = *reinterpret_cast<const f32x4*>(
-                    p.gx + ((((size_t)t * B + col) * p.D + d) * H + unit_reg[o]) * SLOTS);
+            const int unit = min(unit_reg[o], H - 1);
+            gx_reg[o] = *reinterpret_cast<const f32x4*>(p.gx + ((((size_t)tt * B + colc) * p.D + d) * H + unit) * SLOTS);
         }
+    };
+    // (In a launch with fused layers the first layer sets the pace of all of them and was measured
+    // faster with the request at the top of the step, as it always was there.)
+    if (!FUSED) fetch_gx(0);
+
+    for (int s = 0; s < T; ++s) {
+        const int t = d ? (T - 1 - s) : s;
+        if (FUSED && !fused) fetch_gx(s);
 
         f32x4 acc[RT];
 #pragma unroll
@@ -282,6 +293,10 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
 
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) red[(((s & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+        f32x4 gx_now[NOWN];
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) gx_now[o] = gx_reg[o];
+        if (!FUSED) fetch_gx(s + 1);
         __syncthreads();
 
 #pragma unroll
@@ -291,7 +306,7 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
                 f32x4 a = red[(((s & 1) * 4 + 0) * RT + rt) * 64 + lane];
 #pragma unroll
                 for (int q = 1; q < 4; ++q) a += red[(((s & 1) * 4 + q) * RT + rt) * 64 + lane];
-                a += gx_reg[o];
+                if (!fused) a += gx_now[o];
                 a += bias_reg[o];
                 const bool active = valid && t < len;
                 float c_new = c_reg[o];
