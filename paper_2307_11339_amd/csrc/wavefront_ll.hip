@@ -299,13 +299,19 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
         if (!FUSED) fetch_gx(s + 1);
         __syncthreads();
 
+        // all partial sums this wave needs are read before the first is used (one LDS round trip)
+        f32x4 part[NOWN][4];
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                part[o][q] = red[(((s & 1) * 4 + q) * RT + min(w + 4 * o, RT - 1)) * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int rt = w + 4 * o;
             if (rt < RT) {  // uniform per wave
-                f32x4 a = red[(((s & 1) * 4 + 0) * RT + rt) * 64 + lane];
-#pragma unroll
-                for (int q = 1; q < 4; ++q) a += red[(((s & 1) * 4 + q) * RT + rt) * 64 + lane];
+                f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
                 if (!fused) a += gx_now[o];
                 a += bias_reg[o];
                 const bool active = valid && t < len;
