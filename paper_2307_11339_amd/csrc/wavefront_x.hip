@@ -1,6 +1,7 @@
 // Persistent kernel for one layer whose input sequence is complete before the launch and has the
-// layer's own width (every layer above the first of a unidirectional stack): the input product
-// W_ih x_t runs inside the recurrent kernel, so the projection never goes through HBM as fp32.
+// layer's own width (every layer above the first of a unidirectional stack, and the first when its
+// input is H wide): the input product W_ih x_t runs inside the recurrent kernel, cell by cell, as in
+// the paper's cell (Section 2.2), so the projection never goes through HBM as fp32.
 //
 // Same decomposition and step protocol as the flag-vector kernel (a workgroup owns RT*4 hidden
 // units for NCH chains of CT*16 sequences, the four waves split K, a vector of flag words per
@@ -9,13 +10,17 @@
 //     fragment by fragment exactly as the MFMA reads its A operand (each wave reads back only what
 //     it wrote itself); W_hh stays in registers, because the recurrent product is the part of a
 //     step that sits on the dependency chain;
-//   - x_t needs no flags.  Its fragments for the next chain step are requested right after the
-//     state fragments of that chain step (loads return in order: the state is asked for first
-//     because it is consumed first), and they are multiplied at the top of the chain step, where
-//     the state fragments may still be on their way.
-// With the projection kernel's fp32 output (16 bytes per unit and sequence, fetched in scattered
-// 64-byte pieces that the matrix instructions then had to wait for) gone, a step reads 2 bytes per
-// input element instead.
+//   - x has the layout of a state sequence (blocked by 16 units): a layer above the first reads
+//     the state sequence of the layer below directly (and a layer that is not the last keeps no
+//     other output), the first layer reads a re-laid-out copy of the caller's x.  Fragment loads
+//     then ask for whole cache lines; the CU's path to L2 is bound by requests, not bytes;
+//   - x_t needs no flags: with several chains, a chain step does its input part first (its
+//     fragments were requested during the previous chain step) while the flags it will need
+//     become visible, then the recurrent part;
+//   - one wave writes a chain step to memory, from LDS, in whole cache lines, and is the only
+//     one that needs a store acknowledged; it checks for the acknowledgement with a counted wait
+//     (loads requested behind the stores stay in flight) early in the next chain step and stores
+//     the flag word there.
 #include "wf_traits.h"
 
 namespace rnn {

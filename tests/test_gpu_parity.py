@@ -74,6 +74,9 @@ SMALL = [
     ("lstm_bf16_inside_sq", 0, 2, 1, 512, 512, 21, 500, 1, True, True),  # I == H: no projection launch; ragged batch tail
     ("gru_bf16_inside_sq", 1, 2, 1, 512, 512, 17, 512, 1, True, False),
     ("lstm_f32_inside_sq", 0, 2, 1, 128, 128, 9, 512, 0, True, True),
+    ("lstm_bf16_inside_t1", 0, 2, 1, 512, 512, 1, 512, 1, False, True),    # a single step: nothing to pipeline
+    ("gru_bf16_inside_t2", 1, 2, 1, 512, 512, 2, 497, 1, True, True),      # two steps, ragged lengths 1..2, ragged batch
+    ("lstm_bf16_inside_1layer", 0, 1, 1, 512, 512, 19, 512, 1, True, False),  # one layer: input re-laid out, output written
 ]
 
 
