@@ -108,6 +108,15 @@ void rnn_model_destroy(rnn_model* model);
  * shape cannot run under that plan. */
 int rnn_model_set_plan(rnn_model* model, int plan);
 
+/* GRU only: on = 1 selects the GRU that applies the reset gate before the candidate's recurrent
+ * product, n = tanh(W_in x + b_in + W_hn (r * h) + b_hn), the default of the ONNX operator set
+ * (the file format the paper's system takes its models in, Section 1); on = 0 (the default)
+ * applies it after the product, n = tanh(W_in x + b_in + r * (W_hn h + b_hn)).  The first form
+ * needs two dependent recurrent products per cell and runs under the cellwise plan only:
+ * RNN_EUNSUPPORTED for an LSTM model or while RNN_PLAN_WAVEFRONT is selected (and selecting that
+ * plan afterwards is refused). */
+int rnn_model_set_gru_reset_before(rnn_model* model, int on);
+
 /* Size the workspace now for forwards of T steps and B sequences under the current plan, so that
  * later rnn_forward calls of that shape allocate nothing.  Only what the plan chosen for (T, B)
  * touches is allocated (the paper's memory model, Section 3, Equation 4, counts exactly such

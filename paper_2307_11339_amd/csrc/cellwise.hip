@@ -3,7 +3,9 @@
 // The cellwise plan executes the unrolled cell grid one cell after another on one stream, the
 // regime the paper attributes to a single GPU (Section 2.2, caption of the unfolded-RNN
 // figure): per cell one recurrent product (gemm.hip, M = batch) and one launch of the kernel
-// below, which adds the projection, applies the gate functions and updates the state.
+// below, which adds the projection, applies the gate functions and updates the state.  The GRU
+// that applies the reset gate before the candidate's recurrent product needs two products per
+// cell with a pointwise kernel between them.
 #include "common.h"
 #include "kernels.h"
 
@@ -51,7 +53,16 @@ __global__ void cell_step_kernel(CellStepArgs a) {
     const float pre[SLOTS] = {gx.x + gh.x + bs.x, gx.y + gh.y + bs.y, gx.z + gh.z + bs.z,
                               gx.w + gh.w + bs.w};
     float c = a.c_f32[i];
-    float h = cell_update<CELL>(pre, a.h_f32[i], c);
+    float h;
+    if (CELL == CELL_GRU && a.gh_rh) {
+        // the candidate's recurrent part was computed from r * h_{t-1}: nothing left to scale
+        const float nh = a.gh_rh[((size_t)b * a.H + u) * SLOTS + 3] + bs.w;
+        const float z = sigmoid_f(pre[1]);
+        const float n = tanh_f(pre[2] + nh);
+        h = (1.0f - z) * n + z * a.h_f32[i];
+    } else {
+        h = cell_update<CELL>(pre, a.h_f32[i], c);
+    }
     if (DT == DT_BF16) {
         const bf16_t hb = f32_to_bf16(h);
         h = bf16_to_f32(hb);
@@ -65,7 +76,26 @@ __global__ void cell_step_kernel(CellStepArgs a) {
     a.c_f32[i] = c;
 }
 
+template <int DT>
+__global__ void gru_reset_kernel(CellStepArgs a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;  // (b, u)
+    if (i >= a.B * a.H) return;
+    const int b = i / a.H, u = i % a.H;
+    const size_t g = ((((size_t)a.t * a.B + b) * a.D + a.d) * a.H + u) * SLOTS;
+    const float r = sigmoid_f(a.gx[g] + a.gh[((size_t)b * a.H + u) * SLOTS] + a.bias[(size_t)u * SLOTS]);
+    const float rh = r * a.h_f32[i];
+    if (DT == DT_BF16) ((bf16_t*)a.rh_st)[i] = f32_to_bf16(rh);
+    else ((float*)a.rh_st)[i] = rh;
+}
+
 }  // namespace
+
+hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream) {
+    const unsigned blocks = (unsigned)(((size_t)a.B * a.H + 255) / 256);
+    if (a.dtype == DT_BF16) gru_reset_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(a);
+    else gru_reset_kernel<DT_F32><<<blocks, 256, 0, stream>>>(a);
+    return hipGetLastError();
+}
 
 hipError_t launch_state_init(int dtype, const float* h0, const float* c0, float* h_f32,
                              float* c_f32, void* h_st, size_t n, hipStream_t stream) {

@@ -26,6 +26,9 @@ struct CellStepArgs {
     int B, H, D, d, t;
     const float* gx;      // [T*B, D, H, 4] projection of this layer (no bias)
     const float* gh;      // [B, H, 4] recurrent product of this step and direction
+    const float* gh_rh;   // NULL, or (GRU with the reset gate applied before the product) [B, H, 4]
+                          // product of W_hh with r * h_{t-1}: its slot n_h replaces gh's, unscaled
+    void* rh_st;          // launch_gru_reset only: [B, H] storage type, receives r * h_{t-1}
     const float* bias;    // [H, 4]
     float* h_f32;         // [B, H] in/out
     float* c_f32;         // [B, H] in/out
@@ -35,6 +38,9 @@ struct CellStepArgs {
     int T;
 };
 hipError_t launch_cell_step(const CellStepArgs& a, hipStream_t stream);
+// GRU variant that applies the reset gate before the candidate's recurrent product: from gx, gh and
+// the bias compute r and write r * h_{t-1} (all sequences, storage type) to a.rh_st.
+hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream);
 
 // ---- persistent wavefront kernel (wavefront.hip) -------------------------------------------
 constexpr int WF_MAX_LAYERS = 16;  // layers that may run concurrently in one launch

@@ -39,6 +39,8 @@ struct rnn_model {
     size_t weight_bytes = 0;
 
     DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
+    DevBuf rh_st, gh2;      // reset-before-product GRU (cellwise plan): r * h and the second product
+    bool gru_reset_before = false;
     DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
     DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
     uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
@@ -83,6 +85,8 @@ void free_workspace(rnn_model* m) {
     m->ybuf.clear();
     dev_free(m->lseq);
     dev_free(m->xblk);
+    dev_free(m->rh_st);
+    dev_free(m->gh2);
     m->workspace_bytes = 0;
 }
 
@@ -135,7 +139,8 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
 }
 
 int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
-    if (m->requested_plan == RNN_PLAN_CELLWISE) {
+    if (m->gru_reset_before && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    if (m->requested_plan == RNN_PLAN_CELLWISE || m->gru_reset_before) {
         plan = Plan();
         return RNN_OK;
     }
@@ -225,6 +230,14 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
                 a.h_f32 = (float*)m->h_f32.p + (size_t)g * per;
                 a.c_f32 = (float*)m->c_f32.p + (size_t)g * per;
                 a.h_st = hst; a.out = out; a.lengths = lengths; a.T = T;
+                a.gh_rh = nullptr; a.rh_st = nullptr;
+                if (m->gru_reset_before) {  // r, then W_hh (r * h), whose candidate slot replaces gh's
+                    a.rh_st = m->rh_st.p;
+                    HIP_TRY(launch_gru_reset(a, st));
+                    HIP_TRY(launch_gemm_nt(m->dtype, m->rh_st.p, m->H, m->whh[g].p, m->H, (float*)m->gh2.p, N4, B,
+                                           N4, m->H, st));
+                    a.gh_rh = (const float*)m->gh2.p;
+                }
                 HIP_TRY(launch_cell_step(a, st));
             }
         }
@@ -355,6 +368,10 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
         if (rc == RNN_OK) rc = grow(m, m->c_f32, state * sizeof(float));
         if (rc == RNN_OK) rc = grow(m, m->h_st, state * m->esize);
         if (rc == RNN_OK) rc = grow(m, m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
+        if (rc == RNN_OK && m->gru_reset_before) {
+            rc = grow(m, m->rh_st, (size_t)B * m->H * m->esize);
+            if (rc == RNN_OK) rc = grow(m, m->gh2, (size_t)B * m->H * SLOTS * sizeof(float));
+        }
     }
     if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
     return rc;
@@ -536,9 +553,17 @@ int rnn_model_set_plan(rnn_model* m, int plan) {
         return RNN_EINVAL;
     if (plan == RNN_PLAN_WAVEFRONT) {
         Plan p;
-        if (!choose_wavefront(m, 1, 1, p)) return RNN_EUNSUPPORTED;
+        if (m->gru_reset_before || !choose_wavefront(m, 1, 1, p)) return RNN_EUNSUPPORTED;
     }
     m->requested_plan = plan;
+    return RNN_OK;
+}
+
+int rnn_model_set_gru_reset_before(rnn_model* m, int on) {
+    if (!m || (on != 0 && on != 1)) return RNN_EINVAL;
+    if (m->cell != CELL_GRU) return on ? RNN_EUNSUPPORTED : RNN_OK;
+    if (on && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    m->gru_reset_before = on != 0;
     return RNN_OK;
 }
 

@@ -27,7 +27,8 @@ RNN_PROFILE_KERNELS, RNN_PROFILE_STEP_TICKS = 1, 2
 EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_model_reserve",
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
-           "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered")
+           "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
+           "rnn_model_set_gru_reset_before")
 
 _lib = None
 
@@ -52,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp), ci]
     lib.rnn_model_create_ordered.restype = ci
     lib.rnn_model_create_ordered.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ci, ci, ci, ctypes.POINTER(vp), ci, ci]
+    lib.rnn_model_set_gru_reset_before.restype = ci
+    lib.rnn_model_set_gru_reset_before.argtypes = [vp, ci]
     lib.rnn_model_destroy.restype = None
     lib.rnn_model_destroy.argtypes = [vp]
     lib.rnn_model_set_plan.restype = ci
@@ -134,6 +137,10 @@ def rnn_model_destroy(model: Optional[int]) -> None:
 
 def rnn_model_set_plan(model: int, plan: int) -> int:
     return load_library().rnn_model_set_plan(model, plan)
+
+
+def rnn_model_set_gru_reset_before(model: int, on: int) -> int:
+    return load_library().rnn_model_set_gru_reset_before(model, on)
 
 
 def rnn_model_reserve(model: int, T: int, B: int) -> int:

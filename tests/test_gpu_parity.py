@@ -241,6 +241,34 @@ def test_onnx_gate_order(gpu, oracle, cell):
     ref_model.close()
 
 
+@pytest.mark.parametrize("spec", [("gru_rb_bf16", 1, 2, 2, 40, 128, 9, 21, 1, True, True),
+                                  ("gru_rb_f32", 1, 2, 1, 24, 64, 7, 5, 0, True, True)], ids=lambda s: s[0])
+def test_gru_reset_before_product(gpu, oracle, spec):
+    """The GRU that applies the reset gate before the candidate's recurrent product (the oracle's
+    variant 1, pinned by its own closed-form tests) runs under the cellwise plan."""
+    harness, rnn, W = gpu
+    wl = _small_workload(W, spec)
+    model = harness.DeviceModel(wl)
+    assert rnn.rnn_model_set_gru_reset_before(model.handle, 1) == rnn.RNN_OK
+    assert rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_EUNSUPPORTED
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    ref = oracle.forward_workload(wl, nthreads=8, gru_variant=1)
+    _check(harness, wl, io, ref)
+    # the two variants really differ on this input, and switching back gives the default again
+    other = oracle.forward_workload(wl, nthreads=8, gru_variant=0)
+    assert float(np.max(np.abs(other[0] - ref[0]))) > 5e-2
+    assert rnn.rnn_model_set_gru_reset_before(model.handle, 0) == rnn.RNN_OK
+    harness.forward(model, io)
+    _check(harness, wl, io, other)
+    model.close()
+    # an LSTM has no such variant
+    lstm = harness.DeviceModel(_small_workload(W, SMALL[0]))
+    assert rnn.rnn_model_set_gru_reset_before(lstm.handle, 1) == rnn.RNN_EUNSUPPORTED
+    assert rnn.rnn_model_set_gru_reset_before(lstm.handle, 0) == rnn.RNN_OK
+    lstm.close()
+
+
 def test_workspace_follows_the_plan(gpu):
     """The workspace holds what the plan of the current shape touches; a call of another shape that gets
     another plan grows it, and going back gives the first result again, bit for bit."""
