@@ -169,6 +169,20 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const int nfl = p.nrb / 4;
     const int fl0 = w * nfl;
 
+    // Addresses of the activation loads = uniform base of the step + uniform offset of the K block
+    // + a 32-bit per-lane offset that does not change over the launch (one register per chain and
+    // column tile; full per-load pointers do not fit beside two sets of resident weights).  In the
+    // blocked layout a K block of KW units lies KW * B elements further when KW is a multiple of
+    // 16; otherwise (fp32 fragments of 4 units) the offset is computed per load.
+    constexpr bool LINEAR_K = (KW % 16) == 0;
+    uint32_t hoff[NCH][CT], xoff[NCH][CT];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], B) * sizeof(elem));
+            xoff[c][ct] = (uint32_t)(((size_t)bcol[c][ct] * H + kbase) * sizeof(elem));
+        }
     // h_{t-1} fragments of the chain that is processed next
     frag hbuf[KB][CT];
     auto fetch_h = [&](int c, int s) {  // wait for step s-1 of chain c, then request its state
@@ -178,9 +192,15 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
         const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            const int k = kbase + ((kb + rot_k) & (KB - 1)) * KW;
+            const int kr = (kb + rot_k) & (KB - 1);
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(hprev + hseq_off(k, bcol[c][ct], B));
+            for (int ct = 0; ct < CT; ++ct) {
+                if (LINEAR_K)
+                    hbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
+                        reinterpret_cast<const char*>(hprev) + (size_t)kr * KW * B * sizeof(elem) + hoff[c][ct]));
+                else
+                    hbuf[kb][ct] = TR::load(hprev + hseq_off(kbase + kr * KW, bcol[c][ct], B));
+            }
         }
     };
     if (NCH > 1) fetch_h(0, 0);
@@ -210,11 +230,14 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                 if (fused) {  // x_t = h_t of the layer below
                     wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
                                p.status, p.spin_limit, aborted);
-                    const elem* src[CT];
-#pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) src[ct] = below + ((size_t)t * B + bcol[c][ct]) * H + kbase;
+                    const char* xs = reinterpret_cast<const char*>(below + (size_t)t * B * H);
                     frag xbuf[KB][CT];
-                    load_part<TR, CT, KB>(src, rot_k, xbuf);
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct)
+                            xbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
+                                xs + (size_t)((kb + rot_k) & (KB - 1)) * KW * sizeof(elem) + xoff[c][ct]));
                     mma_part<TR, RT, CT, KB>(wx, xbuf, acc);
                 }
             }
@@ -235,17 +258,20 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
             __syncthreads();
 
             elem* hcur = hseq + (size_t)(s + 1) * B * H;
+            // all partial sums of the tiles this wave finishes are read before the first is used
+            // (one LDS round trip instead of one per read)
+            f32x4 part[NOWN][4];
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) part[o][q] = red[(q * NTILE + min(w + 4 * o, NTILE - 1)) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
                 const int j = w + 4 * o;
                 if (j < NTILE) {  // uniform per wave
                     const bool valid = col_reg[c][o] < B;
-                    f32x4 a = red[(0 * NTILE + j) * 64 + lane];
-#pragma unroll
-                    for (int q = 1; q < 4; ++q) {
-                        const f32x4 b = red[(q * NTILE + j) * 64 + lane];
-                        a += b;
-                    }
+                    f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
                     a += gx_reg[o];
                     a += bias_reg[o];
                     const bool active = valid && t < len_reg[c][o];
@@ -314,6 +340,7 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
+    if ((size_t)a.B * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
     const int grid = a.LP * a.D * a.nrb * (a.ncb / NCH);
     const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
     auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH>;

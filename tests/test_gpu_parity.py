@@ -77,7 +77,12 @@ SMALL = [
     ("lstm_bf16_inside_t1", 0, 2, 1, 512, 512, 1, 512, 1, False, True),    # a single step: nothing to pipeline
     ("gru_bf16_inside_t2", 1, 2, 1, 512, 512, 2, 497, 1, True, True),      # two steps, ragged lengths 1..2, ragged batch
     ("lstm_bf16_inside_1layer", 0, 1, 1, 512, 512, 19, 512, 1, True, False),  # one layer: input re-laid out, output written
+    # Wide layers at a medium batch: several layers share one launch of the flag-vector kernel, the upper
+    # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.
+    ("lstm_bf16_fusedflag_l4", 0, 4, 1, 64, 1024, 5, 40, 1, True, True),    # 4 layers x 64 workgroups, tiles of 64 sequences
+    ("gru_bf16_fusedflag_l2", 1, 2, 1, 64, 1024, 6, 100, 1, True, True),    # 2 layers x 128 workgroups, two chains of 32
 ]
+SAMPLED = ("_inside", "_fusedflag")
 
 
 def _small_workload(W, spec):
@@ -106,7 +111,7 @@ def test_small_shapes(gpu, oracle, spec, plan):
         return
     io = harness.DeviceIO(wl)
     harness.forward(model, io)
-    if "_inside" in spec[0]:
+    if any(k in spec[0] for k in SAMPLED):
         rows = np.unique(np.linspace(0, wl.cfg.B - 1, 24).astype(int))
         ref = oracle.forward_workload(wl.take_batch(rows), nthreads=8)
         _check(harness, wl, io, ref, rows=rows)
