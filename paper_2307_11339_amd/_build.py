@@ -9,8 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librnn_mi355x.so")
-SOURCES = ["rnn_api.hip", "gemm.hip", "cellwise.hip", "wavefront.hip", "wavefront_x.hip", "wavefront_ll.hip"]
-HEADERS = ["common.h", "kernels.h", "wf_traits.h", os.path.join("..", "..", "include", "rnn.h")]
+SOURCES = ["rnn_api.hip", "gemm.hip", "cellwise.hip", "wavefront.hip", "wavefront_x.hip", "wavefront_ll.hip", "schedule.hip"]
+HEADERS = ["common.h", "kernels.h", "wf_traits.h", os.path.join("..", "..", "include", "rnn.h"),
+           os.path.join("..", "..", "include", "rnn_schedule.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -8,8 +8,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "rnn.h")).read()
+def declared_functions(header="rnn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(rnn_[a-z_]+)\s*\(", text)))
 
@@ -34,6 +34,16 @@ def test_library_exports_every_declared_symbol(lib):
     for name in declared_functions():
         assert hasattr(lib, name), name
     assert sorted(rnn.EXPORTS) == declared_functions()
+
+
+def test_every_header_is_covered(lib):
+    """include/ holds two headers; every function either declares is exported and bound."""
+    from paper_2307_11339_amd import schedule
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["rnn.h", "rnn_schedule.h"]
+    names = declared_functions("rnn_schedule.h")
+    assert names == sorted(schedule.EXPORTS)
+    for name in names:
+        assert hasattr(lib, name), name
 
 
 def test_host_only_calls(lib):

@@ -274,6 +274,44 @@ def test_gru_reset_before_product(gpu, oracle, spec):
     lstm.close()
 
 
+def test_kernel_runs_a_schedule_of_the_cell_graph(gpu):
+    """The persistent kernel's own clock stamps (one per cell, taken when the cell is published), read as
+    finish times, form a valid schedule of the cell graph that the host-side scheduler builds: no cell
+    finishes before its predecessors.  And the whole grid takes about as many step times as the list
+    schedule with one processor per layer predicts (its depth L + T - 1), far from the L * T of one cell
+    after another.  Model: the paper's Table 6 shape, 12 layers x 96 steps."""
+    import torch
+    from paper_2307_11339_amd import schedule
+    harness, rnn, W = gpu
+    cfg = W.paper_grid()[0]
+    wl = W.make_workload(cfg)
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    assert rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_STEP_TICKS) == rnn.RNN_OK
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    n_cells = cfg.L * cfg.D * cfg.T
+    rc, ticks = rnn.rnn_model_read_step_ticks(model.handle, n_cells)
+    assert rc == rnn.RNN_OK and ticks.min() > 0
+    model.close()
+    rc, off, idx = schedule.rnn_schedule_grid(cfg.L, cfg.T, cfg.D)
+    assert rc == rnn.RNN_OK and off.size == n_cells + 1
+    finish = ticks.astype(np.int64)
+    for v in range(n_cells):
+        for m in idx[off[v]:off[v + 1]]:
+            assert finish[m] <= finish[v], "cell %d published before its predecessor %d" % (v, m)
+    rc, order = schedule.rnn_schedule_order(off, idx, np.zeros(idx.size), np.ones(n_cells))
+    assert rc == rnn.RNN_OK
+    rc, _, _, depth = schedule.rnn_schedule_simulate(off, idx, order, cfg.L * cfg.D, np.ones(n_cells), np.zeros(idx.size))
+    assert rc == rnn.RNN_OK and depth == cfg.L + cfg.T - 1
+    step = float(np.median(np.diff(finish.reshape(cfg.L * cfg.D, cfg.T)[-1])))     # top layer, steady state
+    span = float(finish.max() - finish.min())
+    _say("    grid of %d cells: %.1f step times measured, %d predicted by the list schedule, %d one after another"
+         % (n_cells, span / step, depth, n_cells))
+    assert span <= 1.5 * depth * step
+
+
 def test_workspace_follows_the_plan(gpu):
     """The workspace holds what the plan of the current shape touches; a call of another shape that gets
     another plan grows it, and going back gives the first result again, bit for bit."""
