@@ -312,6 +312,14 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     a.hseq = state_region(m, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->flags.p;
+    // the launch must stay inside the buffers the workspace holds (a kernel never checks)
+    if (tagged) {
+        if (wavefront_ll_words(m->dtype, LP * m->D, T, B, m->H) * sizeof(uint64_t) > m->lseq.bytes) return RNN_EDEVICE;
+    } else {
+        const size_t flag_words = (size_t)LP * m->D * T * plan.ncb * plan.nrb;
+        const size_t state_end = (size_t)(l0 + LP) * m->D * (T + 1) * B * m->H * m->esize;
+        if (flag_words * sizeof(uint64_t) > m->flags.bytes || state_end > m->hseq.bytes) return RNN_EDEVICE;
+    }
     a.status = (unsigned*)m->status.p;
     a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
     a.spin_limit = 1u << 22;
@@ -355,10 +363,10 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
     if (rc == RNN_OK && any_projection) rc = grow(m, m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
     if (rc == RNN_OK && wavefront && !tagged) {
         rc = grow(m, m->hseq, state * (size_t)(T + 1) * m->esize);
-        // one flag word per (layer, direction, step, workgroup of that group); at most num_cus per launch
+        // one flag word per (layer, direction, step, chain, row block); a launch of LP layers uses the
+        // first LP * D * T * ncb * nrb words
         if (rc == RNN_OK)
-            rc = grow(m, m->flags, (size_t)m->L * m->D * T * (size_t)(m->num_cus > 256 ? m->num_cus : 256) * sizeof(uint64_t),
-                      true);
+            rc = grow(m, m->flags, (size_t)m->L * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
         if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->xblk, rows * m->H * m->esize);
     }
     if (rc == RNN_OK && tagged)
