@@ -48,6 +48,8 @@ constexpr int WF_MAX_LAYERS = 16;  // layers that may run concurrently in one la
 struct WavefrontArgs {
     int cell, dtype;
     int T, B, H, D;
+    int Bp;                      // B rounded up to a multiple of 4: row count of the blocked state
+                                 // sequences, so that no cache line of one holds sequences of two chains
     int L_total;                 // layers of the model (for the hT / cT row index)
     int l0, LP;                  // this launch runs layers [l0, l0 + LP)
     int RT, CT;                  // 16-row tiles per workgroup, 16-column tiles per chain
@@ -84,7 +86,7 @@ bool wavefront_variant_exists(int dtype, int RT, int CT, int NCH, int H, bool fu
 // Workgroups per CU the variants with this CT are compiled for (1 or 2).
 int wavefront_variant_occupancy(int CT);
 // Write slot 0 of the state sequence (the state "before step 0") from h0.
-hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B, int Bp,
                                  int H, void* hseq, hipStream_t stream);
 
 // ---- persistent kernel with the input product inside, one layer per launch (wavefront_x.hip) --
@@ -92,9 +94,9 @@ hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream);
 // True when a variant exists for this combination and its LDS footprint fits the current device.
 bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H);
-// src [T, B, H] -> dst [T][H/16][B][16] (the layout of a state sequence); H % 16 == 0, T <= 65535,
+// src [T, B, H] -> dst [T][H/16][Bp][16] (the layout of a state sequence, Bp >= B rows per block); H % 16 == 0, T <= 65535,
 // one row of 16 sequences must fit 64 KiB of LDS.
-hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int H, hipStream_t stream);
+hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int Bp, int H, hipStream_t stream);
 
 // ---- persistent wavefront kernel, tag-in-data variant for CT == 1 (wavefront_ll.hip) --------
 hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream);

@@ -262,10 +262,16 @@ int grow(rnn_model* m, DevBuf& b, size_t bytes, bool zeroed = false) {
     return RNN_OK;
 }
 
+// Rows per 16-unit block of a blocked sequence: B rounded up to a multiple of 4, so that a block
+// (rows x 16 elements of 2 or 4 bytes) is a whole number of 128-byte cache lines and no line holds
+// sequences of two chains.
+inline size_t blocked_rows(int B) { return ((size_t)B + 3) & ~(size_t)3; }
+
 // State sequences of the layers from l0 on (flag-vector kernels): every (layer, direction) owns
-// T + 1 slots of B * H elements, so a layer can read the finished sequence of the layer below.
+// T + 1 slots of blocked_rows(B) * H elements, so a layer can read the finished sequence of the
+// layer below.
 void* state_region(rnn_model* m, int l0, int T, int B) {
-    return (char*)m->hseq.p + (size_t)l0 * m->D * (T + 1) * B * m->H * m->esize;
+    return (char*)m->hseq.p + (size_t)l0 * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
 }
 
 // One persistent launch: layers [l0, l0 + LP) over all T steps.
@@ -285,12 +291,13 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         HIP_TRY(launch_wavefront_ll_init(m->dtype, h0, l0, LP, m->D, T, B, m->H,
                                          (uint64_t*)m->lseq.p, m->epoch, st));
     } else {
-        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, m->H, state_region(m, l0, T, B), st));
+        HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, (int)blocked_rows(B), m->H,
+                                      state_region(m, l0, T, B), st));
     }
     WavefrontArgs a;
     memset(&a, 0, sizeof(a));
     a.cell = m->cell; a.dtype = m->dtype;
-    a.T = T; a.B = B; a.H = m->H; a.D = m->D; a.L_total = m->L;
+    a.T = T; a.B = B; a.Bp = (int)blocked_rows(B); a.H = m->H; a.D = m->D; a.L_total = m->L;
     a.l0 = l0; a.LP = LP;
     a.RT = plan.RT; a.CT = plan.CT; a.NCH = plan.NCH; a.nrb = plan.nrb; a.ncb = plan.ncb;
     for (int ll = 0; ll < LP; ++ll) {
@@ -308,7 +315,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     a.gx = gx;
     a.xin = xin;
     if (x_from_state)  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
-        a.xin = (const char*)state_region(m, l0 - 1, T, B) + (size_t)B * m->H * m->esize;
+        a.xin = (const char*)state_region(m, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
     a.hseq = state_region(m, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->flags.p;
@@ -317,7 +324,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         if (wavefront_ll_words(m->dtype, LP * m->D, T, B, m->H) * sizeof(uint64_t) > m->lseq.bytes) return RNN_EDEVICE;
     } else {
         const size_t flag_words = (size_t)LP * m->D * T * plan.ncb * plan.nrb;
-        const size_t state_end = (size_t)(l0 + LP) * m->D * (T + 1) * B * m->H * m->esize;
+        const size_t state_end = (size_t)(l0 + LP) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
         if (flag_words * sizeof(uint64_t) > m->flags.bytes || state_end > m->hseq.bytes) return RNN_EDEVICE;
     }
     a.status = (unsigned*)m->status.p;
@@ -362,12 +369,12 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
     }
     if (rc == RNN_OK && any_projection) rc = grow(m, m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
     if (rc == RNN_OK && wavefront && !tagged) {
-        rc = grow(m, m->hseq, state * (size_t)(T + 1) * m->esize);
+        rc = grow(m, m->hseq, (size_t)m->L * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize);
         // one flag word per (layer, direction, step, chain, row block); a launch of LP layers uses the
         // first LP * D * T * ncb * nrb words
         if (rc == RNN_OK)
             rc = grow(m, m->flags, (size_t)m->L * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
-        if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->xblk, rows * m->H * m->esize);
+        if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->xblk, (size_t)T * blocked_rows(B) * m->H * m->esize);
     }
     if (rc == RNN_OK && tagged)
         rc = grow(m, m->lseq, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H) * sizeof(uint64_t), true);
@@ -394,7 +401,7 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
         if (input_product_inside(m, plan, l0, T)) {
             // the first layer reads the caller's x, re-laid out; a layer above reads the state sequence below it
-            if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, m->H, st));
+            if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, (int)blocked_rows(B), m->H, st));
             const int rc = launch_recurrent(m, plan, l0, 1, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
                                             l0 == 0 ? m->xblk.p : nullptr, l0 > 0);
             if (rc != RNN_OK) return rc;

@@ -28,10 +28,14 @@
 //     is stored;
 //   - every exchanged address is written exactly once per launch (the state of step s has its
 //     own slot, layer outputs are indexed by t) and is read only after its flag vector is
-//     complete, and a cache line never spans two column blocks.  A reader's caches therefore
-//     cannot hold a stale copy, so activations are read with ordinary cached loads and the
-//     workgroups of one XCD share them through that XCD's L2.
-// The state sequence is stored in blocks of 16 hidden units: slot[unit / 16][sequence][unit % 16].
+//     complete, and a cache line never holds data of two writers that finish at different times.
+//     A reader's caches therefore cannot hold a stale copy, so activations are read with ordinary
+//     cached loads and the workgroups of one XCD share them through that XCD's L2.
+// The state sequence is stored in blocks of 16 hidden units: slot[unit / 16][row][unit % 16] with
+// Bp = B rounded up to a multiple of 4 rows per block (rows >= B are padding nobody writes), so
+// that a block is a whole number of 128-byte lines: without the padding a line at the end of one
+// block would continue in the next block, whose first sequences belong to another chain, and a
+// reader could cache that line before the other chain has written its part.
 // A workgroup that owns 16 units then writes whole cache lines (32 bytes per sequence,
 // sequences adjacent), and a fragment load of a wave covers 16 sequences x 32 contiguous bytes
 // per unit block instead of 16 half lines 2 KiB apart.
@@ -88,6 +92,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const bool fused = FUSED && ll > 0;
     const bool out_shared = FUSED && ll + 1 < p.LP;  // a fused layer above reads this layer's output
     const int H = p.H, B = p.B, T = p.T;
+    const int Bp = p.Bp;                            // rows per 16-unit block of a state sequence
     const int kq = H / 4;                           // K range of one wave inside each part
 
     // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
@@ -152,7 +157,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
         for (int ct = 0; ct < CT; ++ct)
             bcol[c][ct] = min(((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
 
-    elem* hseq = static_cast<elem*>(p.hseq) + (size_t)g * (T + 1) * B * H;
+    elem* hseq = static_cast<elem*>(p.hseq) + (size_t)g * (T + 1) * Bp * H;
     elem* out = static_cast<elem*>(p.out[ll]);
     const elem* below = fused ? static_cast<const elem*>(p.out[ll - 1]) : nullptr;
     const int out_ld = p.D * H;
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     for (int c = 0; c < NCH; ++c)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
-            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], B) * sizeof(elem));
+            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], Bp) * sizeof(elem));
             xoff[c][ct] = (uint32_t)(((size_t)bcol[c][ct] * H + kbase) * sizeof(elem));
         }
     // h_{t-1} fragments of the chain that is processed next
@@ -189,7 +194,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
         if (s > 0)
             wait_flags(my_flags + (size_t)(s - 1) * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
                        p.status, p.spin_limit, aborted);
-        const elem* hprev = hseq + (size_t)s * B * H;  // state after step s-1
+        const elem* hprev = hseq + (size_t)s * Bp * H;  // state after step s-1
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
             const int kr = (kb + rot_k) & (KB - 1);
@@ -197,9 +202,9 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
             for (int ct = 0; ct < CT; ++ct) {
                 if (LINEAR_K)
                     hbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
-                        reinterpret_cast<const char*>(hprev) + (size_t)kr * KW * B * sizeof(elem) + hoff[c][ct]));
+                        reinterpret_cast<const char*>(hprev) + (size_t)kr * KW * Bp * sizeof(elem) + hoff[c][ct]));
                 else
-                    hbuf[kb][ct] = TR::load(hprev + hseq_off(kbase + kr * KW, bcol[c][ct], B));
+                    hbuf[kb][ct] = TR::load(hprev + hseq_off(kbase + kr * KW, bcol[c][ct], Bp));
             }
         }
     };
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                     red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
             __syncthreads();
 
-            elem* hcur = hseq + (size_t)(s + 1) * B * H;
+            elem* hcur = hseq + (size_t)(s + 1) * Bp * H;
             // all partial sums of the tiles this wave finishes are read before the first is used
             // (one LDS round trip instead of one per read)
             f32x4 part[NOWN][4];
@@ -290,7 +295,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                     // lanes n, n+16, n+32, n+48 hold units unit0 .. unit0+3 of sequence n
                     const int unit0 = unit_reg[o] - (lane >> 4);
                     const int colc = valid ? col_reg[c][o] : 0;
-                    TR::publish(state_v, out_v, valid, out_shared, lane, hcur + hseq_off(unit0, colc, B),
+                    TR::publish(state_v, out_v, valid, out_shared, lane, hcur + hseq_off(unit0, colc, Bp),
                                 out + ((size_t)t * B + colc) * out_ld + (size_t)d * H + unit0);
                 }
             }
@@ -321,7 +326,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
 }
 
 template <int DT>
-__global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, int T, int B, int H,
+__global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, int T, int B, int Bp, int H,
                                       void* hseq) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t per = (size_t)B * H;
@@ -331,7 +336,7 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
         const float h = h0 ? h0[((size_t)l0 * D) * per + i] : 0.0f;
         const size_t b = rem / H, u = rem - b * H;
         // slot 0 = state before step 0, blocked by 16 hidden units
-        const size_t dst = g * (size_t)(T + 1) * per + ((u >> 4) * B + b) * 16 + (u & 15);
+        const size_t dst = g * (size_t)(T + 1) * Bp * H + ((u >> 4) * Bp + b) * 16 + (u & 15);
         if (DT == DT_BF16) ((bf16_t*)hseq)[dst] = f32_to_bf16(h);
         else ((float*)hseq)[dst] = h;
     }
@@ -340,7 +345,8 @@ __global__ void wavefront_init_kernel(const float* h0, int l0, int LP, int D, in
 template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
-    if ((size_t)a.B * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
+    if ((size_t)a.Bp * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
+    if (a.Bp < a.B || a.Bp % 4 != 0) return hipErrorInvalidValue;
     const int grid = a.LP * a.D * a.nrb * (a.ncb / NCH);
     const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
     auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH>;
@@ -416,14 +422,14 @@ hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B,
+hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B, int Bp,
                                  int H, void* hseq, hipStream_t stream) {
     const size_t n = (size_t)LP * D * B * H;
     const unsigned blocks = (unsigned)((n + 255) / 256);
     if (dtype == DT_BF16)
-        wavefront_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, hseq);
+        wavefront_init_kernel<DT_BF16><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, Bp, H, hseq);
     else
-        wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, H, hseq);
+        wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, Bp, H, hseq);
     return hipGetLastError();
 }
 

@@ -49,6 +49,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     const int cbg = v / p.nrb, rb = v - cbg * p.nrb;
     const int l = p.l0;
     const int H = p.H, B = p.B, T = p.T;
+    const int Bp = p.Bp;                            // rows per 16-unit block of a state sequence
     const int kq = H / 4;                           // K range of one wave inside each part
 
     // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
@@ -145,22 +146,22 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     for (int c = 0; c < NCH; ++c)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
-            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], B) * sizeof(elem));
+            hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], Bp) * sizeof(elem));
         }
     auto blocked_ptr = [&](const elem* step, int c, int ct, int kb) -> const elem* {
         const int kr = (kb + rot_k) & (KB - 1);
         if (LINEAR_K)
             return reinterpret_cast<const elem*>(reinterpret_cast<const char*>(step) +
-                                                 (size_t)kr * KW * B * sizeof(elem) + hoff[c][ct]);
-        return step + hseq_off(kbase + kr * KW, bcol[c][ct], B);
+                                                 (size_t)kr * KW * Bp * sizeof(elem) + hoff[c][ct]);
+        return step + hseq_off(kbase + kr * KW, bcol[c][ct], Bp);
     };
     auto load_h = [&](int c, int s, int kb) {  // K block kb of the state after step s-1
-        const elem* hprev = hseq + (size_t)min(s, T - 1) * B * H;
+        const elem* hprev = hseq + (size_t)min(s, T - 1) * Bp * H;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) hbuf[kb][ct] = TR::load(blocked_ptr(hprev, c, ct, kb));
     };
     auto load_x = [&](int c, int s, int kb) {  // K block kb of x at step s (same layout as the state)
-        const elem* xs = xin + (size_t)min(s, T - 1) * B * H;
+        const elem* xs = xin + (size_t)min(s, T - 1) * Bp * H;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) xbuf[kb][ct] = TR::load(blocked_ptr(xs, c, ct, kb));
     };
@@ -249,11 +250,11 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     for (int c = 0; c < NCH; ++c) {
         const int col0 = (cbg * NCH + c) * CT * 16;
         const int line = min(pf_idx + per_xcd * lane, NLINES * (H / 16) - 1);
-        const size_t off = ((size_t)(line / NLINES) * B + col0) * 16 + (size_t)(line % NLINES) * LINE;
-        pf_off[c] = (uint32_t)(min(off, (size_t)B * H - 1) & ~(size_t)(LINE - 1));
+        const size_t off = ((size_t)(line / NLINES) * Bp + col0) * 16 + (size_t)(line % NLINES) * LINE;
+        pf_off[c] = (uint32_t)(min(off, (size_t)Bp * H - 1) & ~(size_t)(LINE - 1));
     }
     auto touch_x = [&](int c, int s) -> uint32_t {
-        return *reinterpret_cast<const uint32_t*>(xin + (size_t)min(s, T - 1) * B * H + pf_off[c]);
+        return *reinterpret_cast<const uint32_t*>(xin + (size_t)min(s, T - 1) * Bp * H + pf_off[c]);
     };
 
     if (NCH > 1) {
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     red[(w * NTILE + rt * CT + ct) * 64 + lane] = acc[rt][ct];
             __syncthreads();
 
-            elem* hcur = hseq + (size_t)(s + 1) * B * H;
+            elem* hcur = hseq + (size_t)(s + 1) * Bp * H;
             // all partial sums of the tiles this wave finishes are read before the first is used
             // (one LDS round trip instead of one per read)
             f32x4 part[NOWN][4];
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     const elem* stage = reinterpret_cast<const elem*>(red + (size_t)(rt * CT + ct) * 64) + (sl & 15) * 4;
                     const int unit0 = (rb * RT + rt) * 4;
                     if (col < B) {
-                        TR::store_piece_dev(hcur + hseq_off(unit0, col, B), *reinterpret_cast<const piece*>(stage));
+                        TR::store_piece_dev(hcur + hseq_off(unit0, col, Bp), *reinterpret_cast<const piece*>(stage));
                         if (out)
                             *reinterpret_cast<piece*>(out + ((size_t)t * B + col) * H + unit0) =
                                 *reinterpret_cast<const piece*>(stage + 64);
@@ -415,12 +416,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         }
 }
 
-// [rows of H elements] -> blocked by 16 elements: dst[t][H/16][B][16] from src[t][B][H].  One
+// [rows of H elements] -> blocked by 16 elements: dst[t][H/16][Bp][16] from src[t][B][H] (rows B..Bp-1
+// of a block are padding and stay unwritten).  One
 // workgroup moves 16 sequences of one step through LDS, so that it reads whole rows and writes
 // runs of 16 sequences x 16 units (both sides in whole cache lines).  ES = element size in bytes.
 template <int ES>
 __global__ __launch_bounds__(256) void to_blocked_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                          int B, int H) {
+                                                          int B, int Bp, int H) {
     extern __shared__ uint4 tile[];                 // [16 sequences][U] 16-byte units
     const int U = H * ES / 16;                      // 16-byte units per row
     const int t = blockIdx.y, b0 = blockIdx.x * 16;
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(256) void to_blocked_kernel(const uint4* __restrict
     // output order: [block of 16 units][sequence][ES units of 16 bytes]
     for (int i = threadIdx.x; i < 16 * U; i += 256) {
         const int q = i % ES, r = (i / ES) % 16, blk = i / (ES * 16);
-        if (r < nb) dst[(((size_t)t * (H / 16) + blk) * B + b0 + r) * ES + q] = tile[r * U + blk * ES + q];
+        if (r < nb) dst[(((size_t)t * (H / 16) + blk) * Bp + b0 + r) * ES + q] = tile[r * U + blk * ES + q];
     }
 }
 
@@ -458,7 +460,8 @@ int device_lds_limit() {
 template <class TR, int CELL, int RT, int CT, int KB, int NCH>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
-    if ((size_t)a.B * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
+    if ((size_t)a.Bp * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
+    if (a.Bp < a.B || a.Bp % 4 != 0) return hipErrorInvalidValue;
     const int grid = a.nrb * (a.ncb / NCH);
     constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
@@ -518,16 +521,16 @@ bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H) {
     return false;
 }
 
-hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int H, hipStream_t stream) {
+hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int Bp, int H, hipStream_t stream) {
     const int es = dtype == DT_BF16 ? 2 : 4;
-    if (H % 16 != 0 || T < 1 || B < 1 || T > 65535) return hipErrorInvalidValue;
+    if (H % 16 != 0 || T < 1 || B < 1 || Bp < B || T > 65535) return hipErrorInvalidValue;
     const size_t smem = (size_t)16 * H * es;
     if (smem > 64 * 1024) return hipErrorInvalidValue;
     const dim3 grid((B + 15) / 16, T);
     if (es == 2)
-        to_blocked_kernel<2><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, H);
+        to_blocked_kernel<2><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, Bp, H);
     else
-        to_blocked_kernel<4><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, H);
+        to_blocked_kernel<4><<<grid, 256, smem, stream>>>((const uint4*)src, (uint4*)dst, B, Bp, H);
     return hipGetLastError();
 }
 

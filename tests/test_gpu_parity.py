@@ -66,6 +66,7 @@ SMALL = [
     ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
+    ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state
     # Large batch, wide enough that a layer needs every compute unit: one persistent launch per layer.
     # Layers whose input has the layer's own width compute W_ih x_t inside the recurrent kernel; layers
     # above the first read the state sequence of the layer below.  Checked on 24 sampled sequences.
@@ -77,6 +78,7 @@ SMALL = [
     ("lstm_bf16_inside_t1", 0, 2, 1, 512, 512, 1, 512, 1, False, True),    # a single step: nothing to pipeline
     ("gru_bf16_inside_t2", 1, 2, 1, 512, 512, 2, 497, 1, True, True),      # two steps, ragged lengths 1..2, ragged batch
     ("lstm_bf16_inside_1layer", 0, 1, 1, 512, 512, 19, 512, 1, True, False),  # one layer: input re-laid out, output written
+    ("lstm_f32_inside_b501", 0, 2, 1, 128, 128, 6, 501, 0, True, True),    # odd batch in fp32: padded rows in the blocked state
     # Wide layers at a medium batch: several layers share one launch of the flag-vector kernel, the upper
     # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.
     ("lstm_bf16_fusedflag_l4", 0, 4, 1, 64, 1024, 5, 40, 1, True, True),    # 4 layers x 64 workgroups, tiles of 64 sequences
@@ -341,6 +343,45 @@ def test_workspace_follows_the_plan(gpu):
     harness.forward(model, io)
     torch.cuda.synchronize()
     assert torch.equal(io.y, y_first)
+    model.close()
+
+
+@pytest.mark.parametrize("name", ["gru_bf16_inside_t2", "lstm_f32_inside_b501", "lstm_bf16_b299", "lstm_bf16_inside_sq"])
+def test_first_call_on_used_memory_equals_later_calls(gpu, name):
+    """The kernels exchange states through memory that every address of is written once per launch and
+    read with cached loads.  That only works if what a reader's cache line holds besides the data it
+    waited for is never needed later in the same launch: the blocked state sequence pads its rows so a
+    line never holds sequences of two chains.  Without that, the first call on memory holding anything
+    else (or a call after other inputs) read stale values for a few sequences.  Here: workspace memory
+    is dirtied first, then the same inputs, other inputs, and the first inputs again must give the
+    first call's bits."""
+    import torch
+    harness, rnn, W = gpu
+    by_name = {s[0]: s for s in SMALL}
+    junk = [torch.full((32 << 20,), 3.0e4, dtype=torch.bfloat16, device="cuda") for _ in range(4)]
+    torch.cuda.synchronize()
+    del junk
+    torch.cuda.empty_cache()          # hands the memory back to the runtime; the library allocates from it next
+    wl = _small_workload(W, by_name[name])
+    spec2 = list(by_name[name])
+    spec2[0] = name + "_other"
+    wl2 = _small_workload(W, tuple(spec2))
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io, io2 = harness.DeviceIO(wl), harness.DeviceIO(wl2)
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    y0, h0 = io.y.clone(), io.hT.clone()
+    for _ in range(2):
+        harness.forward(model, io)
+        torch.cuda.synchronize()
+        assert torch.equal(io.y, y0) and torch.equal(io.hT, h0)
+    harness.forward(model, io2)        # same weights, other inputs and initial states: leaves other values behind
+    torch.cuda.synchronize()
+    assert not torch.equal(io2.y, y0)
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    assert torch.equal(io.y, y0) and torch.equal(io.hT, h0)
     model.close()
 
 
