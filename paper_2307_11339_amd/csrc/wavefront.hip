@@ -170,9 +170,12 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
     // A wave reads only its own K quarter of an activation vector, so it waits only for the row
-    // blocks that produce that quarter (a quarter of the flag vector: one cache line at most).
-    const int nfl = p.nrb / 4;
-    const int fl0 = w * nfl;
+    // blocks that produce the cache lines of that quarter (a quarter of the flag vector, one cache
+    // line at most, unless a quarter is narrower than a line).  A line of a state sequence holds 16
+    // units, a line of a layer output (row-major) 128 bytes of one sequence.
+    int fl0, nfl, xfl0, xnfl;
+    flag_span(w * kq, kq, H, 16, RT * 4, fl0, nfl);
+    flag_span(w * kq, kq, H, 128 / (int)sizeof(elem), RT * 4, xfl0, xnfl);
 
     // Addresses of the activation loads = uniform base of the step + uniform offset of the K block
     // + a 32-bit per-lane offset that does not change over the launch (one register per chain and
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
 
             if (FUSED) {
                 if (fused) {  // x_t = h_t of the layer below
-                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch,
+                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + xfl0, xnfl, lane, epoch,
                                p.status, p.spin_limit, aborted);
                     const char* xs = reinterpret_cast<const char*>(below + (size_t)t * B * H);
                     frag xbuf[KB][CT];

@@ -122,9 +122,10 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     const uint32_t epoch = p.epoch;
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
-    // a wave waits only for the row blocks that produce its own K quarter of the state
-    const int nfl = p.nrb / 4;
-    const int fl0 = w * nfl;
+    // a wave waits only for the row blocks that produce the cache lines (16 units each) of its own
+    // K quarter of the state
+    int fl0, nfl;
+    flag_span(w * kq, kq, H, 16, RT * 4, fl0, nfl);
 
     frag hbuf[KB][CT];   // h_{t-1} fragments of the chain step that is processed next
     frag xbuf[KB][CT];   // x_t fragments of the chain step that is processed next

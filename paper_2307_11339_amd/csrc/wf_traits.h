@@ -147,6 +147,18 @@ __device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t
     return true;
 }
 
+// Row blocks a wave must wait for before it reads units [k0, k0 + kn) of an activation vector with
+// cached loads: those that write any unit sharing a cache line with that range, `line_units`
+// consecutive units to a line (a line the wave brings into its caches must be complete, or a later
+// reader of the same line, e.g. the wave of the next K quarter, would find the incomplete copy).
+// `rb_units` = units per row block; line_units is a multiple of it.
+__device__ inline void flag_span(int k0, int kn, int H, int line_units, int rb_units, int& first, int& count) {
+    const int lo = (k0 / line_units) * line_units;
+    const int hi = min(H, ((k0 + kn + line_units - 1) / line_units) * line_units);
+    first = lo / rb_units;
+    count = (hi - lo + rb_units - 1) / rb_units;
+}
+
 // Activation fragments of one part (h_{t-1} or x_t) for CT column tiles: buf[kb][ct].  src[ct]
 // points at this lane's first K element of the sequence in column tile ct.  Register slot kb
 // holds K block (kb + rot) mod KB: workgroups that read the same activations at the same
