@@ -104,6 +104,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
         const int LP = (m->L + launches - 1) / launches;
         const int budget = m->num_cus / (LP * m->D);
         int best = -1, best_cost = 0, best_rt = 0, best_nch = 0;
+        int tag_small = -1, tag_large = -1;   // tag-in-data candidates: smallest tile within 3/8 of the chip, largest tile
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
             const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
             if (row_tiles % RT) continue;
@@ -117,6 +118,17 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             if (tagged && wavefront_ll_words(m->dtype, 2, T, B, m->H) * 8 >= ((size_t)1 << 31)) continue;
             const int occ = tagged ? 1 : wavefront_variant_occupancy(CT);
             if (nrb * (ncb / NCH) > budget * occ || ncb > FLAG_COLBLOCKS_MAX) continue;
+            if (tagged) {
+                // The step of that kernel is an all-gather among the workgroups of a layer, and the more
+                // workgroups poll, the longer a store takes to reach them (measured at batch 8, 2 layers of
+                // 512 units: 256, 128, 64 workgroups in the launch take 3.6, 2.3-2.9, 2.15 us per step;
+                // one layer of 1024 units at batch 1 on 256 or 64 workgroups: 1.95 and 2.05 us; 12 layers
+                // of 64 units: 192, 96, 48 workgroups give 1.45, 1.3, 1.5 us).  So: the smallest tile that
+                // keeps the whole launch within 3/8 of the compute units, else the largest tile.
+                if (tag_small < 0 && LP * m->D * nrb * ncb <= m->num_cus * 3 / 8) tag_small = c;
+                tag_large = c;
+                continue;
+            }
             // work per workgroup and step; at equal work prefer interleaved chains, then taller tiles
             const int cost = RT * CT * NCH;
             if (best < 0 || cost < best_cost || (cost == best_cost && NCH > best_nch) ||
@@ -124,6 +136,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
                 best = c; best_cost = cost; best_rt = RT; best_nch = NCH;
             }
         }
+        if (tag_large >= 0) best = tag_small >= 0 ? tag_small : tag_large;
         if (best >= 0) {
             plan.kind = RNN_PLAN_WAVEFRONT;
             plan.LP = LP;

@@ -13,9 +13,9 @@
 // word is either old (tag differs) or complete.  The state sequence has one slot per step
 // (slot 0 = h0, slot s+1 = state after step s), each word is written once per launch, and the
 // epoch changes with every launch, so nothing has to be cleared between launches.  Critical
-// path per step: the store becoming visible, one probe and one load round trip; no counters,
-// no store acknowledgement wait, and a single workgroup barrier (for the partial-sum exchange,
-// which is double buffered).
+// path per step: the store becoming visible and one load round trip (both overlap: a load issued
+// right after the stores comes back about when they have landed), the matrix part, two workgroup
+// barriers; no counters and no store acknowledgement wait.
 //
 // For a unidirectional stack the layer above reads the same state sequence as its x_t: where a
 // sequence is still running the state is the layer's output, and where it is padded the cell
@@ -81,50 +81,59 @@ struct LLF32 : TraitsF32 {
 // Device-scope buffer loads (sc1): they see other workgroups' write-through stores and the
 // compiler can keep many of them in flight.  `base` is the byte offset, inside the buffer
 // resource, of word 0 of this wave's quarter for column 0 of the block; row_bytes separates
-// consecutive sequences.  Returns whether every tag equals `epoch`.
-template <int QW>
-__device__ inline bool ll_fetch(__amdgpu_buffer_rsrc_t rsrc, uint32_t base, uint32_t row_bytes, int ncol,
-                                int lane, uint32_t epoch, uint32_t* stage) {
-    constexpr int NI_MAX = (16 * QW + 127) / 128;       // load instructions for a full column block
-    constexpr int STRIDE = QW + 4;                      // padded staging row (dwords)
-    const int total = ncol * QW;                        // tagged words wanted by this wave
-    u32x4 v[NI_MAX];
+// consecutive sequences.
+// ALL: every one of the NI instructions is issued and checked whatever ncol is (instructions past
+// the end re-read the last pair), so that the compiler sees the same loads on every path and can
+// tell what is still in flight; used where a request stays in flight across other work.
+template <int QW, int NI = (16 * QW + 127) / 128, bool ALL = false>   // covers up to 128 * NI words
+struct LLFetch {
+    static constexpr int STRIDE = QW + 4;                  // padded staging row (dwords)
+    u32x4 v[NI];
+    // request the words (no wait)
+    __device__ inline void issue(__amdgpu_buffer_rsrc_t rsrc, uint32_t base, uint32_t row_bytes, int ncol, int lane) {
+        const int total = ncol * QW;                        // tagged words wanted by this wave
 #pragma unroll
-    for (int i = 0; i < NI_MAX; ++i) {
-        const int f = i * 128 + 2 * lane;               // first of this lane's two words
-        if (i * 128 < total) {                          // uniform
-            const int c = f / QW, wd = f % QW;
-            // lanes past the end re-read the last pair (in bounds, result unused)
-            const uint32_t off = (f < total) ? base + (uint32_t)c * row_bytes + (uint32_t)wd * 8u
-                                             : base + (uint32_t)(ncol - 1) * row_bytes + (uint32_t)(QW - 2) * 8u;
-            v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 16 /* sc1 */);
+        for (int i = 0; i < NI; ++i) {
+            const int f = i * 128 + 2 * lane;               // first of this lane's two words
+            if (ALL || i * 128 < total) {                   // uniform
+                const int c = f / QW, wd = f % QW;
+                // lanes past the end re-read the last pair (in bounds, result unused)
+                const uint32_t off = (f < total) ? base + (uint32_t)c * row_bytes + (uint32_t)wd * 8u
+                                                 : base + (uint32_t)(ncol - 1) * row_bytes + (uint32_t)(QW - 2) * 8u;
+                v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 16 /* sc1 */);
+            }
         }
     }
-    bool ok = true;
+    // check the tags of what arrived and leave the payloads in the staging area; returns whether
+    // every tag equals `epoch`
+    __device__ inline bool land(int ncol, int lane, uint32_t epoch, uint32_t* stage) const {
+        const int total = ncol * QW;
+        bool ok = true;
 #pragma unroll
-    for (int i = 0; i < NI_MAX; ++i) {
-        const int f = i * 128 + 2 * lane;
-        if (i * 128 < total && f < total) {
-            const int c = f / QW, wd = f % QW;
-            ok = ok && v[i][1] == epoch && v[i][3] == epoch;
-            *reinterpret_cast<uint2*>(stage + c * STRIDE + wd) = make_uint2(v[i][0], v[i][2]);
+        for (int i = 0; i < NI; ++i) {
+            const int f = i * 128 + 2 * lane;
+            if (ALL) {
+                ok = ok && v[i][1] == epoch && v[i][3] == epoch;
+                if (f < total) *reinterpret_cast<uint2*>(stage + (f / QW) * STRIDE + f % QW) = make_uint2(v[i][0], v[i][2]);
+            } else if (i * 128 < total && f < total) {
+                ok = ok && v[i][1] == epoch && v[i][3] == epoch;
+                *reinterpret_cast<uint2*>(stage + (f / QW) * STRIDE + f % QW) = make_uint2(v[i][0], v[i][2]);
+            }
         }
+        return __all(ok);
     }
-    return __all(ok);
-}
+};
 
-// acc[rt] += W[rt][:] x (activations of one source), the source being tagged state words.
+// Wait until the tagged words at `base` are complete and leave their payloads in the staging area.
 // When the source needs more than one load instruction, waiting is done on a single probe
 // instruction whose lanes sample the first word of every producer tile (4 hidden units written
 // by one wave of one workgroup) over the sequences of the block; the full fetch follows and is
 // repeated until every tag matches.
-template <class TR, int RT, int KB>
-__device__ inline void ll_mma(const typename TR::frag (&wreg)[RT][KB], uint32_t base,
-                              __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol, int lane,
-                              uint32_t probe_rel, uint32_t* stage, f32x4 (&acc)[RT], uint32_t epoch,
-                              unsigned* status, unsigned spin_limit, bool& aborted) {
+template <class TR, int KB>
+__device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol, int lane,
+                               uint32_t probe_rel, uint32_t* stage, uint32_t epoch, unsigned* status,
+                               unsigned spin_limit, bool& aborted) {
     constexpr int QW = KB * TR::WORDS_PER_KW;           // tagged words per sequence in one K quarter
-    constexpr int STRIDE = QW + 4;
     unsigned spins = 0;
     auto give_up = [&]() {  // called now and then while waiting
         const unsigned st = ld_dev_u32(status);
@@ -141,32 +150,65 @@ __device__ inline void ll_mma(const typename TR::frag (&wreg)[RT][KB], uint32_t 
         }
     }
     for (;;) {
-        const bool ok = ll_fetch<QW>(rsrc, base, row_bytes, ncol, lane, epoch, stage);
+        LLFetch<QW> f;
+        f.issue(rsrc, base, row_bytes, ncol, lane);
+        const bool ok = f.land(ncol, lane, epoch, stage);
         if (ok || aborted) break;
         if ((++spins & 63u) == 0u) give_up();
     }
+}
+
+// acc[rt] += W[rt][:] x (payloads in the staging area of this wave).  The B fragments are read from
+// LDS a group ahead of the MFMAs that use them, so that the LDS latency is paid once per group, not
+// once per K block.
+template <class TR, int RT, int KB>
+__device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const uint32_t* stage, int ncol, int lane,
+                                  f32x4 (&acc)[RT]) {
+    constexpr int QW = KB * TR::WORDS_PER_KW;
+    constexpr int STRIDE = QW + 4;
+    constexpr int G = KB < 4 ? KB : 4;                  // fragments per group
     // B operand fragments from the staging area: lane (n, q) reads sequence min(n, ncol-1)
     const uint32_t* mine = stage + min(lane & 15, ncol - 1) * STRIDE + TR::word_of(TR::koff(lane));
+    typename TR::frag f[2][G];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        const typename TR::frag f = TR::frag_from_lds(mine + kb * TR::WORDS_PER_KW);
+    for (int i = 0; i < G; ++i) f[0][i] = TR::frag_from_lds(mine + i * TR::WORDS_PER_KW);
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wreg[rt][kb], f, acc[rt]);
+    for (int g = 0; g < KB / G; ++g) {
+        if (g + 1 < KB / G) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) f[(g + 1) & 1][i] = TR::frag_from_lds(mine + ((g + 1) * G + i) * TR::WORDS_PER_KW);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < G; ++i)
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wreg[rt][g * G + i], f[g & 1][i], acc[rt]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
+// Waves 0..3 ("h waves") carry the recurrence: they fetch h_{t-1}, multiply, exchange partial sums,
+// finish the gates and publish.  In a launch with fused layers the workgroup has four more waves
+// ("x waves") that hold the W_ih slice and do nothing but the input product of the NEXT step: they
+// request x_{t+1} (the state of the layer below) before the two barriers of step t, and multiply it
+// right after them, i.e. while the h waves wait for h_t to come round.  The input product is then off
+// the recurrent critical path, and neither wave type holds two sets of weights (with both sets in
+// one wave the compiler parks one in the accumulator registers and copies it back before every MFMA).
 template <class TR, int CELL, int RT, int KB, bool FUSED>
-__global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
+__global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
     constexpr int KW = TR::KW;
     constexpr int NOWN = (RT + 3) / 4;               // tiles finished by one wave
     constexpr int QW = KB * TR::WORDS_PER_KW;        // tagged words per sequence and K quarter
     constexpr int STAGE_DW = 16 * (QW + 4);          // staging dwords per wave: 16 sequence rows
+    constexpr int RED = 4 * RT * 64;                 // f32x4 entries of one set of partial sums
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    // partial sums [2 (step parity)][4 waves][RT][64 lanes], then the per-wave staging areas
+    // partial sums of the h waves [4][RT][64 lanes]; of the x waves [2 (step parity)][4][RT][64];
+    // then the per-wave staging areas
     f32x4* red = reinterpret_cast<f32x4*>(smem_raw);
-    uint32_t* stage = reinterpret_cast<uint32_t*>(smem_raw + (size_t)2 * 4 * RT * 64 * sizeof(f32x4)) +
+    f32x4* xred = red + RED;
+    uint32_t* stage = reinterpret_cast<uint32_t*>(smem_raw + (size_t)(FUSED ? 3 : 1) * RED * sizeof(f32x4)) +
                       (threadIdx.x >> 6) * STAGE_DW;
 
     // every step of this kernel is on a dependency chain: when a projection kernel shares the CU,
@@ -174,7 +216,8 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int w = tid >> 6;
+    const int w = (tid >> 6) & 3;                    // K quarter of this wave
+    const bool xwave = FUSED && (tid >> 8) != 0;
     const int v = xcd_contiguous_id();
     const int wpg = p.nrb * p.ncb;
     const int g = v / wpg;
@@ -189,20 +232,90 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
     const int kq = H / 4;
     const uint32_t epoch = p.epoch;
 
+    const int row_words = TR::row_words(H);
+    const size_t seq_words = (size_t)(T + 1) * B * row_words;
+    uint64_t* lseq = p.lseq + (size_t)g * seq_words;
+    // one buffer resource over the state sequences of this group and (when fused) of the layer
+    // below it, which lies directly before it (D == 1); offsets are bytes inside that window.
+    // (The pieces are wave-uniform; saying so keeps the descriptor in scalar registers, otherwise
+    // every load is wrapped in a loop over the distinct descriptors of the wave.)
+    const uint64_t* window = fused ? lseq - seq_words : lseq;
+    const uint32_t own_off = fused ? (uint32_t)(seq_words * 8) : 0u;
+    const uint64_t wbits = reinterpret_cast<uint64_t>(window);
+    const uint32_t wlo = __builtin_amdgcn_readfirstlane((uint32_t)wbits);
+    const uint32_t whi = __builtin_amdgcn_readfirstlane((uint32_t)(wbits >> 32));
+    const int wbytes = __builtin_amdgcn_readfirstlane((int)((fused ? 2 : 1) * seq_words * 8));
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<void*>(((uint64_t)whi << 32) | wlo), 0, wbytes, 0x00020000);
+    const uint32_t row_bytes = (uint32_t)row_words * 8u;
+    const int ncol = min(16, B - cb * 16);
+    // byte offset (inside a slot) of word 0 of this wave's K quarter for column 0 of the block
+    const uint32_t quarter_off = ((uint32_t)(cb * 16) * row_words + TR::word_of(w * kq)) * 8u;
+    uint32_t probe_rel;  // probe word of this lane relative to quarter_off
+    {
+        const int ntile = kq / 4;                               // producer tiles in this K quarter
+        const int ti = lane % ntile, ci = (lane / ntile) % ncol;
+        probe_rel = (uint32_t)ci * row_bytes + (uint32_t)TR::word_of(ti * 4) * 8u;
+    }
+    const uint32_t slot_bytes = (uint32_t)B * row_bytes;
+    bool aborted = false;
+
+    if (xwave) {
+        // ---- input product of the next step (fused layers); the x waves of the first layer of the
+        // launch only keep the barriers company ----
+        if (fused) {
+            frag wx[RT][KB];
+            const elem* wih = static_cast<const elem*>(p.wih[g]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) wx[rt][kb] = TR::load(wih + row * H + w * kq + kb * KW + TR::koff(lane));
+            }
+            // x_t = state of the layer below after its step t = slot t + 1 of its sequence (t == s when
+            // D == 1).  A quarter that fits a few load instructions is requested a step early and stays
+            // in flight across the barriers; a larger one is fetched after them.
+            constexpr int XNI = (16 * QW + 127) / 128 < 4 ? (16 * QW + 127) / 128 : 4;
+            const bool early = ncol * QW <= 128 * XNI;
+            LLFetch<QW, XNI, true> xq;
+            if (early) xq.issue(rsrc, slot_bytes + quarter_off, row_bytes, ncol, lane);
+            for (int sx = 0; sx < T; ++sx) {            // produces the input part of step sx
+                if (sx > 0) {                           // steps sx-1 of the h waves: their two barriers
+                    __syncthreads();
+                    __syncthreads();
+                }
+                const uint32_t xbase = (uint32_t)(sx + 1) * slot_bytes + quarter_off;
+                if (!(early && xq.land(ncol, lane, epoch, stage)))
+                    ll_wait<TR, KB>(xbase, rsrc, row_bytes, ncol, lane, probe_rel, stage, epoch, p.status, p.spin_limit, aborted);
+                if (early) xq.issue(rsrc, (uint32_t)min(sx + 2, T) * slot_bytes + quarter_off, row_bytes, ncol, lane);
+                __builtin_amdgcn_sched_barrier(0);
+                f32x4 acc[RT];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                ll_consume<TR, RT, KB>(wx, stage, ncol, lane, acc);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) xred[(((sx & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+            }
+            __syncthreads();
+            __syncthreads();
+        } else {
+            for (int s = 0; s < T; ++s) {
+                __syncthreads();
+                __syncthreads();
+            }
+        }
+        return;
+    }
+
+    // ---- h waves ----
     frag wh[RT][KB];
-    frag wx[RT][KB];  // only live when FUSED
     {
         const elem* whh = static_cast<const elem*>(p.whh[g]);
-        const elem* wih = fused ? static_cast<const elem*>(p.wih[g]) : whh;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                const int k = w * kq + kb * KW + TR::koff(lane);
-                wh[rt][kb] = TR::load(whh + row * H + k);
-                if (FUSED) wx[rt][kb] = TR::load(wih + row * H + k);
-            }
+            for (int kb = 0; kb < KB; ++kb) wh[rt][kb] = TR::load(whh + row * H + w * kq + kb * KW + TR::koff(lane));
         }
     }
 
@@ -229,30 +342,8 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
             bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
         }
     }
-
-    const int row_words = TR::row_words(H);
-    const size_t seq_words = (size_t)(T + 1) * B * row_words;
-    uint64_t* lseq = p.lseq + (size_t)g * seq_words;
-    // one buffer resource over the state sequences of this group and (when fused) of the layer
-    // below it, which lies directly before it (D == 1); offsets are bytes inside that window
-    const uint64_t* window = fused ? lseq - seq_words : lseq;
-    const uint32_t own_off = fused ? (uint32_t)(seq_words * 8) : 0u;
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint64_t*>(window), 0, (int)((fused ? 2 : 1) * seq_words * 8), 0x00020000);
-    const uint32_t row_bytes = (uint32_t)row_words * 8u;
-    const int ncol = min(16, B - cb * 16);
-    // byte offset (inside a slot) of word 0 of this wave's K quarter for column 0 of the block
-    const uint32_t quarter_off = ((uint32_t)(cb * 16) * row_words + TR::word_of(w * kq)) * 8u;
-    uint32_t probe_rel;  // probe word of this lane relative to quarter_off
-    {
-        const int ntile = kq / 4;                               // producer tiles in this K quarter
-        const int ti = lane % ntile, ci = (lane / ntile) % ncol;
-        probe_rel = (uint32_t)ci * row_bytes + (uint32_t)TR::word_of(ti * 4) * 8u;
-    }
-    const uint32_t slot_bytes = (uint32_t)B * row_bytes;
     elem* out = static_cast<elem*>(p.out[ll]);
     const int out_ld = p.D * H;
-    bool aborted = false;
 
     // Projection of a step for the pairs this lane finishes.  It is requested one step ahead, right
     // after the last poll of a step: loads return in order, so a request to HBM issued just before a
@@ -269,49 +360,44 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
             gx_reg[o] = *reinterpret_cast<const f32x4*>(p.gx + ((((size_t)tt * B + colc) * p.D + d) * H + unit) * SLOTS);
         }
     };
-    // (In a launch with fused layers the first layer sets the pace of all of them and was measured
-    // faster with the request at the top of the step, as it always was there.)
-    if (!FUSED) fetch_gx(0);
+    if (!fused) fetch_gx(0);
 
     for (int s = 0; s < T; ++s) {
         const int t = d ? (T - 1 - s) : s;
-        if (FUSED && !fused) fetch_gx(s);
-
         f32x4 acc[RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        // A fused layer first consumes x_t = state of the layer below after its step s (slot s+1
-        // of that sequence; t == s when D == 1), then h_{t-1} of its own layer (slot s).  In steady
-        // state the layer trails the one below by a fixed offset: it waits for x_t, while its own
-        // h_{t-1} has been there for a while, so the x part stays off the recurrent critical path.
-        if (FUSED && fused)
-            ll_mma<TR, RT, KB>(wx, (uint32_t)(s + 1) * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
-                               probe_rel, stage, acc, epoch, p.status, p.spin_limit, aborted);
-        ll_mma<TR, RT, KB>(wh, own_off + (uint32_t)s * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
-                           probe_rel, stage, acc, epoch, p.status, p.spin_limit, aborted);
+        ll_wait<TR, KB>(own_off + (uint32_t)s * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane, probe_rel, stage,
+                        epoch, p.status, p.spin_limit, aborted);
+        ll_consume<TR, RT, KB>(wh, stage, ncol, lane, acc);
 
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) red[(((s & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+        for (int rt = 0; rt < RT; ++rt) red[(w * RT + rt) * 64 + lane] = acc[rt];
         f32x4 gx_now[NOWN];
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) gx_now[o] = gx_reg[o];
-        if (!FUSED) fetch_gx(s + 1);
+        if (!fused) fetch_gx(s + 1);
         __syncthreads();
 
         // all partial sums this wave needs are read before the first is used (one LDS round trip)
-        f32x4 part[NOWN][4];
+        f32x4 part[NOWN][FUSED ? 8 : 4];
 #pragma unroll
         for (int o = 0; o < NOWN; ++o)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                part[o][q] = red[(((s & 1) * 4 + q) * RT + min(w + 4 * o, RT - 1)) * 64 + lane];
+            for (int q = 0; q < 4; ++q) {
+                part[o][q] = red[(q * RT + min(w + 4 * o, RT - 1)) * 64 + lane];
+                if constexpr (FUSED) part[o][4 + q] = xred[(((s & 1) * 4 + q) * RT + min(w + 4 * o, RT - 1)) * 64 + lane];
+            }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int rt = w + 4 * o;
             if (rt < RT) {  // uniform per wave
                 f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
+                if constexpr (FUSED) {
+                    if (fused) a += (part[o][4] + part[o][5]) + (part[o][6] + part[o][7]);
+                }
                 if (!fused) a += gx_now[o];
                 a += bias_reg[o];
                 const bool active = valid && t < len;
@@ -334,6 +420,10 @@ __global__ __launch_bounds__(256) void wavefront_ll_kernel(WavefrontArgs p) {
             }
         }
         if (p.ticks && tid == 0 && rb == 0 && cb == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
+        // Second barrier of the step: no wave starts polling for the next state before the waves that
+        // finish tiles have issued their stores.  (Waves without a tile of their own otherwise poll
+        // from here on, fail, and every failed poll costs a full round trip more than waiting would.)
+        __syncthreads();
     }
 
 #pragma unroll
@@ -372,14 +462,15 @@ template <class TR, int CELL, int RT, int KB, bool FUSED>
 hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
     const int grid = a.LP * a.D * a.nrb * a.ncb;
     constexpr int QW = KB * TR::WORDS_PER_KW;
-    const size_t smem = (size_t)2 * 4 * RT * 64 * sizeof(f32x4) + (size_t)4 * 16 * (QW + 4) * sizeof(uint32_t);
+    const size_t smem = (size_t)(FUSED ? 3 : 1) * 4 * RT * 64 * sizeof(f32x4) +
+                        (size_t)(FUSED ? 8 : 4) * 16 * (QW + 4) * sizeof(uint32_t);
     auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, FUSED>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    kern<<<dim3(grid), dim3(256), smem, stream>>>(a);
+    kern<<<dim3(grid), dim3(FUSED ? 512 : 256), smem, stream>>>(a);
     return hipGetLastError();
 }
 
@@ -396,8 +487,11 @@ hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
 // (dtype traits, RT, KB) combinations that are compiled; KB = H / (4 * KW), CT is always 1.
 #define RNN_LL_VARIANTS(X)                                                       \
     X(LLBf16, 1, 1) X(LLBf16, 1, 2) X(LLBf16, 1, 4) X(LLBf16, 1, 8)               \
-    X(LLBf16, 2, 4) X(LLBf16, 2, 8) X(LLBf16, 4, 4) X(LLBf16, 4, 8)               \
-    X(LLF32, 1, 2) X(LLF32, 1, 4) X(LLF32, 1, 8) X(LLF32, 2, 4) X(LLF32, 2, 8)
+    X(LLBf16, 2, 1) X(LLBf16, 2, 2) X(LLBf16, 2, 4) X(LLBf16, 2, 8)               \
+    X(LLBf16, 4, 1) X(LLBf16, 4, 2) X(LLBf16, 4, 4) X(LLBf16, 4, 8)               \
+    X(LLF32, 1, 2) X(LLF32, 1, 4) X(LLF32, 1, 8)                                  \
+    X(LLF32, 2, 2) X(LLF32, 2, 4) X(LLF32, 2, 8)                                  \
+    X(LLF32, 4, 2) X(LLF32, 4, 4) X(LLF32, 4, 8)
 
 template <class TR> struct LLDtOf;
 template <> struct LLDtOf<LLBf16> { static constexpr int value = DT_BF16; };
