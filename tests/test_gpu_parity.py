@@ -64,6 +64,12 @@ SMALL = [
     ("lstm_f32_wide", 0, 1, 1, 64, 128, 5, 70, 0, False, False),
     ("lstm_bf16_oddshape", 0, 2, 1, 24, 72, 5, 4, 1, True, True),   # H not a multiple of 128: cellwise only
     ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
+    # small batches, several layers in one launch of the tag-in-data kernel (fused layers have their own waves
+    # for the input product): taller tiles, a quarter too large to be requested a step early, fp32
+    ("lstm_bf16_8layer_h256", 0, 8, 1, 48, 256, 12, 3, 1, True, True),     # 8 layers x 16 workgroups, 16-row tiles x 4
+    ("gru_bf16_2layer_h1024_b12", 1, 2, 1, 40, 1024, 6, 12, 1, True, True),  # x fetched after the barriers (12 x 128 words per wave)
+    ("lstm_f32_6layer_h128", 0, 6, 1, 24, 128, 9, 5, 0, True, True),
+    ("gru_bf16_4layer_h512_t1", 1, 4, 1, 32, 512, 1, 2, 1, False, True),   # a single step
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
     ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state
