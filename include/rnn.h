@@ -141,7 +141,8 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  * The call enqueues work on `stream` and returns without waiting; outputs are valid once the
  * stream has reached the end of that work.  It allocates device memory only if this shape needs
  * more workspace than earlier calls or rnn_model_reserve provided (then it synchronises).
- * x and y must not overlap.  Inputs are not validated on the device beyond the clamping above.
+ * x and y must not overlap and must be 16-byte aligned (RNN_EINVAL otherwise: the kernels read and
+ * write them in 16-byte pieces).  Inputs are not validated on the device beyond the clamping above.
  */
 int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,
                 const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream);

@@ -323,7 +323,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         char* base = (char*)((l == m->L - 1) ? y : m->ybuf[l].p);
         a.out[ll] = base;
         // a layer whose consumer reads the state sequence instead keeps no separate output
-        if ((xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
+        if (!tagged && (xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
     }
     a.gx = gx;
     a.xin = xin;
@@ -355,12 +355,13 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
 
 // A layer that runs alone in its launch, in one direction, on an input of its own width can do
 // its input product inside the recurrent kernel (wavefront_x.hip) instead of through a projection.
+// So can the first layer of a launch of the tag-in-data kernel (its x waves read the plain input).
 bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
+    if (plan.kind != RNN_PLAN_WAVEFRONT || m->D != 1 || m->layer_input(l) != m->H) return false;
+    if (plan.CT == 1 && plan.NCH == 1) return l % plan.LP == 0;   // layers above it are fused anyway
     // the first layer's input is first brought into the layout of a state sequence
     if (l == 0 && (T > 65535 || (size_t)16 * m->H * m->esize > 64 * 1024)) return false;
-    return plan.kind == RNN_PLAN_WAVEFRONT && plan.LP == 1 && m->D == 1 &&
-           !(plan.CT == 1 && plan.NCH == 1) && m->layer_input(l) == m->H &&
-           wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
+    return plan.LP == 1 && wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
 }
 
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
@@ -377,8 +378,9 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
     for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
         const bool inside = wavefront && input_product_inside(m, plan, l, T);
         if (!inside && (!wavefront || l % plan.LP == 0)) any_projection = true;
-        // a layer keeps an output of its own unless its consumer reads its state sequence instead
-        if (l + 1 < m->L && !inside) rc = grow(m, m->ybuf[l], rows * m->D * m->H * m->esize);
+        // a layer keeps an output of its own unless its consumer reads its state sequence instead (the
+        // inside-product kernel of large batches; the tag-in-data kernel's consumers read plain outputs)
+        if (l + 1 < m->L && (!inside || tagged)) rc = grow(m, m->ybuf[l], rows * m->D * m->H * m->esize);
     }
     if (rc == RNN_OK && any_projection) rc = grow(m, m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
     if (rc == RNN_OK && wavefront && !tagged) {
@@ -412,6 +414,12 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
     for (int l0 = 0; l0 < m->L; l0 += plan.LP) {
         const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
+        if (plan.CT == 1 && plan.NCH == 1 && input_product_inside(m, plan, l0, T)) {
+            // tag-in-data kernel: the x waves of the launch's first layer read the plain input
+            const int rc = launch_recurrent(m, plan, l0, LP, T, B, nullptr, y, lengths, h0, c0, hT, cT, st, in);
+            if (rc != RNN_OK) return rc;
+            continue;
+        }
         if (input_product_inside(m, plan, l0, T)) {
             // the first layer reads the caller's x, re-laid out; a layer above reads the state sequence below it
             if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, (int)blocked_rows(B), m->H, st));
@@ -606,6 +614,7 @@ int rnn_model_reserve(rnn_model* m, int T, int B) {
 int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
                 const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
     if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
+    if (((uintptr_t)x | (uintptr_t)y) & 15) return RNN_EINVAL;
     if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
     Plan plan;
     int rc = resolve_plan(m, T, B, plan);

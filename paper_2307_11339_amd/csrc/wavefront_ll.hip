@@ -227,6 +227,9 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
     const int ll = g / p.D, d = g - ll * p.D;
     const int l = p.l0 + ll;
     const bool fused = FUSED && ll > 0;
+    // the first layer of the launch multiplies its input itself (from a plain [T, B, H] tensor) when the
+    // host hands one over; otherwise it adds the projection gx
+    const bool plain_x = FUSED && ll == 0 && p.xin != nullptr;
     const bool write_out = (ll == p.LP - 1);         // only the last layer of a launch is read later
     const int H = p.H, B = p.B, T = p.T;
     const int kq = H / 4;
@@ -298,6 +301,45 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
             }
             __syncthreads();
             __syncthreads();
+        } else if (plain_x) {
+            // first layer of the launch: x_t is a finished tensor without tags, read straight into MFMA
+            // B fragments (lane (n, q) holds 8 consecutive inputs of sequence n), a step ahead
+            frag wx[RT][KB];
+            const elem* wih = static_cast<const elem*>(p.wih[g]);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) wx[rt][kb] = TR::load(wih + row * H + w * kq + kb * KW + TR::koff(lane));
+            }
+            const elem* xrow = static_cast<const elem*>(p.xin) +
+                               (size_t)(cb * 16 + min(lane & 15, ncol - 1)) * H + w * kq + TR::koff(lane);
+            frag xb[KB];
+            auto request = [&](int t) {
+                const elem* src = xrow + (size_t)min(t, T - 1) * B * H;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) xb[kb] = *reinterpret_cast<const frag*>(src + kb * KW);
+            };
+            request(0);
+            for (int sx = 0; sx < T; ++sx) {
+                if (sx > 0) {
+                    __syncthreads();
+                    __syncthreads();
+                }
+                f32x4 acc[RT];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wx[rt][kb], xb[kb], acc[rt]);
+                __builtin_amdgcn_sched_barrier(0);
+                request(sx + 1);   // in flight across the barriers of step sx
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) xred[(((sx & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+            }
+            __syncthreads();
+            __syncthreads();
         } else {
             for (int s = 0; s < T; ++s) {
                 __syncthreads();
@@ -360,7 +402,8 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
             gx_reg[o] = *reinterpret_cast<const f32x4*>(p.gx + ((((size_t)tt * B + colc) * p.D + d) * H + unit) * SLOTS);
         }
     };
-    if (!fused) fetch_gx(0);
+    const bool has_x = fused || plain_x;   // the input part comes from the x waves
+    if (!has_x) fetch_gx(0);
 
     for (int s = 0; s < T; ++s) {
         const int t = d ? (T - 1 - s) : s;
@@ -377,7 +420,7 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
         f32x4 gx_now[NOWN];
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) gx_now[o] = gx_reg[o];
-        if (!fused) fetch_gx(s + 1);
+        if (!has_x) fetch_gx(s + 1);
         __syncthreads();
 
         // all partial sums this wave needs are read before the first is used (one LDS round trip)
@@ -396,9 +439,9 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
             if (rt < RT) {  // uniform per wave
                 f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
                 if constexpr (FUSED) {
-                    if (fused) a += (part[o][4] + part[o][5]) + (part[o][6] + part[o][7]);
+                    if (has_x) a += (part[o][4] + part[o][5]) + (part[o][6] + part[o][7]);
                 }
-                if (!fused) a += gx_now[o];
+                if (!has_x) a += gx_now[o];
                 a += bias_reg[o];
                 const bool active = valid && t < len;
                 float c_new = c_reg[o];
@@ -476,7 +519,7 @@ hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
 
 template <class TR, int RT, int KB>
 hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
-    const bool fused = a.LP > 1;
+    const bool fused = a.LP > 1 || a.xin != nullptr;   // workgroups with x waves
     if (a.cell == CELL_LSTM)
         return fused ? launch_ll_variant<TR, CELL_LSTM, RT, KB, true>(a, stream)
                      : launch_ll_variant<TR, CELL_LSTM, RT, KB, false>(a, stream);

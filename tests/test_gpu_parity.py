@@ -70,6 +70,10 @@ SMALL = [
     ("gru_bf16_2layer_h1024_b12", 1, 2, 1, 40, 1024, 6, 12, 1, True, True),  # x fetched after the barriers (12 x 128 words per wave)
     ("lstm_f32_6layer_h128", 0, 6, 1, 24, 128, 9, 5, 0, True, True),
     ("gru_bf16_4layer_h512_t1", 1, 4, 1, 32, 512, 1, 2, 1, False, True),   # a single step
+    # input as wide as the layer: the first layer of the launch multiplies the plain input itself (no projection)
+    ("lstm_bf16_3layer_sq_h256", 0, 3, 1, 256, 256, 11, 7, 1, True, True),
+    ("gru_f32_2layer_sq_h64", 1, 2, 1, 64, 64, 9, 19, 0, True, True),
+    ("lstm_bf16_1layer_sq_h512", 0, 1, 1, 512, 512, 8, 1, 1, False, False),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
     ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state
@@ -410,6 +414,12 @@ def test_input_product_placement(gpu):
     assert [rnn.rnn_model_input_product_placement(model.handle, c.T, 2, l)[1] for l in range(c.L)] == [1, 0]
     assert rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, c.L)[0] == rnn.RNN_EINVAL
     assert rnn.rnn_model_input_product_placement(model.handle, 0, c.B, 0)[0] == rnn.RNN_EINVAL
+    # x and y must be 16-byte aligned
+    io = harness.DeviceIO(wl)
+    import torch
+    xv = io.x.view(-1)[1:]
+    assert rnn.rnn_forward(model.handle, xv, io.lengths, io.h0, io.c0, io.y, io.hT, io.cT, 1, 1,
+                           torch.cuda.current_stream()) == rnn.RNN_EINVAL
     model.close()
     # square first layer: no projection launch at all
     wl = _small_workload(W, by_name["lstm_bf16_inside_sq"])
@@ -418,6 +428,12 @@ def test_input_product_placement(gpu):
     assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l)[1] for l in range(c.L)] == [0, 0]
     assert rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_CELLWISE) == rnn.RNN_OK
     assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l)[1] for l in range(c.L)] == [1, 1]
+    model.close()
+    # small batch, square first layer: the tag-in-data kernel's first layer reads the plain input
+    wl = _small_workload(W, by_name["lstm_bf16_3layer_sq_h256"])
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    c = wl.cfg
+    assert [rnn.rnn_model_input_product_placement(model.handle, c.T, c.B, l)[1] for l in range(c.L)] == [0, 0, 0]
     model.close()
 
 
