@@ -199,6 +199,24 @@ int rnn_model_input_product_placement(const rnn_model* model, int T, int B, int 
  * (the quantity the paper's memory model sums per operator, Section 3, Equation 4). */
 size_t rnn_model_device_bytes(const rnn_model* model);
 
+/*
+ * How the library would lay the cell grid (Section 2.2) of a model of this shape over a GPU with
+ * `compute_units` compute units and `lds_bytes` of LDS per workgroup, for calls of T steps and B
+ * sequences.  Pure host code: no model, no device and no GPU are needed (all pointers are HOST
+ * pointers owned by the caller).  requested_plan as in rnn_model_set_plan.
+ *   plan[8]: resolved plan (RNN_PLAN_CELLWISE or RNN_PLAN_WAVEFRONT), layers per launch, then for
+ *            the persistent kernels the workgroup tile (16-row tiles, 16-sequence column tiles per
+ *            chain, chains per workgroup), row blocks, chains (column blocks) and the number of
+ *            recurrent launches per forward pass; zeros where the cellwise plan has no such figure.
+ *   separate_projection[num_layers] (may be NULL): 1 where W_ih x_t of that layer is a projection
+ *            launch of its own, 0 where it is computed inside the recurrent kernel.
+ * Returns RNN_EINVAL / RNN_EUNSUPPORTED for the shapes rnn_model_create rejects and for a requested
+ * plan the shape cannot run under.
+ */
+int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, int num_directions,
+                   int dtype, int requested_plan, int T, int B, int compute_units, size_t lds_bytes,
+                   int* plan, int* separate_projection);
+
 /* Static, NUL-terminated description of an rnn_status value. */
 const char* rnn_status_string(int status);
 

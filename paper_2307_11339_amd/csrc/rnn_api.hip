@@ -31,6 +31,7 @@ struct rnn_model {
     int cell, L, I, H, D, dtype;
     int device = 0;
     int num_cus = 0;
+    size_t lds_limit = 0;   // LDS bytes one workgroup may use
     int requested_plan = RNN_PLAN_AUTO;
     size_t esize = 4;  // bytes per stored element
 
@@ -361,7 +362,7 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
     if (plan.CT == 1 && plan.NCH == 1) return l % plan.LP == 0;   // layers above it are fused anyway
     // the first layer's input is first brought into the layout of a state sequence
     if (l == 0 && (T > 65535 || (size_t)16 * m->H * m->esize > 64 * 1024)) return false;
-    return plan.LP == 1 && wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H);
+    return plan.LP == 1 && wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit);
 }
 
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
@@ -405,6 +406,19 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
     }
     if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
     return rc;
+}
+
+// Shapes the library accepts (rnn_model_create_ordered, rnn_plan_query).
+int check_model_shape(int cell, int num_layers, int input_size, int hidden_size, int num_directions, int dtype) {
+    if (cell != RNN_LSTM && cell != RNN_GRU) return RNN_EINVAL;
+    if (dtype != RNN_F32 && dtype != RNN_BF16) return RNN_EINVAL;
+    if (num_layers < 1 || input_size < 1 || hidden_size < 1) return RNN_EINVAL;
+    if (num_directions != 1 && num_directions != 2) return RNN_EINVAL;
+    if (num_layers > 1024 || input_size > (1 << 20) || hidden_size > (1 << 16)) return RNN_EUNSUPPORTED;
+    const int align = (dtype == RNN_BF16) ? 8 : 4;
+    if (hidden_size % align != 0) return RNN_EUNSUPPORTED;
+    if (dtype == RNN_BF16 && input_size % 8 != 0) return RNN_EUNSUPPORTED;
+    return RNN_OK;
 }
 
 int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths,
@@ -456,14 +470,10 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
                              int weights_on_device, int gate_order) {
     if (!out || !weights) return RNN_EINVAL;
     if (gate_order != RNN_ORDER_IFGO_RZN && gate_order != RNN_ORDER_ONNX) return RNN_EINVAL;
-    if (cell != RNN_LSTM && cell != RNN_GRU) return RNN_EINVAL;
-    if (dtype != RNN_F32 && dtype != RNN_BF16) return RNN_EINVAL;
-    if (num_layers < 1 || input_size < 1 || hidden_size < 1) return RNN_EINVAL;
-    if (num_directions != 1 && num_directions != 2) return RNN_EINVAL;
-    if (num_layers > 1024 || input_size > (1 << 20) || hidden_size > (1 << 16)) return RNN_EUNSUPPORTED;
-    const int align = (dtype == RNN_BF16) ? 8 : 4;
-    if (hidden_size % align != 0) return RNN_EUNSUPPORTED;
-    if (dtype == RNN_BF16 && input_size % 8 != 0) return RNN_EUNSUPPORTED;
+    {
+        const int rc = check_model_shape(cell, num_layers, input_size, hidden_size, num_directions, dtype);
+        if (rc != RNN_OK) return rc;
+    }
     const int G = (cell == RNN_LSTM) ? 4 : 3;
     for (int i = 0; i < num_layers * num_directions * 4; ++i)
         if ((i % 4) < 2 && !weights[i]) return RNN_EINVAL;  // the two matrices are mandatory
@@ -482,6 +492,7 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
         return RNN_EDEVICE;
     }
     m->num_cus = prop.multiProcessorCount;
+    m->lds_limit = prop.sharedMemPerBlock;
 
     const int H = m->H, D = m->D;
     m->wih.resize(m->L);
@@ -686,6 +697,38 @@ int rnn_model_input_product_placement(const rnn_model* m, int T, int B, int laye
     if (plan.kind != RNN_PLAN_WAVEFRONT) *separate_launch = 1;
     else if (input_product_inside(m, plan, layer, T)) *separate_launch = 0;
     else *separate_launch = (layer % plan.LP == 0) ? 1 : 0;  // layers above the first of a launch are fused
+    return RNN_OK;
+}
+
+int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, int num_directions, int dtype,
+                   int requested_plan, int T, int B, int compute_units, size_t lds_bytes, int* plan_out,
+                   int* separate_projection) {
+    if (!plan_out || T < 1 || B < 1 || compute_units < 1) return RNN_EINVAL;
+    if (requested_plan != RNN_PLAN_AUTO && requested_plan != RNN_PLAN_CELLWISE && requested_plan != RNN_PLAN_WAVEFRONT)
+        return RNN_EINVAL;
+    int rc = check_model_shape(cell, num_layers, input_size, hidden_size, num_directions, dtype);
+    if (rc != RNN_OK) return rc;
+    rnn_model m;   // shape and device figures only: no buffer is touched
+    m.cell = cell; m.L = num_layers; m.I = input_size; m.H = hidden_size; m.D = num_directions; m.dtype = dtype;
+    m.esize = (dtype == RNN_BF16) ? 2 : 4;
+    m.num_cus = compute_units;
+    m.lds_limit = lds_bytes;
+    m.requested_plan = requested_plan;
+    Plan plan;
+    rc = resolve_plan(&m, T, B, plan);
+    if (rc != RNN_OK) return rc;
+    const bool wavefront = plan.kind == RNN_PLAN_WAVEFRONT;
+    plan_out[0] = plan.kind;
+    plan_out[1] = wavefront ? plan.LP : 1;
+    plan_out[2] = wavefront ? plan.RT : 0;
+    plan_out[3] = wavefront ? plan.CT : 0;
+    plan_out[4] = wavefront ? plan.NCH : 0;
+    plan_out[5] = wavefront ? plan.nrb : 0;
+    plan_out[6] = wavefront ? plan.ncb : 0;
+    plan_out[7] = wavefront ? (num_layers + plan.LP - 1) / plan.LP : num_layers;
+    if (separate_projection)
+        for (int l = 0; l < num_layers; ++l)
+            separate_projection[l] = !wavefront ? 1 : input_product_inside(&m, plan, l, T) ? 0 : (l % plan.LP == 0) ? 1 : 0;
     return RNN_OK;
 }
 

@@ -510,13 +510,13 @@ template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
 }  // namespace
 
-bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H) {
+bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit) {
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (H % (4 * kw) != 0) return false;
     const int KB = H / (4 * kw);
 #define X(TR, rt, ct, kb, nch)                                                               \
     if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb && NCH == nch)          \
-        return lds_bytes<TR, rt, ct, kb>() <= (size_t)device_lds_limit();
+        return lds_bytes<TR, rt, ct, kb>() <= lds_limit;
     RNN_WFX_VARIANTS(X)
 #undef X
     return false;

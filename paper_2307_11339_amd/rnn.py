@@ -28,7 +28,7 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
-           "rnn_model_set_gru_reset_before")
+           "rnn_model_set_gru_reset_before", "rnn_plan_query")
 
 _lib = None
 
@@ -71,6 +71,9 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_device_bytes.argtypes = [vp]
     lib.rnn_model_input_product_placement.restype = ci
     lib.rnn_model_input_product_placement.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci)]
+    lib.rnn_plan_query.restype = ci
+    lib.rnn_plan_query.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.c_size_t, ctypes.POINTER(ci),
+                                   ctypes.POINTER(ci)]
     lib.rnn_status_string.restype = ctypes.c_char_p
     lib.rnn_status_string.argtypes = [ci]
     lib.rnn_model_set_profiling.restype = ci
@@ -173,6 +176,19 @@ def rnn_model_input_product_placement(model: int, T: int, B: int, layer: int):
     out = ctypes.c_int(-1)
     rc = load_library().rnn_model_input_product_placement(model, T, B, layer, ctypes.byref(out))
     return rc, out.value
+
+
+PLAN_FIELDS = ("kind", "layers_per_launch", "row_tiles", "col_tiles", "chains", "row_blocks", "col_blocks", "launches")
+
+
+def rnn_plan_query(cell: int, num_layers: int, input_size: int, hidden_size: int, num_directions: int, dtype: int,
+                   requested_plan: int, T: int, B: int, compute_units: int, lds_bytes: int):
+    """Host only (no GPU needed).  Returns (status, plan dict keyed by PLAN_FIELDS, separate_projection list)."""
+    plan = (ctypes.c_int * 8)()
+    sep = (ctypes.c_int * max(num_layers, 1))()
+    rc = load_library().rnn_plan_query(cell, num_layers, input_size, hidden_size, num_directions, dtype,
+                                       requested_plan, T, B, compute_units, lds_bytes, plan, sep)
+    return rc, dict(zip(PLAN_FIELDS, list(plan))), list(sep)[:max(num_layers, 0)]
 
 
 def rnn_model_set_profiling(model: int, flags: int) -> int:

@@ -1,0 +1,109 @@
+"""Host logic of the library: which execution plan it chooses for a model shape on a GPU with a given
+number of compute units and LDS size (include/rnn.h, rnn_plan_query).  Runs without a GPU."""
+import random
+
+import pytest
+
+from paper_2307_11339_amd import rnn, workloads as W
+
+CUS, LDS = 256, 160 * 1024      # MI355X
+
+
+def _query(c, plan=rnn.RNN_PLAN_AUTO, cus=CUS, lds=LDS, T=None, B=None):
+    return rnn.rnn_plan_query(c.cell, c.L, c.I, c.H, c.D, c.dtype, plan, T or c.T, B or c.B, cus, lds)
+
+
+def test_named_workloads():
+    """The five named workloads on an MI355X: the plans the measurements in the design notes refer to."""
+    expect = {
+        # layers per launch, tile (16-row tiles, column tiles, chains), row blocks, column blocks, launches, projections
+        "C1": (1, (1, 1, 1), 32, 1, 1, [1]),
+        "C2": (2, (4, 1, 1), 32, 1, 1, [1, 0]),
+        "C3": (4, (4, 1, 1), 64, 1, 1, [0, 0, 0, 0]),
+        "C4": (1, (4, 1, 1), 32, 4, 2, [1, 1]),
+        "C5": (1, (4, 2, 2), 64, 8, 8, [0] * 8),
+    }
+    for name, (lp, tile, nrb, ncb, launches, proj) in expect.items():
+        rc, plan, sep = _query(W.CONFIGS[name])
+        assert rc == rnn.RNN_OK, name
+        assert plan["kind"] == rnn.RNN_PLAN_WAVEFRONT, name
+        assert plan["layers_per_launch"] == lp, name
+        assert (plan["row_tiles"], plan["col_tiles"], plan["chains"]) == tile, name
+        assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (nrb, ncb, launches), name
+        assert sep == proj, name
+
+
+def test_cellwise_requested_or_forced():
+    c = W.CONFIGS["C2"]
+    rc, plan, sep = _query(c, plan=rnn.RNN_PLAN_CELLWISE)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_CELLWISE
+    assert sep == [1] * c.L and plan["launches"] == c.L
+    # a width no persistent kernel is compiled for: AUTO falls back to cellwise, WAVEFRONT is refused
+    odd = W.Config("odd", W.LSTM, L=2, D=1, I=24, H=72, T=5, B=4, dtype=W.BF16, seed=1)
+    rc, plan, _ = _query(odd)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_CELLWISE
+    assert _query(odd, plan=rnn.RNN_PLAN_WAVEFRONT)[0] == rnn.RNN_EUNSUPPORTED
+
+
+def test_fewer_compute_units_mean_more_launches():
+    c = W.CONFIGS["C3"]
+    rc, plan, sep = _query(c, cus=64, lds=64 * 1024)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert plan["layers_per_launch"] == 1 and plan["launches"] == 4 and plan["row_blocks"] == 64
+    assert sep == [0, 0, 0, 0]          # every launch's first layer reads its plain input itself
+    # a GPU too small for one layer of this width
+    rc, plan, _ = _query(c, cus=8, lds=64 * 1024)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_CELLWISE
+
+
+def test_inside_product_needs_lds_for_the_weights():
+    """Large batch, one layer per launch: W_ih lives in LDS; without enough LDS the layer projects."""
+    c = W.CONFIGS["C5"]
+    rc, plan, sep = _query(c, lds=64 * 1024)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert sep == [1] * 8
+
+
+def test_invariants_over_random_shapes():
+    rng = random.Random(20230711)
+    seen_kinds = set()
+    for _ in range(400):
+        dtype = rng.choice([W.F32, W.BF16])
+        H = rng.choice([32, 64, 128, 256, 512, 1024]) if rng.random() < 0.8 else 8 * rng.randint(1, 40)
+        c = W.Config("r", rng.choice([W.LSTM, W.GRU]), L=rng.randint(1, 16), D=rng.choice([1, 2]),
+                     I=8 * rng.randint(1, 64), H=H, T=rng.randint(1, 300), B=rng.choice([1, 2, 8, 17, 64, 100, 256, 500]),
+                     dtype=dtype, seed=1)
+        cus = rng.choice([64, 128, 256])
+        rc, plan, sep = _query(c, cus=cus)
+        assert rc == rnn.RNN_OK
+        seen_kinds.add(plan["kind"])
+        assert len(sep) == c.L and set(sep) <= {0, 1}
+        if plan["kind"] == rnn.RNN_PLAN_CELLWISE:
+            assert sep == [1] * c.L
+            continue
+        lp, rt, ct, nch = plan["layers_per_launch"], plan["row_tiles"], plan["col_tiles"], plan["chains"]
+        assert plan["launches"] * lp >= c.L and (plan["launches"] - 1) * lp < c.L
+        assert c.D == 1 or lp == 1                      # bidirectional layers cannot share a launch
+        assert plan["row_blocks"] * rt * 4 == c.H       # 16 gate rows = 4 hidden units per tile
+        assert plan["col_blocks"] * ct * 16 >= c.B and plan["col_blocks"] % nch == 0
+        # all workgroups of a launch are resident at once: at most one per compute unit
+        assert lp * c.D * plan["row_blocks"] * (plan["col_blocks"] // nch) <= cus
+        # only the first layer of a launch can need a projection launch
+        assert all(sep[l] == 0 for l in range(c.L) if l % lp != 0)
+    assert seen_kinds == {rnn.RNN_PLAN_CELLWISE, rnn.RNN_PLAN_WAVEFRONT}
+
+
+def test_errors():
+    c = W.CONFIGS["C1"]
+    q = lambda **kw: rnn.rnn_plan_query(kw.get("cell", c.cell), kw.get("L", c.L), c.I, kw.get("H", c.H), kw.get("D", c.D),
+                                        c.dtype, kw.get("plan", rnn.RNN_PLAN_AUTO), kw.get("T", c.T), kw.get("B", c.B),
+                                        kw.get("cus", CUS), LDS)[0]
+    assert q() == rnn.RNN_OK
+    assert q(cell=7) == rnn.RNN_EINVAL
+    assert q(L=0) == rnn.RNN_EINVAL
+    assert q(D=3) == rnn.RNN_EINVAL
+    assert q(T=0) == rnn.RNN_EINVAL
+    assert q(B=0) == rnn.RNN_EINVAL
+    assert q(cus=0) == rnn.RNN_EINVAL
+    assert q(plan=9) == rnn.RNN_EINVAL
+    assert q(H=30) == rnn.RNN_EUNSUPPORTED           # fp32 widths are multiples of 4
