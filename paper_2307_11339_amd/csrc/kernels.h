@@ -59,10 +59,12 @@ struct WavefrontArgs {
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
     const float* gx;             // projection of layer l0: [T*B, D, H, 4] (unused when xin is given)
-    const void* xin;             // NULL, or the finished input of layer l0 (D = 1, input width H) in
-                                 // the layout of a state sequence, [T][H/16][B][16]: layer l0 then
-                                 // multiplies it with its resident W_ih inside the kernel instead
-                                 // of reading gx
+    const void* xin;             // NULL, or the finished input of layer l0, which then multiplies it
+                                 // with its resident W_ih inside the kernel instead of reading gx.
+                                 // wavefront_x.hip: D = 1, width H, in the layout of a state sequence
+                                 // [T][H/16][Bp][16]; wavefront_ll.hip: plain [T, B, xin_width * H]
+    int xin_width;               // wavefront_ll.hip: width of xin in units of H (1, or 2 for a
+                                 // bidirectional layer above the first)
     void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type (the kernel of
                                  // wavefront_x.hip accepts NULL: output not wanted)
     void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state

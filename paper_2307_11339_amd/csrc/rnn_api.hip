@@ -328,6 +328,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     }
     a.gx = gx;
     a.xin = xin;
+    a.xin_width = (tagged && xin) ? m->layer_input(l0) / m->H : 0;
     if (x_from_state)  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
         a.xin = (const char*)state_region(m, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
     a.hseq = state_region(m, l0, T, B);
@@ -358,8 +359,17 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
 // its input product inside the recurrent kernel (wavefront_x.hip) instead of through a projection.
 // So can the first layer of a launch of the tag-in-data kernel (its x waves read the plain input).
 bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
-    if (plan.kind != RNN_PLAN_WAVEFRONT || m->D != 1 || m->layer_input(l) != m->H) return false;
-    if (plan.CT == 1 && plan.NCH == 1) return l % plan.LP == 0;   // layers above it are fused anyway
+    if (plan.kind != RNN_PLAN_WAVEFRONT) return false;
+    if (plan.CT == 1 && plan.NCH == 1) {
+        // tag-in-data kernel, first layer of a launch (layers above it in the launch are fused anyway): its
+        // x waves hold the W_ih slice in registers, which fits for an input H wide, or 2H wide (a
+        // bidirectional layer above the first) with small tiles
+        if (l % plan.LP != 0) return false;
+        const int kw = (m->dtype == DT_BF16) ? 32 : 4;          // K elements per MFMA
+        if (m->layer_input(l) == m->H) return true;
+        return m->D == 2 && m->layer_input(l) == 2 * m->H && plan.RT * (m->H / (4 * kw)) * 2 <= 32;
+    }
+    if (m->D != 1 || m->layer_input(l) != m->H) return false;
     // the first layer's input is first brought into the layout of a state sequence
     if (l == 0 && (T > 65535 || (size_t)16 * m->H * m->esize > 64 * 1024)) return false;
     return plan.LP == 1 && wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit);

@@ -194,8 +194,11 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
 // right after them, i.e. while the h waves wait for h_t to come round.  The input product is then off
 // the recurrent critical path, and neither wave type holds two sets of weights (with both sets in
 // one wave the compiler parks one in the accumulator registers and copies it back before every MFMA).
-template <class TR, int CELL, int RT, int KB, bool FUSED>
-__global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
+// XW: 0 = no x waves; 1 = x waves, inputs as wide as the layer; 2 = x waves, a plain input twice as wide
+// (a bidirectional layer above the first, which reads [forward, backward] of the layer below).
+template <class TR, int CELL, int RT, int KB, int XW>
+__global__ __launch_bounds__(XW ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
+    constexpr bool FUSED = XW > 0;
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
     constexpr int KW = TR::KW;
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
     const int cb = r / p.nrb, rb = r - cb * p.nrb;
     const int ll = g / p.D, d = g - ll * p.D;
     const int l = p.l0 + ll;
-    const bool fused = FUSED && ll > 0;
+    const bool fused = XW == 1 && ll > 0;
     // the first layer of the launch multiplies its input itself (from a plain [T, B, H] tensor) when the
     // host hands one over; otherwise it adds the projection gx
     const bool plain_x = FUSED && ll == 0 && p.xin != nullptr;
@@ -304,42 +307,51 @@ __global__ __launch_bounds__(FUSED ? 512 : 256) void wavefront_ll_kernel(Wavefro
         } else if (plain_x) {
             // first layer of the launch: x_t is a finished tensor without tags, read straight into MFMA
             // B fragments (lane (n, q) holds 8 consecutive inputs of sequence n), a step ahead
-            frag wx[RT][KB];
-            const elem* wih = static_cast<const elem*>(p.wih[g]);
+            constexpr int KBX = (XW > 0 ? XW : 1) * KB;   // K blocks of this wave's quarter of the input
+            const int IW = (XW > 0 ? XW : 1) * H;         // input width
+            frag wx[RT][KBX];
+            // W_ih of all directions is one matrix [D * 4H, IW]; direction d owns rows d * 4H ...
+            const elem* wih = static_cast<const elem*>(p.wih[g]) + (size_t)d * 4 * H * IW;
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) {
                 const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) wx[rt][kb] = TR::load(wih + row * H + w * kq + kb * KW + TR::koff(lane));
+                for (int kb = 0; kb < KBX; ++kb)
+                    wx[rt][kb] = TR::load(wih + row * IW + w * (IW / 4) + kb * KW + TR::koff(lane));
             }
             const elem* xrow = static_cast<const elem*>(p.xin) +
-                               (size_t)(cb * 16 + min(lane & 15, ncol - 1)) * H + w * kq + TR::koff(lane);
-            frag xb[KB];
-            auto request = [&](int t) {
-                const elem* src = xrow + (size_t)min(t, T - 1) * B * H;
+                               (size_t)(cb * 16 + min(lane & 15, ncol - 1)) * IW + w * (IW / 4) + TR::koff(lane);
+            // x_t is requested NBUF steps ahead, between the two barriers of a step: the h waves are in
+            // their gate phase then and have no polls in flight that the request could hold up.  Two
+            // register sets used in turn where they fit beside the weights (x may come from HBM).
+            constexpr int NBUF = (RT * KBX + 2 * KBX <= 48 && KB <= 4) ? 2 : 1;
+            frag xb[NBUF][KBX];
+            auto request = [&](int s, frag (&dst)[KBX]) {   // the step of this direction's order that is s-th
+                const int sc = min(s, T - 1);
+                const elem* src = xrow + (size_t)(d ? T - 1 - sc : sc) * B * IW;
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) xb[kb] = *reinterpret_cast<const frag*>(src + kb * KW);
+                for (int kb = 0; kb < KBX; ++kb) dst[kb] = *reinterpret_cast<const frag*>(src + kb * KW);
             };
-            request(0);
-            for (int sx = 0; sx < T; ++sx) {
-                if (sx > 0) {
-                    __syncthreads();
-                    __syncthreads();
-                }
+            auto produce = [&](int sx, frag (&cur)[KBX]) {
                 f32x4 acc[RT];
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
+                for (int kb = 0; kb < KBX; ++kb)
 #pragma unroll
-                    for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wx[rt][kb], xb[kb], acc[rt]);
-                __builtin_amdgcn_sched_barrier(0);
-                request(sx + 1);   // in flight across the barriers of step sx
+                    for (int rt = 0; rt < RT; ++rt) acc[rt] = TR::mfma(wx[rt][kb], cur[kb], acc[rt]);
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt) xred[(((sx & 1) * 4 + w) * RT + rt) * 64 + lane] = acc[rt];
+                __syncthreads();            // first barrier of step sx: the partial sums are in LDS
+                request(sx + NBUF, cur);
+                __syncthreads();            // second barrier of step sx
+            };
+#pragma unroll
+            for (int b = 0; b < NBUF; ++b) request(b, xb[b]);
+            for (int sx = 0; sx < T; sx += NBUF) {
+                produce(sx, xb[0]);
+                if (NBUF > 1 && sx + 1 < T) produce(sx + 1, xb[NBUF - 1]);
             }
-            __syncthreads();
-            __syncthreads();
         } else {
             for (int s = 0; s < T; ++s) {
                 __syncthreads();
@@ -501,30 +513,42 @@ __global__ void wavefront_ll_init_kernel(const float* h0, int l0, int LP, int D,
     lseq[g * (size_t)(T + 1) * per + rem] = ((uint64_t)epoch << 32) | payload;
 }
 
-template <class TR, int CELL, int RT, int KB, bool FUSED>
+template <class TR, int CELL, int RT, int KB, int XW>
 hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
     const int grid = a.LP * a.D * a.nrb * a.ncb;
     constexpr int QW = KB * TR::WORDS_PER_KW;
-    const size_t smem = (size_t)(FUSED ? 3 : 1) * 4 * RT * 64 * sizeof(f32x4) +
-                        (size_t)(FUSED ? 8 : 4) * 16 * (QW + 4) * sizeof(uint32_t);
-    auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, FUSED>;
+    const size_t smem = (size_t)(XW ? 3 : 1) * 4 * RT * 64 * sizeof(f32x4) +
+                        (size_t)(XW ? 8 : 4) * 16 * (QW + 4) * sizeof(uint32_t);
+    auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, XW>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
     }
-    kern<<<dim3(grid), dim3(FUSED ? 512 : 256), smem, stream>>>(a);
+    kern<<<dim3(grid), dim3(XW ? 512 : 256), smem, stream>>>(a);
     return hipGetLastError();
+}
+
+template <class TR, int RT, int KB, int XW>
+hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
+    if (a.cell == CELL_LSTM) return launch_ll_variant<TR, CELL_LSTM, RT, KB, XW>(a, stream);
+    return launch_ll_variant<TR, CELL_GRU, RT, KB, XW>(a, stream);
 }
 
 template <class TR, int RT, int KB>
 hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
-    const bool fused = a.LP > 1 || a.xin != nullptr;   // workgroups with x waves
-    if (a.cell == CELL_LSTM)
-        return fused ? launch_ll_variant<TR, CELL_LSTM, RT, KB, true>(a, stream)
-                     : launch_ll_variant<TR, CELL_LSTM, RT, KB, false>(a, stream);
-    return fused ? launch_ll_variant<TR, CELL_GRU, RT, KB, true>(a, stream)
-                 : launch_ll_variant<TR, CELL_GRU, RT, KB, false>(a, stream);
+    // workgroups with x waves: fused layers, or a first layer that multiplies its plain input itself
+    // (a.xin_width = that input's width in units of H)
+    if (a.xin != nullptr && a.xin_width == 2) {
+        if constexpr (RT * KB * 2 <= 32) {       // the x waves hold RT * 2KB weight fragments
+            if (a.LP != 1) return hipErrorInvalidValue;
+            return launch_ll_cell<TR, RT, KB, 2>(a, stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if (a.LP > 1 || a.xin != nullptr) return launch_ll_cell<TR, RT, KB, 1>(a, stream);
+    return launch_ll_cell<TR, RT, KB, 0>(a, stream);
 }
 
 // (dtype traits, RT, KB) combinations that are compiled; KB = H / (4 * KW), CT is always 1.

@@ -20,7 +20,7 @@ def test_named_workloads():
         "C1": (1, (1, 1, 1), 32, 1, 1, [1]),
         "C2": (2, (4, 1, 1), 32, 1, 1, [1, 0]),
         "C3": (4, (4, 1, 1), 64, 1, 1, [0, 0, 0, 0]),
-        "C4": (1, (4, 1, 1), 32, 4, 2, [1, 1]),
+        "C4": (1, (4, 1, 1), 32, 4, 2, [0, 0]),     # both directions; the upper layer reads [forward, backward] of the lower
         "C5": (1, (4, 2, 2), 64, 8, 8, [0] * 8),
     }
     for name, (lp, tile, nrb, ncb, launches, proj) in expect.items():
