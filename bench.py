@@ -116,6 +116,40 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
     return cfg, out
 
 
+def time_projection_gemm(name: str, reps: int = 10):
+    """The batched input projection X W_ih^T of one layer of the workload over all time steps, as a launch of its
+    own (rnn_input_projection).  No named workload needs it any more (their input products run inside the
+    recurrent kernels), so it is measured here on its own: it serves every layer whose input is not H/2, H or 2H
+    wide, and the cellwise plan."""
+    import torch
+    from paper_2307_11339_amd import harness, rnn, workloads as W
+
+    cfg = W.CONFIGS[name]
+    wl = W.make_workload(cfg.scaled(L=1, T=1, B=1, len_min=None, h0_std=0.0))   # one layer of weights; activations are made here
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_CELLWISE)
+    rows, K, N = cfg.T * cfg.B, cfg.I, cfg.D * 4 * cfg.H
+    tdt = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+    a = torch.randn(rows, K, device="cuda", dtype=torch.float32).to(tdt)
+    gx = torch.empty(rows, N, device="cuda", dtype=torch.float32)
+    st = torch.cuda.current_stream()
+    for _ in range(3):
+        rnn.rnn_input_projection(model.handle, 0, a, gx, rows, st)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(reps):
+        rnn.rnn_input_projection(model.handle, 0, a, gx, rows, st)
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    model.close()
+    flops = 2.0 * rows * K * N
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == 1 else PEAK_F32_TFLOPS
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"shape": {"M": rows, "K": K, "N": N}, "ms": round(ms, 4), "tflops": round(tf, 2),
+            "frac_of_mfma_peak": round(tf / peak, 4),
+            "output_bytes": rows * N * 4, "output_gbps": round(rows * N * 4 / (ms * 1e-3) / 1e9, 1)}
+
+
 def cpu_baseline(name: str, n_seq: int):
     """The oracle as it stands, timed on the host cores for a bounded sample of the workload."""
     import numpy as np
@@ -156,6 +190,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C5")
     ap.add_argument("--no-extra", action="store_true", help="skip the other named workloads")
+    ap.add_argument("--projection-gemm", action="store_true",
+                    help="time only the stand-alone input projection of one layer of the workload and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB mebibytes five times (reference reading "
@@ -172,6 +208,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.projection_gemm:
+        print(json.dumps({"projection_gemm": time_projection_gemm(args.workload)}))
+        return 0
     if args.copy_calibration > 0:
         n = args.copy_calibration << 20
         src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
@@ -267,6 +306,9 @@ def main() -> int:
             grid[c.name] = {"p50_ms": round(r["p50_ms"], 4), "ms_per_call": round(r["ms_per_step"], 4),
                             "device_mb": round(r["device_bytes"] / 1e6, 3)}
         line["paper_grid"] = grid
+
+    if not args.no_extra:
+        line["projection_gemm"] = time_projection_gemm(args.workload)
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)

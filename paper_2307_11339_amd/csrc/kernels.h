@@ -62,9 +62,10 @@ struct WavefrontArgs {
     const void* xin;             // NULL, or the finished input of layer l0, which then multiplies it
                                  // with its resident W_ih inside the kernel instead of reading gx.
                                  // wavefront_x.hip: D = 1, width H, in the layout of a state sequence
-                                 // [T][H/16][Bp][16]; wavefront_ll.hip: plain [T, B, xin_width * H]
-    int xin_width;               // wavefront_ll.hip: width of xin in units of H (1, or 2 for a
-                                 // bidirectional layer above the first)
+                                 // [T][H/16][Bp][16]; wavefront_ll.hip: plain [T, B, xin_width2 * H / 2]
+    int xin_width2;              // wavefront_ll.hip: twice the width of xin over H: 2 (as wide as the
+                                 // layer), 1 (half as wide), 4 (a bidirectional layer above
+                                 // the first, LP = 1)
     void* out[WF_MAX_LAYERS];    // output of each local layer: [T, B, D*H] storage type (the kernel of
                                  // wavefront_x.hip accepts NULL: output not wanted)
     void* hseq;                  // [LP*D, T+1, B, H] storage type: slot 0 = h0, slot s+1 = state

@@ -328,7 +328,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     }
     a.gx = gx;
     a.xin = xin;
-    a.xin_width = (tagged && xin) ? m->layer_input(l0) / m->H : 0;
+    a.xin_width2 = (tagged && xin) ? 2 * m->layer_input(l0) / m->H : 0;
     if (x_from_state)  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
         a.xin = (const char*)state_region(m, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
     a.hseq = state_region(m, l0, T, B);
@@ -366,8 +366,10 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
         // bidirectional layer above the first) with small tiles
         if (l % plan.LP != 0) return false;
         const int kw = (m->dtype == DT_BF16) ? 32 : 4;          // K elements per MFMA
+        const int KB = m->H / (4 * kw);
         if (m->layer_input(l) == m->H) return true;
-        return m->D == 2 && m->layer_input(l) == 2 * m->H && plan.RT * (m->H / (4 * kw)) * 2 <= 32;
+        if (2 * m->layer_input(l) == m->H) return KB % 2 == 0;
+        return plan.LP == 1 && m->D == 2 && m->layer_input(l) == 2 * m->H && plan.RT * KB * 2 <= 32;
     }
     if (m->D != 1 || m->layer_input(l) != m->H) return false;
     // the first layer's input is first brought into the layout of a state sequence

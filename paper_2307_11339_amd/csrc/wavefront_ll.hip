@@ -194,7 +194,8 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
 // right after them, i.e. while the h waves wait for h_t to come round.  The input product is then off
 // the recurrent critical path, and neither wave type holds two sets of weights (with both sets in
 // one wave the compiler parks one in the accumulator registers and copies it back before every MFMA).
-// XW: 0 = no x waves; 1 = x waves, inputs as wide as the layer; 2 = x waves, a plain input twice as wide
+// XW: 0 = no x waves; otherwise x waves, XW = twice the ratio of input width to H of the launch's first
+// layer: 2 = as wide as the layer (also when that layer reads a projection), 1 = half as wide, 4 = twice as wide
 // (a bidirectional layer above the first, which reads [forward, backward] of the layer below).
 template <class TR, int CELL, int RT, int KB, int XW>
 __global__ __launch_bounds__(XW ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(XW ? 512 : 256) void wavefront_ll_kernel(WavefrontA
     const int cb = r / p.nrb, rb = r - cb * p.nrb;
     const int ll = g / p.D, d = g - ll * p.D;
     const int l = p.l0 + ll;
-    const bool fused = XW == 1 && ll > 0;
+    const bool fused = FUSED && ll > 0;
     // the first layer of the launch multiplies its input itself (from a plain [T, B, H] tensor) when the
     // host hands one over; otherwise it adds the projection gx
     const bool plain_x = FUSED && ll == 0 && p.xin != nullptr;
@@ -307,8 +308,8 @@ __global__ __launch_bounds__(XW ? 512 : 256) void wavefront_ll_kernel(WavefrontA
         } else if (plain_x) {
             // first layer of the launch: x_t is a finished tensor without tags, read straight into MFMA
             // B fragments (lane (n, q) holds 8 consecutive inputs of sequence n), a step ahead
-            constexpr int KBX = (XW > 0 ? XW : 1) * KB;   // K blocks of this wave's quarter of the input
-            const int IW = (XW > 0 ? XW : 1) * H;         // input width
+            constexpr int KBX = (XW > 0 ? XW * KB / 2 : 1) > 0 ? (XW > 0 ? XW * KB / 2 : 1) : 1;   // K blocks of this wave's quarter of the input
+            const int IW = (XW > 0 ? XW : 2) * H / 2;     // input width
             frag wx[RT][KBX];
             // W_ih of all directions is one matrix [D * 4H, IW]; direction d owns rows d * 4H ...
             const elem* wih = static_cast<const elem*>(p.wih[g]) + (size_t)d * 4 * H * IW;
@@ -538,16 +539,24 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
 template <class TR, int RT, int KB>
 hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     // workgroups with x waves: fused layers, or a first layer that multiplies its plain input itself
-    // (a.xin_width = that input's width in units of H)
-    if (a.xin != nullptr && a.xin_width == 2) {
+    // (a.xin_width2 = twice that input's width over H)
+    if (a.xin != nullptr && a.xin_width2 == 4) {
         if constexpr (RT * KB * 2 <= 32) {       // the x waves hold RT * 2KB weight fragments
             if (a.LP != 1) return hipErrorInvalidValue;
-            return launch_ll_cell<TR, RT, KB, 2>(a, stream);
+            return launch_ll_cell<TR, RT, KB, 4>(a, stream);
         } else {
             return hipErrorInvalidValue;
         }
     }
-    if (a.LP > 1 || a.xin != nullptr) return launch_ll_cell<TR, RT, KB, 1>(a, stream);
+    if (a.xin != nullptr && a.xin_width2 == 1) {
+        if constexpr (KB % 2 == 0) {
+            return launch_ll_cell<TR, RT, KB, 1>(a, stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if (a.xin != nullptr && a.xin_width2 != 2) return hipErrorInvalidValue;
+    if (a.LP > 1 || a.xin != nullptr) return launch_ll_cell<TR, RT, KB, 2>(a, stream);
     return launch_ll_cell<TR, RT, KB, 0>(a, stream);
 }
 

@@ -74,6 +74,11 @@ SMALL = [
     ("lstm_bf16_3layer_sq_h256", 0, 3, 1, 256, 256, 11, 7, 1, True, True),
     ("gru_f32_2layer_sq_h64", 1, 2, 1, 64, 64, 9, 19, 0, True, True),
     ("lstm_bf16_1layer_sq_h512", 0, 1, 1, 512, 512, 8, 1, 1, False, False),
+    # input half as wide as the layer, and both directions (first layer H/2 or H wide, upper layer 2H wide)
+    ("gru_bf16_3layer_half_h256", 1, 3, 1, 128, 256, 10, 6, 1, True, True),
+    ("lstm_f32_half_h64", 0, 1, 1, 32, 64, 7, 33, 0, True, True),
+    ("lstm_bf16_bidir_sq_h256", 0, 2, 2, 256, 256, 9, 20, 1, True, True),
+    ("gru_bf16_bidir_half_h128", 1, 2, 2, 64, 128, 8, 5, 1, True, False),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
     ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state

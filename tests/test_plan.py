@@ -17,8 +17,8 @@ def test_named_workloads():
     """The five named workloads on an MI355X: the plans the measurements in the design notes refer to."""
     expect = {
         # layers per launch, tile (16-row tiles, column tiles, chains), row blocks, column blocks, launches, projections
-        "C1": (1, (1, 1, 1), 32, 1, 1, [1]),
-        "C2": (2, (4, 1, 1), 32, 1, 1, [1, 0]),
+        "C1": (1, (1, 1, 1), 32, 1, 1, [0]),             # input half as wide as the layer: read by the x waves
+        "C2": (2, (4, 1, 1), 32, 1, 1, [0, 0]),
         "C3": (4, (4, 1, 1), 64, 1, 1, [0, 0, 0, 0]),
         "C4": (1, (4, 1, 1), 32, 4, 2, [0, 0]),     # both directions; the upper layer reads [forward, backward] of the lower
         "C5": (1, (4, 2, 2), 64, 8, 8, [0] * 8),
