@@ -79,6 +79,8 @@ SMALL = [
     ("lstm_f32_half_h64", 0, 1, 1, 32, 64, 7, 33, 0, True, True),
     ("lstm_bf16_bidir_sq_h256", 0, 2, 2, 256, 256, 9, 20, 1, True, True),
     ("gru_bf16_bidir_half_h128", 1, 2, 2, 64, 128, 8, 5, 1, True, False),
+    ("lstm_bf16_20layer_h256", 0, 20, 1, 256, 256, 6, 2, 1, True, True),     # two launches: the second reads the first's output
+    ("gru_bf16_sq_h128_t1", 1, 2, 1, 128, 128, 1, 3, 1, False, True),          # a single step, input read by the x waves
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
     ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state
