@@ -40,12 +40,8 @@ struct LLBf16 : TraitsBf16 {
     static __device__ inline void ll_publish(elem state, elem outv, bool valid, bool write_out,
                                              int lane, uint32_t epoch, uint64_t* state_dst,
                                              elem* out_dst) {
-        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
-        const int n = lane & 15;
-        const uint32_t v0 = (uint32_t)__shfl(mine, n);
-        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
-        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
-        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
+        uint32_t v0, v1, v2, v3;
+        gather_rows((uint32_t)state | ((uint32_t)outv << 16), v0, v1, v2, v3);
         if (valid && lane < 16) {
             const uint64_t tag = (uint64_t)epoch << 32;
             st_dev_u64(state_dst, tag | (v0 & 0xFFFFu) | ((v1 & 0xFFFFu) << 16));

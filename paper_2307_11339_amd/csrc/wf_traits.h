@@ -28,6 +28,17 @@ __device__ inline void st_dev_u32(void* p, uint32_t v) {
     __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// For lanes 0..15: the value `mine` of lanes n, n + 16, n + 32, n + 48 (v0..v3), without a trip through
+// LDS: v_permlane16_swap exchanges rows 1 and 3 (of 16 lanes) of its first operand with rows 0 and 2 of
+// its second, v_permlane32_swap the upper half of the first with the lower half of the second.  In the
+// other lanes the outputs hold other rows' values and are not used.
+__device__ inline void gather_rows(uint32_t mine, uint32_t& v0, uint32_t& v1, uint32_t& v2, uint32_t& v3) {
+    const auto r = __builtin_amdgcn_permlane16_swap(mine, mine, false, false);
+    const auto q0 = __builtin_amdgcn_permlane32_swap(r[0], r[0], false, false);
+    const auto q1 = __builtin_amdgcn_permlane32_swap(r[1], r[1], false, false);
+    v0 = r[0]; v1 = r[1]; v2 = q0[1]; v3 = q1[1];
+}
+
 struct TraitsBf16 {
     typedef bf16_t elem;
     typedef bf16x8 frag;
@@ -53,12 +64,8 @@ struct TraitsBf16 {
     static __device__ inline void publish(elem state, elem outv, bool valid, bool out_shared, int lane,
                                           elem* state_dst, elem* out_dst) {
         // out_dst == nullptr: the layer output is not wanted (the consumer reads the state sequence)
-        const int mine = (int)((uint32_t)state | ((uint32_t)outv << 16));
-        const int n = lane & 15;
-        const uint32_t v0 = (uint32_t)__shfl(mine, n);
-        const uint32_t v1 = (uint32_t)__shfl(mine, n + 16);
-        const uint32_t v2 = (uint32_t)__shfl(mine, n + 32);
-        const uint32_t v3 = (uint32_t)__shfl(mine, n + 48);
+        uint32_t v0, v1, v2, v3;
+        gather_rows((uint32_t)state | ((uint32_t)outv << 16), v0, v1, v2, v3);
         if (valid && lane < 16) {
             const uint64_t st = (uint64_t)(v0 & 0xFFFFu) | ((uint64_t)(v1 & 0xFFFFu) << 16) |
                                 ((uint64_t)(v2 & 0xFFFFu) << 32) | ((uint64_t)(v3 & 0xFFFFu) << 48);
