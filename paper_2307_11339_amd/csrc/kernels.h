@@ -93,10 +93,12 @@ hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int
                                  int H, void* hseq, hipStream_t stream);
 
 // ---- persistent kernel with the input product inside, one layer per launch (wavefront_x.hip) --
-// Needs a.LP == 1, a.D == 1 and a.xin (the finished input sequence, width H); a.gx is not read.
+// Needs a.D == 1 and a.xin (the finished input sequence of layer l0, width H); a.gx is not read.  With
+// a.LP > 1 the layers run side by side and a layer above the first reads the state sequence below it.
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream);
 // True when a variant exists for this combination and its LDS footprint fits the current device.
-bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit);  // host only
+bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit,
+                                bool several_layers = false);  // host only
 // src [T, B, H] -> dst [T][H/16][Bp][16] (the layout of a state sequence, Bp >= B rows per block); H % 16 == 0, T <= 65535,
 // one row of 16 sequences must fit 64 KiB of LDS.
 hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B, int Bp, int H, hipStream_t stream);

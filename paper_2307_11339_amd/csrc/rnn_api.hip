@@ -93,6 +93,11 @@ void free_workspace(rnn_model* m) {
 
 constexpr int FLAG_COLBLOCKS_MAX = 16;
 
+// The caller's x can be brought into the layout of a state sequence (launch_to_blocked's limits).
+bool relayout_fits(const rnn_model* m, int T) {
+    return T <= 65535 && (size_t)16 * m->H * m->esize <= 64 * 1024;
+}
+
 // Choose how the grid of cells is laid over the compute units for batch size B.
 bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     if (m->H % 4 != 0) return false;
@@ -110,8 +115,12 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
             if (row_tiles % RT) continue;
             const bool tagged = (CT == 1 && NCH == 1);  // single tile of 16 sequences: tag-in-data kernel
+            // several layers of large tiles side by side: the inside-product kernel when every layer's
+            // input is H wide, else the flag-vector kernel with a projection for the first layer
             const bool have = tagged ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
-                                     : wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1);
+                                     : (wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1) ||
+                                        (LP > 1 && m->D == 1 && m->I == m->H && relayout_fits(m, T) &&
+                                         wavefront_x_variant_exists(m->dtype, RT, CT, NCH, m->H, m->lds_limit, true)));
             if (!have) continue;
             const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
             if (ncb % NCH) continue;
@@ -373,8 +382,13 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
     }
     if (m->D != 1 || m->layer_input(l) != m->H) return false;
     // the first layer's input is first brought into the layout of a state sequence
-    if (l == 0 && (T > 65535 || (size_t)16 * m->H * m->esize > 64 * 1024)) return false;
-    return plan.LP == 1 && wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit);
+    if (plan.LP == 1) {
+        if (l == 0 && !relayout_fits(m, T)) return false;
+        return wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit);
+    }
+    // several layers per launch: all of them inside, or none (the launch's first layer would need gx)
+    return m->I == m->H && relayout_fits(m, T) &&
+           wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit, true);
 }
 
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
@@ -449,7 +463,7 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         if (input_product_inside(m, plan, l0, T)) {
             // the first layer reads the caller's x, re-laid out; a layer above reads the state sequence below it
             if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, (int)blocked_rows(B), m->H, st));
-            const int rc = launch_recurrent(m, plan, l0, 1, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
+            const int rc = launch_recurrent(m, plan, l0, LP, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
                                             l0 == 0 ? m->xblk.p : nullptr, l0 > 0);
             if (rc != RNN_OK) return rc;
             continue;

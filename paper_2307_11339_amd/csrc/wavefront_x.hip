@@ -27,8 +27,12 @@ namespace rnn {
 
 namespace {
 
-template <class TR, int CELL, int RT, int CT, int KB, int NCH>
+// MULTI: the launch runs p.LP layers side by side, one group of workgroups each; a layer above the first
+// of the launch reads the state sequence of the group below as its x, behind that group's flags, so the
+// groups settle on successive anti-diagonals of the layer x time grid (paper Section 2.2).
+template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool MULTI>
 __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
+    static_assert(!MULTI || NCH > 1, "layers side by side need interleaved chains");
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
     constexpr int KW = TR::KW;
@@ -45,9 +49,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 
     const int v = xcd_contiguous_id();
     const int ngrp = p.ncb / NCH;                   // column block groups (ncb counts chains)
-    if (v >= p.nrb * ngrp) return;
-    const int cbg = v / p.nrb, rb = v - cbg * p.nrb;
-    const int l = p.l0;
+    const int wpl = p.nrb * ngrp;                   // workgroups per layer
+    const int g = MULTI ? v / wpl : 0;              // layer of the launch this workgroup belongs to
+    if (v >= (MULTI ? p.LP : 1) * wpl) return;
+    const int vr = v - g * wpl;
+    const int cbg = vr / p.nrb, rb = vr - cbg * p.nrb;
+    const int l = p.l0 + g;
+    const bool xfused = MULTI && g > 0;             // x_t = state of the group below, guarded by its flags
     const int H = p.H, B = p.B, T = p.T;
     const int Bp = p.Bp;                            // rows per 16-unit block of a state sequence
     const int kq = H / 4;                           // K range of one wave inside each part
@@ -60,8 +68,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     frag wh[RT][KB];
     frag* wx_mine = wxl + (size_t)w * RT * KB * 64 + lane;
     {
-        const elem* whh = static_cast<const elem*>(p.whh[0]);
-        const elem* wih = static_cast<const elem*>(p.wih[0]);
+        const elem* whh = static_cast<const elem*>(p.whh[g]);
+        const elem* wih = static_cast<const elem*>(p.wih[g]);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
@@ -87,7 +95,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         const int unit = (rb * RT + rt) * 4 + (lane >> 4);
         unit_reg[o] = unit;
         bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[0] + (size_t)unit * SLOTS);
+        if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int col = ((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
@@ -113,12 +121,14 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         for (int ct = 0; ct < CT; ++ct)
             bcol[c][ct] = min(((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15), B - 1);
 
-    elem* hseq = static_cast<elem*>(p.hseq);
-    elem* out = static_cast<elem*>(p.out[0]);
-    const elem* xin = static_cast<const elem*>(p.xin);
-    // flag word of (step, chain column block, row block): (s*ncb + cb)*nrb + rb
+    elem* hseq = static_cast<elem*>(p.hseq) + (size_t)g * (T + 1) * Bp * H;
+    elem* out = static_cast<elem*>(p.out[g]);
+    // x of a layer above the first of the launch: slot t + 1 of the state sequence of the group below
+    const elem* xin = xfused ? hseq - (size_t)(T + 1) * Bp * H + (size_t)Bp * H : static_cast<const elem*>(p.xin);
+    // flag word of (layer of the launch, step, chain column block, row block): ((g*T + s)*ncb + cb)*nrb + rb
     const size_t flag_step = (size_t)p.ncb * p.nrb;
-    uint64_t* my_flags = p.flagv + (size_t)(cbg * NCH) * p.nrb;   // chain 0
+    uint64_t* my_flags = p.flagv + (size_t)g * T * flag_step + (size_t)(cbg * NCH) * p.nrb;   // chain 0
+    const uint64_t* x_flags = my_flags - (size_t)T * flag_step;     // the group below (xfused only)
     const uint32_t epoch = p.epoch;
     bool aborted = false;
     const int kbase = w * kq + TR::koff(lane);
@@ -186,7 +196,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             asm volatile("" ::"v"(pf));
             if (lane == 0) {
                 st_dev_u64(pend_flag, ((uint64_t)epoch << 32) | (uint32_t)pend_step);
-                if (p.ticks && rb == 0 && cbg == 0 && pend_chain == 0) p.ticks[pend_step] = wall_clock64();
+                if (p.ticks && rb == 0 && cbg == 0 && pend_chain == 0) p.ticks[(size_t)g * T + pend_step] = wall_clock64();
             }
             pend_flag = nullptr;
         }
@@ -195,7 +205,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // acc += W_ih slice (A fragments from LDS, read one K block ahead of the matrix instructions)
     // x the x fragments.  The scheduling barriers keep the compiler from sinking each LDS read to
     // its first use, which would expose the LDS latency once per fragment.
-    auto input_part = [&](f32x4 (&acc)[RT][CT]) {
+    auto input_part = [&](f32x4 (&acc)[RT][CT], const uint64_t* xflag, uint64_t& seenx) {
         frag abuf[2][RT];
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) abuf[0][rt] = wx_mine[(rt * KB + 0) * 64];
@@ -212,6 +222,9 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 for (int ct = 0; ct < CT; ++ct)
                     acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
             if (NCH > 1 && kb == KB / 8 && w == 0) store_pending_flag(1);
+            // (a layer above the first of the launch) the flag word of the group below for the x fragments
+            // that the recurrent part is about to request
+            if (MULTI && kb == KB / 2 && xflag != nullptr) seenx = ld_dev_u64(xflag);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -262,6 +275,11 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) load_h(0, 0, kb);
     }
+    auto wait_x = [&](int c, int s) {  // wait until step s of chain c of the group below is published
+        wait_flags(x_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch, p.status, p.spin_limit,
+                   aborted);
+    };
+    if (xfused) wait_x(0, 0);
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb) load_x(0, 0, kb);
 
@@ -282,7 +300,12 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 // Input part first.  The flags this chain step will poll (those of the chain step
                 // after it, the same chain as the one just published) were stored moments ago and
                 // need about half a microsecond to become visible; both matrix parts run meanwhile.
-                input_part(acc);
+                const uint64_t* xflag = (xfused && sn < T)
+                    ? x_flags + (size_t)sn * flag_step + (size_t)cn * p.nrb + fl0 + min(lane, nfl - 1) : nullptr;
+                uint64_t seenx = 0;
+                input_part(acc, xflag, seenx);
+                if (MULTI && xflag != nullptr && !__all((uint32_t)(seenx >> 32) == epoch)) wait_x(cn, sn);
+                if (MULTI) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the x requests stay below the flag check
                 // flag word of this lane for step sn-1 of chain cn (clamped to a word that exists)
                 const uint64_t* flag = my_flags + (size_t)max(sn - 1, 0) * flag_step + (size_t)cn * p.nrb + fl0 +
                                        min(lane, nfl - 1);
@@ -290,10 +313,11 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 recurrent_part_prefetching_x(acc, cn, sn, flag, seen);
                 if (sn > 0 && sn < T && !__all((uint32_t)(seen >> 32) == epoch)) poll_h(cn, sn);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // loads of the state stay below the flag check
-                if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
+                if (w == 0 && !xfused) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);   // (never lines that are still being written)
             } else {
                 // One chain: the state is requested as late as possible, after the input part.
-                input_part(acc);
+                uint64_t unused_x = 0;
+                input_part(acc, nullptr, unused_x);
                 poll_h(0, s);
                 if (w == 0) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);
 #pragma unroll
@@ -396,7 +420,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 asm volatile("" ::: "memory");
                 if (lane == 0) {
                     st_dev_u64(my_flags + (size_t)s * flag_step + rb, ((uint64_t)epoch << 32) | (uint32_t)s);
-                    if (p.ticks && rb == 0 && cbg == 0) p.ticks[s] = wall_clock64();
+                    if (p.ticks && rb == 0 && cbg == 0) p.ticks[(size_t)g * T + s] = wall_clock64();
                 }
             }
             if (NCH == 1) asm volatile("" ::"v"(pf));
@@ -458,15 +482,16 @@ int device_lds_limit() {
     return limit;
 }
 
-template <class TR, int CELL, int RT, int CT, int KB, int NCH>
+template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool MULTI>
 hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.ncb % NCH != 0 || a.nrb % 4 != 0 || a.nrb > 256) return hipErrorInvalidValue;
+    if (a.LP < 1 || a.LP > WF_MAX_LAYERS || (!MULTI && a.LP != 1)) return hipErrorInvalidValue;
     if ((size_t)a.Bp * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
     if (a.Bp < a.B || a.Bp % 4 != 0) return hipErrorInvalidValue;
-    const int grid = a.nrb * (a.ncb / NCH);
+    const int grid = a.LP * a.nrb * (a.ncb / NCH);
     constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
-    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH>;
+    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, MULTI>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -492,8 +517,16 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
 
 template <class TR, int RT, int CT, int KB, int NCH>
 hipError_t launch_cell(const WavefrontArgs& a, hipStream_t stream) {
-    if (a.cell == CELL_LSTM) return launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH>(a, stream);
-    return launch_variant<TR, CELL_GRU, RT, CT, KB, NCH>(a, stream);
+    if (a.LP > 1) {   // several layers side by side: compiled for the interleaved-chain shapes only
+        if constexpr (NCH > 1) {
+            if (a.cell == CELL_LSTM) return launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, true>(a, stream);
+            return launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, true>(a, stream);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    if (a.cell == CELL_LSTM) return launch_variant<TR, CELL_LSTM, RT, CT, KB, NCH, false>(a, stream);
+    return launch_variant<TR, CELL_GRU, RT, CT, KB, NCH, false>(a, stream);
 }
 
 // (dtype, RT, CT, KB, NCH) combinations that are compiled: the same shapes as the flag-vector
@@ -510,7 +543,8 @@ template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
 }  // namespace
 
-bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit) {
+bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit, bool several_layers) {
+    if (several_layers && NCH < 2) return false;
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (H % (4 * kw) != 0) return false;
     const int KB = H / (4 * kw);
@@ -536,7 +570,7 @@ hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B
 }
 
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream) {
-    if (a.LP != 1 || a.D != 1 || a.xin == nullptr) return hipErrorInvalidValue;
+    if (a.LP < 1 || a.D != 1 || a.xin == nullptr) return hipErrorInvalidValue;
     const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
     const int KB = a.H / (4 * kw);

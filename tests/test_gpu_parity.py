@@ -100,12 +100,17 @@ SMALL = [
     # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.
     ("lstm_bf16_fusedflag_l4", 0, 4, 1, 64, 1024, 5, 40, 1, True, True),    # 4 layers x 64 workgroups, tiles of 64 sequences
     ("gru_bf16_fusedflag_l2", 1, 2, 1, 64, 1024, 6, 100, 1, True, True),    # 2 layers x 128 workgroups, two chains of 32
+    # the same regime with inputs as wide as the layers: several layers side by side in the inside-product kernel, the
+    # upper ones reading the state sequence below them behind its flags
+    ("lstm_bf16_sidebyside_l4", 0, 4, 1, 1024, 1024, 7, 40, 1, True, True),   # 4 layers x 64 workgroups, two chains of 32
+    ("gru_bf16_sidebyside_l2", 1, 2, 1, 512, 512, 9, 100, 1, True, True),     # 2 layers x 128 workgroups
+    ("lstm_bf16_sidebyside_l3_t1", 0, 3, 1, 512, 512, 1, 64, 1, False, True),  # a single step
     # narrow fp32 layers at a large batch: a K quarter of a wave is narrower than a cache line of the state (H = 32)
     # or of the output of the layer below (H = 32, 64), so a wave waits for the row blocks of the whole line
     ("lstm_f32_fusedflag_h32", 0, 2, 1, 20, 32, 7, 300, 0, True, True),
     ("gru_f32_fusedflag_h64", 1, 3, 1, 24, 64, 6, 290, 0, True, True),
 ]
-SAMPLED = ("_inside", "_fusedflag")
+SAMPLED = ("_inside", "_fusedflag", "_sidebyside")
 
 
 def _small_workload(W, spec):
@@ -368,7 +373,8 @@ def test_workspace_follows_the_plan(gpu):
 
 
 @pytest.mark.parametrize("name", ["gru_bf16_inside_t2", "lstm_f32_inside_b501", "lstm_bf16_b299", "lstm_bf16_inside_sq",
-                                  "lstm_f32_fusedflag_h32", "gru_f32_fusedflag_h64", "gru_f32_bidir"])
+                                  "lstm_f32_fusedflag_h32", "gru_f32_fusedflag_h64", "gru_f32_bidir",
+                                  "lstm_bf16_sidebyside_l4", "gru_bf16_sidebyside_l2"])
 def test_first_call_on_used_memory_equals_later_calls(gpu, name):
     """The kernels exchange states through memory that every address of is written once per launch and
     read with cached loads.  That only works if what a reader's cache line holds besides the data it
