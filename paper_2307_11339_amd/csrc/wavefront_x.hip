@@ -20,7 +20,10 @@
 //   - one wave writes a chain step to memory, from LDS, in whole cache lines, and is the only
 //     one that needs a store acknowledged; it checks for the acknowledgement with a counted wait
 //     (loads requested behind the stores stay in flight) early in the next chain step and stores
-//     the flag word there.
+//     the flag word there;
+//   - a launch may hold several such layers side by side (template flag MULTI): a layer above the
+//     first of the launch takes the state sequence of the group below as its x, as it is produced,
+//     behind that group's flag vectors.
 #include "wf_traits.h"
 
 namespace rnn {

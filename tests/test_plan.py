@@ -33,6 +33,22 @@ def test_named_workloads():
         assert sep == proj, name
 
 
+def test_medium_batch_layers_side_by_side():
+    """64 sequences, 4 layers of 1024 units: one launch of 4 x 64 workgroups.  With inputs as wide as the layers
+    every input product runs inside; with a narrower first layer that layer projects."""
+    sq = W.Config("m", W.LSTM, L=4, D=1, I=1024, H=1024, T=128, B=64, dtype=W.BF16, seed=1)
+    rc, plan, sep = _query(sq)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert (plan["layers_per_launch"], plan["row_tiles"], plan["col_tiles"], plan["chains"]) == (4, 4, 2, 2)
+    assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (64, 2, 1)
+    assert sep == [0, 0, 0, 0]
+    rc, plan, sep = _query(sq.scaled(I=64))
+    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and sep == [1, 0, 0, 0]
+    # without the LDS for W_ih the layers still share a launch, the first one projects
+    rc, plan, sep = _query(sq, lds=64 * 1024)
+    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and sep == [1, 0, 0, 0]
+
+
 def test_cellwise_requested_or_forced():
     c = W.CONFIGS["C2"]
     rc, plan, sep = _query(c, plan=rnn.RNN_PLAN_CELLWISE)
