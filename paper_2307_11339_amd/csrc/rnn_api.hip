@@ -23,6 +23,9 @@ struct DevBuf {
 struct Plan {
     int kind = RNN_PLAN_CELLWISE;   // resolved plan (never AUTO)
     int LP = 1, RT = 1, CT = 1, NCH = 1, nrb = 0, ncb = 0;
+    // the first layer runs in a launch of its own (it needs a projection, the layers above it run side
+    // by side in the inside-product kernel): launches are {0}, {1..LP}, {LP+1..2LP}, ...
+    bool first_alone = false;
 };
 
 }  // namespace
@@ -110,6 +113,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
         const int LP = (m->L + launches - 1) / launches;
         const int budget = m->num_cus / (LP * m->D);
         int best = -1, best_cost = 0, best_rt = 0, best_nch = 0;
+        bool best_first_alone = false;
         int tag_small = -1, tag_large = -1;   // tag-in-data candidates: smallest tile within 3/8 of the chip, largest tile
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
             const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
@@ -117,10 +121,14 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             const bool tagged = (CT == 1 && NCH == 1);  // single tile of 16 sequences: tag-in-data kernel
             // several layers of large tiles side by side: the inside-product kernel when every layer's
             // input is H wide, else the flag-vector kernel with a projection for the first layer
+            // x-kernel launches of several layers: all layers when the model's input is H wide, the layers
+            // above the first (which then runs alone, behind its projection) otherwise
+            const bool side_by_side = !tagged && LP > 1 && m->D == 1 &&
+                                      wavefront_x_variant_exists(m->dtype, RT, CT, NCH, m->H, m->lds_limit, true) &&
+                                      (m->I == m->H ? relayout_fits(m, T)
+                                                    : wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, false));
             const bool have = tagged ? wavefront_ll_variant_exists(m->dtype, RT, m->H)
-                                     : (wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1) ||
-                                        (LP > 1 && m->D == 1 && m->I == m->H && relayout_fits(m, T) &&
-                                         wavefront_x_variant_exists(m->dtype, RT, CT, NCH, m->H, m->lds_limit, true)));
+                                     : (wavefront_variant_exists(m->dtype, RT, CT, NCH, m->H, LP > 1) || side_by_side);
             if (!have) continue;
             const int nrb = row_tiles / RT, ncb = (col_tiles + CT - 1) / CT;
             if (ncb % NCH) continue;
@@ -144,6 +152,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             if (best < 0 || cost < best_cost || (cost == best_cost && NCH > best_nch) ||
                 (cost == best_cost && NCH == best_nch && RT > best_rt)) {
                 best = c; best_cost = cost; best_rt = RT; best_nch = NCH;
+                best_first_alone = side_by_side && m->I != m->H;
             }
         }
         if (tag_large >= 0) best = tag_small >= 0 ? tag_small : tag_large;
@@ -155,6 +164,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
             plan.NCH = cand[best][2];
             plan.nrb = row_tiles / plan.RT;
             plan.ncb = (col_tiles + plan.CT - 1) / plan.CT;
+            plan.first_alone = best_first_alone && !(plan.CT == 1 && plan.NCH == 1);
             return true;
         }
     }
@@ -171,6 +181,27 @@ int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
     if (m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     plan = Plan();
     return RNN_OK;
+}
+
+// First layer and number of layers of the launch that holds layer l.
+void launch_of(const rnn_model* m, const Plan& plan, int l, int& l0, int& n) {
+    if (plan.first_alone) {
+        if (l == 0) { l0 = 0; n = 1; return; }
+        l0 = 1 + ((l - 1) / plan.LP) * plan.LP;
+    } else {
+        l0 = (l / plan.LP) * plan.LP;
+    }
+    n = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
+}
+bool first_of_launch(const rnn_model* m, const Plan& plan, int l) {
+    int l0, n;
+    launch_of(m, plan, l, l0, n);
+    return l == l0;
+}
+int launch_count(const rnn_model* m, const Plan& plan) {
+    int count = 0;
+    for (int l = 0; l < m->L; ++l) count += first_of_launch(m, plan, l) ? 1 : 0;
+    return count;
 }
 
 // Gate row of the caller's [G*H, K] matrix that feeds slot s of unit u; -1 = no row (zeros).
@@ -373,7 +404,7 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
         // tag-in-data kernel, first layer of a launch (layers above it in the launch are fused anyway): its
         // x waves hold the W_ih slice in registers, which fits for an input H wide, or 2H wide (a
         // bidirectional layer above the first) with small tiles
-        if (l % plan.LP != 0) return false;
+        if (!first_of_launch(m, plan, l)) return false;
         const int kw = (m->dtype == DT_BF16) ? 32 : 4;          // K elements per MFMA
         const int KB = m->H / (4 * kw);
         if (m->layer_input(l) == m->H) return true;
@@ -382,13 +413,15 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
     }
     if (m->D != 1 || m->layer_input(l) != m->H) return false;
     // the first layer's input is first brought into the layout of a state sequence
-    if (plan.LP == 1) {
+    int l0, n;
+    launch_of(m, plan, l, l0, n);
+    if (n == 1) {
         if (l == 0 && !relayout_fits(m, T)) return false;
         return wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit);
     }
     // several layers per launch: all of them inside, or none (the launch's first layer would need gx)
-    return m->I == m->H && relayout_fits(m, T) &&
-           wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit, true);
+    if (l0 == 0 && (m->I != m->H || !relayout_fits(m, T))) return false;
+    return wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit, true);
 }
 
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
@@ -404,7 +437,7 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
     int rc = RNN_OK;
     for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
         const bool inside = wavefront && input_product_inside(m, plan, l, T);
-        if (!inside && (!wavefront || l % plan.LP == 0)) any_projection = true;
+        if (!inside && (!wavefront || first_of_launch(m, plan, l))) any_projection = true;
         // a layer keeps an output of its own unless its consumer reads its state sequence instead (the
         // inside-product kernel of large batches; the tag-in-data kernel's consumers read plain outputs)
         if (l + 1 < m->L && (!inside || tagged)) rc = grow(m, m->ybuf[l], rows * m->D * m->H * m->esize);
@@ -451,8 +484,9 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
                       const float* h0, const float* c0, void* y, float* hT, float* cT, int T,
                       int B, hipStream_t st) {
     const int N4 = SLOTS * m->H;
-    for (int l0 = 0; l0 < m->L; l0 += plan.LP) {
-        const int LP = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
+    for (int l0 = 0, LP = 0; l0 < m->L; l0 += LP) {
+        int first;
+        launch_of(m, plan, l0, first, LP);
         const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
         if (plan.CT == 1 && plan.NCH == 1 && input_product_inside(m, plan, l0, T)) {
             // tag-in-data kernel: the x waves of the launch's first layer read the plain input
@@ -722,7 +756,7 @@ int rnn_model_input_product_placement(const rnn_model* m, int T, int B, int laye
     if (rc != RNN_OK) return rc;
     if (plan.kind != RNN_PLAN_WAVEFRONT) *separate_launch = 1;
     else if (input_product_inside(m, plan, layer, T)) *separate_launch = 0;
-    else *separate_launch = (layer % plan.LP == 0) ? 1 : 0;  // layers above the first of a launch are fused
+    else *separate_launch = first_of_launch(m, plan, layer) ? 1 : 0;  // layers above the first of a launch are fused
     return RNN_OK;
 }
 
@@ -751,10 +785,10 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
     plan_out[4] = wavefront ? plan.NCH : 0;
     plan_out[5] = wavefront ? plan.nrb : 0;
     plan_out[6] = wavefront ? plan.ncb : 0;
-    plan_out[7] = wavefront ? (num_layers + plan.LP - 1) / plan.LP : num_layers;
+    plan_out[7] = wavefront ? launch_count(&m, plan) : num_layers;
     if (separate_projection)
         for (int l = 0; l < num_layers; ++l)
-            separate_projection[l] = !wavefront ? 1 : input_product_inside(&m, plan, l, T) ? 0 : (l % plan.LP == 0) ? 1 : 0;
+            separate_projection[l] = !wavefront ? 1 : input_product_inside(&m, plan, l, T) ? 0 : first_of_launch(&m, plan, l) ? 1 : 0;
     return RNN_OK;
 }
 

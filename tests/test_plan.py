@@ -42,11 +42,12 @@ def test_medium_batch_layers_side_by_side():
     assert (plan["layers_per_launch"], plan["row_tiles"], plan["col_tiles"], plan["chains"]) == (4, 4, 2, 2)
     assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (64, 2, 1)
     assert sep == [0, 0, 0, 0]
+    # a narrower first layer runs alone behind its projection, the three above it side by side
     rc, plan, sep = _query(sq.scaled(I=64))
-    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and sep == [1, 0, 0, 0]
+    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and plan["launches"] == 2 and sep == [1, 0, 0, 0]
     # without the LDS for W_ih the layers still share a launch, the first one projects
     rc, plan, sep = _query(sq, lds=64 * 1024)
-    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and sep == [1, 0, 0, 0]
+    assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and plan["launches"] == 1 and sep == [1, 0, 0, 0]
 
 
 def test_cellwise_requested_or_forced():
@@ -98,7 +99,10 @@ def test_invariants_over_random_shapes():
             assert sep == [1] * c.L
             continue
         lp, rt, ct, nch = plan["layers_per_launch"], plan["row_tiles"], plan["col_tiles"], plan["chains"]
-        assert plan["launches"] * lp >= c.L and (plan["launches"] - 1) * lp < c.L
+        plain = -(-c.L // lp)                           # launches of lp layers each
+        first_alone = 1 + -(-(c.L - 1) // lp)           # the first layer alone behind its projection, then lp each
+        assert plan["launches"] == plain or (lp > 1 and c.D == 1 and c.I != c.H and sep[0] == 1 and
+                                             plan["launches"] == first_alone)
         assert c.D == 1 or lp == 1                      # bidirectional layers cannot share a launch
         assert plan["row_blocks"] * rt * 4 == c.H       # 16 gate rows = 4 hidden units per tile
         assert plan["col_blocks"] * ct * 16 >= c.B and plan["col_blocks"] % nch == 0
