@@ -181,9 +181,22 @@ int rnn_model_profile_read(rnn_model* model, int kind, double* total_ms, long lo
  * backward direction's step s is time T-1-s. */
 int rnn_model_read_step_ticks(rnn_model* model, uint64_t* ticks, size_t count);
 
-/* After the stream has been synchronised: RNN_OK, or RNN_EDEVICE if a workgroup of the last
- * persistent forward gave up waiting for a step flag (its outputs are then undefined). */
+/* After the stream has been synchronised: RNN_OK, or RNN_EDEVICE if a workgroup of a persistent
+ * forward since the last check gave up waiting for another workgroup's step (the outputs of that
+ * forward are then undefined).  The condition is latched on the device: while it stands, every wait
+ * of a later forward gives up early as well, and this call lowers it again, so the forward after an
+ * RNN_EDEVICE answer runs normally. */
 int rnn_model_check(rnn_model* model);
+
+/* Every wait inside the persistent kernels is bounded: a wave that has polled `polls` times without
+ * success stops waiting, raises the condition that rnn_model_check reports, and runs on to the end of
+ * the launch without waiting again (so the launch always drains).  The kernels read the budget only now
+ * and then (every 64 to 1024 polls of a wait; where a layer waits for the layer below it, and in the
+ * kernel for small batches, also after the first 8), so the value is rounded up to the next such
+ * moment.  polls = 0 restores the default, about three seconds.  A tiny value makes healthy launches
+ * of several layers give up, because an upper layer waits at the start of a launch for the layers below
+ * it to get going; tests of the give-up path use that. */
+int rnn_model_set_spin_limit(rnn_model* model, unsigned polls);
 
 /* Where the input product W_ih x_t of `layer` is computed for a forward pass of T steps and B
  * sequences under the current plan: *separate_launch = 1 when it is a projection launch of its own

@@ -30,6 +30,10 @@ struct Plan {
 
 }  // namespace
 
+// About three seconds of polling: far beyond any wait of a healthy launch, short enough that a launch
+// whose workgroups are not all resident (which would otherwise never end) drains.
+constexpr unsigned DEFAULT_SPIN_LIMIT = 1u << 22;
+
 struct rnn_model {
     int cell, L, I, H, D, dtype;
     int device = 0;
@@ -51,6 +55,7 @@ struct rnn_model {
     std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
     size_t workspace_bytes = 0;
     bool want_ticks = false;
+    unsigned spin_limit = DEFAULT_SPIN_LIMIT;   // polls before a wait inside a persistent kernel is abandoned
 
     // optional profiling: HIP events around the kernels of each class
     bool profiling = false;
@@ -384,7 +389,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     }
     a.status = (unsigned*)m->status.p;
     a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
-    a.spin_limit = 1u << 22;
+    a.spin_limit = m->spin_limit;
     a.lseq = (uint64_t*)m->lseq.p;
     a.epoch = m->epoch;
     const int ps = prof_begin(m, RNN_KERNEL_RECURRENT, st);
@@ -746,7 +751,16 @@ int rnn_model_check(rnn_model* m) {
     if (!m) return RNN_EINVAL;
     unsigned st = 0;
     HIP_TRY(hipMemcpy(&st, m->status.p, sizeof(st), hipMemcpyDeviceToHost));
-    return st == 0 ? RNN_OK : RNN_EDEVICE;
+    if (st == 0) return RNN_OK;
+    // the word is only ever raised by the kernels: lower it, so that the next forward runs normally
+    HIP_TRY(hipMemset(m->status.p, 0, sizeof(unsigned)));
+    return RNN_EDEVICE;
+}
+
+int rnn_model_set_spin_limit(rnn_model* m, unsigned polls) {
+    if (!m) return RNN_EINVAL;
+    m->spin_limit = polls == 0 ? DEFAULT_SPIN_LIMIT : polls;
+    return RNN_OK;
 }
 
 int rnn_model_input_product_placement(const rnn_model* m, int T, int B, int layer, int* separate_launch) {

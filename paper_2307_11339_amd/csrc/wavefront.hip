@@ -236,8 +236,8 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
 
             if (FUSED) {
                 if (fused) {  // x_t = h_t of the layer below
-                    wait_flags(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + xfl0, xnfl, lane, epoch,
-                               p.status, p.spin_limit, aborted);
+                    wait_flags<true>(below_flags + (size_t)s * flag_step + (size_t)c * p.nrb + xfl0, xnfl, lane, epoch,
+                                     p.status, p.spin_limit, aborted);
                     const char* xs = reinterpret_cast<const char*>(below + (size_t)t * B * H);
                     frag xbuf[KB][CT];
 #pragma unroll

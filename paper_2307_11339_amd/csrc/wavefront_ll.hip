@@ -131,7 +131,10 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
                                unsigned spin_limit, bool& aborted) {
     constexpr int QW = KB * TR::WORDS_PER_KW;           // tagged words per sequence in one K quarter
     unsigned spins = 0;
-    auto give_up = [&]() {  // called now and then while waiting
+    // Called after 8 unsuccessful probes or fetches (no wait of a healthy launch in its steady state
+    // lasts that long) and then every 256 probes or 64 fetches: the poll budget and the status word
+    // (another workgroup may have given up) are only read here, off the path of a wait that succeeds.
+    auto give_up = [&]() {
         const unsigned st = ld_dev_u32(status);
         if (st != 0u || spins >= spin_limit) {
             st_dev_u32(status, 1u);
@@ -153,7 +156,7 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
         while (!aborted) {
             const uint2 a = __builtin_bit_cast(uint2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, base + probe_rel, 0, 16));
             if (__all(a.y == epoch)) break;
-            if ((++spins & 255u) == 0u) give_up();
+            if ((++spins & 255u) == 0u || spins == 8u) give_up();
         }
     }
     for (;;) {
@@ -161,7 +164,7 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
         f.issue(rsrc, base, row_bytes, ncol, lane);
         const bool ok = f.land(ncol, lane, epoch, stage);
         if (ok || aborted) break;
-        if ((++spins & 63u) == 0u) give_up();
+        if ((++spins & 63u) == 0u || spins == 8u) give_up();
     }
 }
 

@@ -279,8 +279,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         for (int kb = 0; kb < KB; ++kb) load_h(0, 0, kb);
     }
     auto wait_x = [&](int c, int s) {  // wait until step s of chain c of the group below is published
-        wait_flags(x_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch, p.status, p.spin_limit,
-                   aborted);
+        wait_flags<true>(x_flags + (size_t)s * flag_step + (size_t)c * p.nrb + fl0, nfl, lane, epoch, p.status,
+                         p.spin_limit, aborted);
     };
     if (xfused) wait_x(0, 0);
 #pragma unroll

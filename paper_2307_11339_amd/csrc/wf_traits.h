@@ -132,6 +132,10 @@ struct TraitsF32 {
 
 // Wait until the `n` flag words at `row` carry `epoch` (n <= 64, one word per lane).  Returns
 // false when the wait was abandoned (poll budget exhausted, or another workgroup gave up).
+// The poll budget and the status word are read every 1024 polls, off the path of a wait that
+// succeeds; with EARLY_LOOK also after 8 unsuccessful polls (for the waits of a layer for the layer
+// below it, which are long at the start of a launch: a tiny budget set by the host then ends them).
+template <bool EARLY_LOOK = false>
 __device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t epoch,
                                   unsigned* status, unsigned spin_limit, bool& aborted) {
     if (aborted) return false;
@@ -140,7 +144,7 @@ __device__ inline bool wait_flags(const uint64_t* row, int n, int lane, uint32_t
     for (;;) {
         const bool ok = (uint32_t)(ld_dev_u64(row + i0) >> 32) == epoch;
         if (__all(ok)) break;
-        if ((++spins & 1023u) == 0u) {
+        if ((++spins & 1023u) == 0u || (EARLY_LOOK && spins == 8u)) {
             const unsigned st = ld_dev_u32(status);
             if (st != 0u || spins >= spin_limit) {
                 st_dev_u32(status, 1u);

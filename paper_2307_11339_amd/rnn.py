@@ -28,7 +28,7 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
-           "rnn_model_set_gru_reset_before", "rnn_plan_query")
+           "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit")
 
 _lib = None
 
@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_input_projection.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.rnn_model_check.restype = ci
     lib.rnn_model_check.argtypes = [vp]
+    lib.rnn_model_set_spin_limit.restype = ci
+    lib.rnn_model_set_spin_limit.argtypes = [vp, ctypes.c_uint]
     lib.rnn_model_device_bytes.restype = ctypes.c_size_t
     lib.rnn_model_device_bytes.argtypes = [vp]
     lib.rnn_model_input_product_placement.restype = ci
@@ -165,6 +167,10 @@ def rnn_input_projection(model: int, layer: int, inp, gx, rows: int, stream=None
 
 def rnn_model_check(model: int) -> int:
     return load_library().rnn_model_check(model)
+
+
+def rnn_model_set_spin_limit(model: int, polls: int) -> int:
+    return load_library().rnn_model_set_spin_limit(model, polls)
 
 
 def rnn_model_device_bytes(model: int) -> int:

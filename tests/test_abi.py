@@ -57,6 +57,7 @@ def test_host_only_calls(lib):
     assert lib.rnn_model_create(None, 0, 1, 8, 8, 1, 0, None, 0) == rnn.RNN_EINVAL
     assert rnn.rnn_model_device_bytes(None) == 0
     assert rnn.rnn_model_check(None) == rnn.RNN_EINVAL
+    assert rnn.rnn_model_set_spin_limit(None, 5) == rnn.RNN_EINVAL
     rnn.rnn_model_destroy(None)
 
 

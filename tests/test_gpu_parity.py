@@ -109,6 +109,7 @@ SMALL = [
     # or of the output of the layer below (H = 32, 64), so a wave waits for the row blocks of the whole line
     ("lstm_f32_fusedflag_h32", 0, 2, 1, 20, 32, 7, 300, 0, True, True),
     ("gru_f32_fusedflag_h64", 1, 3, 1, 24, 64, 6, 290, 0, True, True),
+    ("lstm_f32_fusedflag_l6_h32", 0, 6, 1, 20, 32, 7, 300, 0, True, True),   # six layers in one launch of the flag-vector kernel
 ]
 SAMPLED = ("_inside", "_fusedflag", "_sidebyside")
 
@@ -153,6 +154,40 @@ def test_small_shapes(gpu, oracle, spec, plan):
     import torch
     torch.cuda.synchronize()
     assert torch.equal(y1, io.y)
+    model.close()
+
+
+# models whose upper layers wait a long time at the start of a launch (the layers below have to get there first)
+@pytest.mark.parametrize("name", ["lstm_bf16_8layer_h256", "lstm_f32_6layer_h128",    # tag-in-data kernel
+                                  "lstm_bf16_sidebyside_l4",                           # inside-product kernel
+                                  "lstm_f32_fusedflag_l6_h32"])                        # flag-vector kernel
+def test_abandoned_wait_is_reported_and_the_model_recovers(gpu, oracle, name):
+    """A poll budget of one makes healthy launches give up: a wait that is still unsuccessful when the
+    kernel first looks at its budget (after 8 polls) is abandoned, the launch still drains (all later
+    waits return at once), rnn_model_check reports it once, and the next forward with the default
+    budget is correct again."""
+    harness, rnn, W = gpu
+    import torch
+    spec = [s for s in SMALL if s[0] == name][0]
+    wl = _small_workload(W, spec)
+    _say("\n  case %s, poll budget 1" % name)
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)            # sizes the workspace, healthy
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    assert rnn.rnn_model_set_spin_limit(model.handle, 1) == rnn.RNN_OK
+    for _ in range(3):                    # the launches end by themselves
+        harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_EDEVICE
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK          # reported once, then lowered
+    assert rnn.rnn_model_set_spin_limit(model.handle, 0) == rnn.RNN_OK
+    harness.forward(model, io)
+    rows = np.unique(np.linspace(0, wl.cfg.B - 1, 12).astype(int))
+    ref = oracle.forward_workload(wl.take_batch(rows), nthreads=8)
+    _check(harness, wl, io, ref, rows=rows)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
     model.close()
 
 
