@@ -15,11 +15,17 @@
  *       a = W_ih x_t + b_ih + W_hh h_{t-1} + b_hh
  *       i = sigma(a_i)  f = sigma(a_f)  g = tanh(a_g)  o = sigma(a_o)
  *       c_t = f * c_{t-1} + i * g          h_t = o * tanh(c_t)
+ *     optional peephole weights p_i, p_f, p_o (one value per hidden unit, the form of the ONNX LSTM
+ *     operator, which is the model format the paper's system ingests, Section 1 and Section 4.1):
+ *       i = sigma(a_i + p_i * c_{t-1})   f = sigma(a_f + p_f * c_{t-1})   o = sigma(a_o + p_o * c_t)
  *   GRU (row blocks ordered r, z, n):
  *       r = sigma(W_ir x + b_ir + W_hr h + b_hr)     z = sigma(W_iz x + b_iz + W_hz h + b_hz)
  *       variant 0 (reset applied after the product):  n = tanh(W_in x + b_in + r * (W_hn h + b_hn))
  *       variant 1 (reset applied before the product): n = tanh(W_in x + b_in + W_hn (r * h) + b_hn)
  *       h_t = (1 - z) * n + z * h_{t-1}
+ *   optional clipping threshold clip > 0 (same operator): the argument of every gate activation
+ *   (i, f, g, o with their peephole terms; r, z and the whole argument of n) is limited to
+ *   [-clip, +clip] before sigma / tanh is applied; the cell state inside h_t = o * tanh(c_t) is not.
  *
  * Everything is evaluated in the plainest order: for each layer, each direction, each
  * sequence, each visited time step, each gate row, one dot product.  Arithmetic is double
@@ -42,8 +48,10 @@
  *
  * Parity pins (tests/test_oracle_pins.py): zero-weight closed forms, hidden-size-1 scalar
  * recursions, saturated-gate identities, split-sequence / layer / direction / batch
- * invariants, bounds, a term-by-term brute force, and an fp64 library LSTM/GRU cross-check.
- * Nothing here is "parity unpinned".
+ * invariants, bounds, a term-by-term brute force, and an fp64 library LSTM/GRU cross-check; for
+ * the peephole and clipping terms scalar recursions written out separately, closed forms (clip
+ * so small that every gate sits at its clipped value) and the identities "zero peepholes" and
+ * "threshold beyond every argument" = the plain cell.  Nothing here is "parity unpinned".
  */
 #include <math.h>
 #include <stdlib.h>
@@ -56,16 +64,26 @@ enum { ORACLE_LSTM = 0, ORACLE_GRU = 1 };
 
 static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
 
+/* clip <= 0 means no clipping */
+static double limit(double a, double clip) {
+    if (clip > 0.0) {
+        if (a > clip) return clip;
+        if (a < -clip) return -clip;
+    }
+    return a;
+}
+
 static double dot(const double *w, const double *v, int n) {
     double s = 0.0;
     for (int k = 0; k < n; ++k) s += w[k] * v[k];
     return s;
 }
 
-/* One LSTM cell for one sequence: reads x[In], h_prev[H], c_prev[H]; writes h_new[H], c_new[H]. */
+/* One LSTM cell for one sequence: reads x[In], h_prev[H], c_prev[H]; writes h_new[H], c_new[H].
+ * peep: NULL or [3*H] peephole weights (p_i, p_f, p_o). */
 static void lstm_cell(int In, int H, const double *W_ih, const double *W_hh, const double *b_ih,
-                      const double *b_hh, const double *x, const double *h_prev,
-                      const double *c_prev, double *h_new, double *c_new) {
+                      const double *b_hh, const double *peep, double clip, const double *x,
+                      const double *h_prev, const double *c_prev, double *h_new, double *c_new) {
 #pragma omp parallel for schedule(static)
     for (int j = 0; j < H; ++j) {
         double a[4];
@@ -74,11 +92,12 @@ static void lstm_cell(int In, int H, const double *W_ih, const double *W_hh, con
             a[g] = dot(W_ih + (size_t)row * In, x, In) + (b_ih ? b_ih[row] : 0.0) +
                    dot(W_hh + (size_t)row * H, h_prev, H) + (b_hh ? b_hh[row] : 0.0);
         }
-        const double ig = sigmoid(a[0]);
-        const double fg = sigmoid(a[1]);
-        const double gg = tanh(a[2]);
-        const double og = sigmoid(a[3]);
+        const double p_i = peep ? peep[j] : 0.0, p_f = peep ? peep[H + j] : 0.0, p_o = peep ? peep[2 * H + j] : 0.0;
+        const double ig = sigmoid(limit(a[0] + p_i * c_prev[j], clip));
+        const double fg = sigmoid(limit(a[1] + p_f * c_prev[j], clip));
+        const double gg = tanh(limit(a[2], clip));
         const double c = fg * c_prev[j] + ig * gg;
+        const double og = sigmoid(limit(a[3] + p_o * c, clip));
         c_new[j] = c;
         h_new[j] = og * tanh(c);
     }
@@ -86,7 +105,7 @@ static void lstm_cell(int In, int H, const double *W_ih, const double *W_hh, con
 
 /* One GRU cell for one sequence.  rh is scratch of H doubles (variant 1 only). */
 static void gru_cell(int variant, int In, int H, const double *W_ih, const double *W_hh,
-                     const double *b_ih, const double *b_hh, const double *x,
+                     const double *b_ih, const double *b_hh, double clip, const double *x,
                      const double *h_prev, double *h_new, double *rgate, double *rh) {
     /* reset gate first: variant 1 needs r for every unit before the candidate's product */
 #pragma omp parallel for schedule(static)
@@ -94,7 +113,7 @@ static void gru_cell(int variant, int In, int H, const double *W_ih, const doubl
         const int row = j; /* block r */
         const double a = dot(W_ih + (size_t)row * In, x, In) + (b_ih ? b_ih[row] : 0.0) +
                          dot(W_hh + (size_t)row * H, h_prev, H) + (b_hh ? b_hh[row] : 0.0);
-        rgate[j] = sigmoid(a);
+        rgate[j] = sigmoid(limit(a, clip));
         rh[j] = rgate[j] * h_prev[j];
     }
 #pragma omp parallel for schedule(static)
@@ -102,14 +121,14 @@ static void gru_cell(int variant, int In, int H, const double *W_ih, const doubl
         const int rz = H + j, rn = 2 * H + j;
         const double az = dot(W_ih + (size_t)rz * In, x, In) + (b_ih ? b_ih[rz] : 0.0) +
                           dot(W_hh + (size_t)rz * H, h_prev, H) + (b_hh ? b_hh[rz] : 0.0);
-        const double z = sigmoid(az);
+        const double z = sigmoid(limit(az, clip));
         const double nx = dot(W_ih + (size_t)rn * In, x, In) + (b_ih ? b_ih[rn] : 0.0);
         double nh;
         if (variant == 0)
             nh = rgate[j] * (dot(W_hh + (size_t)rn * H, h_prev, H) + (b_hh ? b_hh[rn] : 0.0));
         else
             nh = dot(W_hh + (size_t)rn * H, rh, H) + (b_hh ? b_hh[rn] : 0.0);
-        const double n = tanh(nx + nh);
+        const double n = tanh(limit(nx + nh, clip));
         h_new[j] = (1.0 - z) * n + z * h_prev[j];
     }
 }
@@ -124,11 +143,14 @@ int rnn_oracle_projection(int rows, int n_out, int K, const double *in, const do
     return 0;
 }
 
-int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, int T, int B,
-                       const double *const *weights, const double *x, const int *lengths,
-                       const double *h0, const double *c0, double *y, double *hT, double *cT,
-                       double *layer_out, int nthreads) {
+/* peepholes: NULL, or L*D pointers (row l*D + d), each NULL or [3*H] (p_i, p_f, p_o), LSTM only;
+ * clip: clipping threshold, <= 0 for none. */
+int rnn_oracle_forward_ext(int cell, int gru_variant, int L, int D, int I, int H, int T, int B,
+                           const double *const *weights, const double *const *peepholes, double clip,
+                           const double *x, const int *lengths, const double *h0, const double *c0,
+                           double *y, double *hT, double *cT, double *layer_out, int nthreads) {
     if (!weights || !x || !y) return 1;
+    if (peepholes && cell != ORACLE_LSTM) return 1;
     if (cell != ORACLE_LSTM && cell != ORACLE_GRU) return 1;
     if (L < 1 || (D != 1 && D != 2) || I < 1 || H < 1 || T < 1 || B < 1) return 1;
     if (lengths)
@@ -153,6 +175,7 @@ int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, in
         for (int d = 0; d < D; ++d) {
             const double *const *w = weights + (size_t)(l * D + d) * 4;
             const double *W_ih = w[0], *W_hh = w[1], *b_ih = w[2], *b_hh = w[3];
+            const double *peep = peepholes ? peepholes[l * D + d] : NULL;
             for (int b = 0; b < B; ++b) {
                 const int len = lengths ? lengths[b] : T;
                 const size_t st = ((size_t)(l * D + d) * B + b) * H;
@@ -164,10 +187,10 @@ int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, in
                     const int t = (d == 0) ? s : len - 1 - s;
                     const double *xt = in + ((size_t)t * B + b) * In;
                     if (cell == ORACLE_LSTM) {
-                        lstm_cell(In, H, W_ih, W_hh, b_ih, b_hh, xt, h, c, h2, c2);
+                        lstm_cell(In, H, W_ih, W_hh, b_ih, b_hh, peep, clip, xt, h, c, h2, c2);
                         memcpy(c, c2, sizeof(double) * H);
                     } else {
-                        gru_cell(gru_variant, In, H, W_ih, W_hh, b_ih, b_hh, xt, h, h2, rg, rh);
+                        gru_cell(gru_variant, In, H, W_ih, W_hh, b_ih, b_hh, clip, xt, h, h2, rg, rh);
                     }
                     memcpy(h, h2, sizeof(double) * H);
                     memcpy(out_buf + ((size_t)t * B + b) * D * H + (size_t)d * H, h,
@@ -190,4 +213,13 @@ int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, in
     free(out_buf);
     free(h);
     return 0;
+}
+
+/* The plain cells: no peepholes, no clipping. */
+int rnn_oracle_forward(int cell, int gru_variant, int L, int D, int I, int H, int T, int B,
+                       const double *const *weights, const double *x, const int *lengths,
+                       const double *h0, const double *c0, double *y, double *hT, double *cT,
+                       double *layer_out, int nthreads) {
+    return rnn_oracle_forward_ext(cell, gru_variant, L, D, I, H, T, B, weights, NULL, 0.0, x, lengths,
+                                  h0, c0, y, hT, cT, layer_out, nthreads);
 }

@@ -48,6 +48,10 @@ def _load():
         lib.rnn_oracle_forward.argtypes = [ctypes.c_int] * 8 + [
             ctypes.POINTER(dp), dp, ctypes.POINTER(ctypes.c_int), dp, dp, dp, dp, dp, dp,
             ctypes.c_int]
+        lib.rnn_oracle_forward_ext.restype = ctypes.c_int
+        lib.rnn_oracle_forward_ext.argtypes = [ctypes.c_int] * 8 + [
+            ctypes.POINTER(dp), ctypes.POINTER(dp), ctypes.c_double, dp, ctypes.POINTER(ctypes.c_int),
+            dp, dp, dp, dp, dp, dp, ctypes.c_int]
         lib.rnn_oracle_projection.restype = ctypes.c_int
         lib.rnn_oracle_projection.argtypes = [ctypes.c_int] * 3 + [dp, dp, dp]
         _lib = lib
@@ -65,10 +69,12 @@ def _ptr(a: Optional[np.ndarray]):
 
 def forward(cell: int, L: int, D: int, I: int, H: int, weights: Sequence[Optional[np.ndarray]],
             x, lengths=None, h0=None, c0=None, gru_variant: int = 0, nthreads: int = 1,
-            return_layers: bool = False):
+            return_layers: bool = False, peepholes=None, clip: float = 0.0):
     """Run the oracle.  weights: L*D*4 arrays (W_ih, W_hh, b_ih, b_hh per layer and direction;
-    a bias may be None).  x: [T, B, I].  Returns (y [T,B,D*H], hT [L*D,B,H], cT or None) in
-    float64, plus layer outputs [L,T,B,D*H] when return_layers is set."""
+    a bias may be None).  x: [T, B, I].  peepholes: None or L*D arrays [3, H] (p_i, p_f, p_o; LSTM
+    only, an entry may be None); clip: clipping threshold of the gate arguments, 0 = none.
+    Returns (y [T,B,D*H], hT [L*D,B,H], cT or None) in float64, plus layer outputs [L,T,B,D*H]
+    when return_layers is set."""
     lib = _load()
     x = _as_f64(x)
     T, B, I_x = x.shape
@@ -106,9 +112,24 @@ def forward(cell: int, L: int, D: int, I: int, H: int, weights: Sequence[Optiona
     hT = np.empty((L * D, B, H), dtype=np.float64)
     cT = np.zeros((L * D, B, H), dtype=np.float64) if cell == LSTM else None
     layers = np.empty((L, T, B, D * H), dtype=np.float64) if return_layers else None
-    rc = lib.rnn_oracle_forward(cell, gru_variant, L, D, I, H, T, B, wptrs, _ptr(x), len_ptr,
-                                _ptr(h0a), _ptr(c0a), _ptr(y), _ptr(hT), _ptr(cT), _ptr(layers),
-                                int(nthreads))
+    if peepholes is None and not clip:
+        rc = lib.rnn_oracle_forward(cell, gru_variant, L, D, I, H, T, B, wptrs, _ptr(x), len_ptr,
+                                    _ptr(h0a), _ptr(c0a), _ptr(y), _ptr(hT), _ptr(cT), _ptr(layers),
+                                    int(nthreads))
+    else:
+        pp = ctypes.cast(None, ctypes.POINTER(dp))
+        keep = []
+        if peepholes is not None:
+            assert len(peepholes) == L * D
+            for q in peepholes:
+                if q is not None:
+                    q = _as_f64(q)
+                    assert q.shape == (3, H)
+                keep.append(q)
+            pp = (dp * (L * D))(*[_ptr(q) for q in keep])
+        rc = lib.rnn_oracle_forward_ext(cell, gru_variant, L, D, I, H, T, B, wptrs, pp, float(clip),
+                                        _ptr(x), len_ptr, _ptr(h0a), _ptr(c0a), _ptr(y), _ptr(hT),
+                                        _ptr(cT), _ptr(layers), int(nthreads))
     if rc != 0:
         raise ValueError("rnn_oracle_forward failed with status %d" % rc)
     if return_layers:

@@ -475,3 +475,148 @@ def test_projection_is_a_matrix_product(oracle):
     bi = np.zeros(4 * H); bi[:H] = 40; bi[H:2 * H] = -40; bi[3 * H:] = 40
     y, _, _ = oracle.forward(LSTM, 1, 1, I, H, [wi, np.zeros((4 * H, H)), bi, None], a[:, None, :])
     np.testing.assert_allclose(y[:, 0], np.tanh(np.tanh(oracle.projection(a, w[:H]))), atol=1e-14)
+
+
+# ---------------------------------------------------------------- peepholes and clipping (the ONNX operator's optional terms)
+def _clamp(a, c):
+    return max(-c, min(c, a))
+
+
+def test_peephole_scalar_recursion(oracle):
+    # hidden size 1, two layers, unrolled by hand: i and f see c_{t-1}, o sees the new c_t
+    rng = np.random.default_rng(31)
+    T = 5
+    x = rng.standard_normal((T, 1, 1))
+    ws, ps = [], []
+    for _ in range(2):
+        ws += [rng.uniform(-1, 1, (4, 1)), rng.uniform(-1, 1, (4, 1)), rng.uniform(-1, 1, 4), rng.uniform(-1, 1, 4)]
+        ps.append(rng.uniform(-2, 2, (3, 1)))
+    h0 = rng.uniform(-1, 1, (2, 1, 1))
+    c0 = rng.uniform(-2, 2, (2, 1, 1))
+    y, hT, cT = oracle.forward(LSTM, 2, 1, 1, 1, ws, x, h0=h0, c0=c0, peepholes=ps)
+    seq = [float(v) for v in x[:, 0, 0]]
+    for l in range(2):
+        wi, wh, bi, bh = ws[4 * l:4 * l + 4]
+        pi, pf, po = (float(v) for v in ps[l][:, 0])
+        h, c = float(h0[l, 0, 0]), float(c0[l, 0, 0])
+        out = []
+        for xv in seq:
+            a = [wi[g, 0] * xv + bi[g] + wh[g, 0] * h + bh[g] for g in range(4)]
+            i_ = sig(a[0] + pi * c)
+            f_ = sig(a[1] + pf * c)
+            c = f_ * c + i_ * math.tanh(a[2])
+            h = sig(a[3] + po * c) * math.tanh(c)
+            out.append(h)
+        assert abs(hT[l, 0, 0] - h) < 1e-14 and abs(cT[l, 0, 0] - c) < 1e-14
+        seq = out
+    np.testing.assert_allclose(y[:, 0, 0], seq, rtol=0, atol=1e-14)
+
+
+def test_peephole_closed_form_and_identities(oracle):
+    rng = np.random.default_rng(32)
+    I, H, T, B = 3, 4, 6, 2
+    x = rng.standard_normal((T, B, I))
+    c0 = rng.uniform(-1, 1, (1, B, H))
+    # all W = 0, b = 0: only the peepholes drive the gates, g = tanh(0) = 0, so
+    # c_t = sigma(p_f c_{t-1}) c_{t-1} and h_t = sigma(p_o c_t) tanh(c_t), whatever p_i is
+    ws = [np.zeros((4 * H, I)), np.zeros((4 * H, H)), None, None]
+    p = rng.uniform(-3, 3, (3, H))
+    y, hT, cT = oracle.forward(LSTM, 1, 1, I, H, ws, x, c0=c0, peepholes=[p])
+    c = c0[0].copy()
+    for t in range(T):
+        c = c / (1.0 + np.exp(-p[1] * c))
+        np.testing.assert_allclose(y[t], np.tanh(c) / (1.0 + np.exp(-p[2] * c)), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(cT[0], c, rtol=0, atol=1e-15)
+    # zero peepholes, a missing entry and "no peepholes" are the same network, bit for bit
+    ws = rand_weights(rng, LSTM, 2, 2, I, H)
+    ref = oracle.forward(LSTM, 2, 2, I, H, ws, x)
+    for ps in ([np.zeros((3, H))] * 4, [None] * 4, [np.zeros((3, H)), None, None, np.zeros((3, H))]):
+        got = oracle.forward(LSTM, 2, 2, I, H, ws, x, peepholes=ps)
+        for a, b in zip(ref, got):
+            assert np.array_equal(a, b)
+    # each of the three weights matters, and only in its own layer and direction
+    for k in range(3):
+        q = np.zeros((3, H)); q[k] = 0.7
+        got = oracle.forward(LSTM, 2, 2, I, H, ws, x, peepholes=[None, q, None, None])
+        assert np.max(np.abs(got[1][1] - ref[1][1])) > 1e-4          # hT of (layer 0, backward) changes
+        assert np.array_equal(got[1][0], ref[1][0])                  # (layer 0, forward) does not
+    with pytest.raises(ValueError):
+        oracle.forward(GRU, 1, 1, I, H, rand_weights(rng, GRU, 1, 1, I, H), x, peepholes=[np.zeros((3, H))])
+
+
+def test_clip_scalar_recursion(oracle):
+    rng = np.random.default_rng(33)
+    T, clip = 6, 0.8
+    x = 2 * rng.standard_normal((T, 1, 1))
+    h0v, c0v = 0.4, 5.0      # f >= sigma(-clip) keeps the first new c above the threshold
+    wi, wh = rng.uniform(-2, 2, (4, 1)), rng.uniform(-2, 2, (4, 1))
+    bi, bh = rng.uniform(-1, 1, 4), rng.uniform(-1, 1, 4)
+    p = rng.uniform(-2, 2, (3, 1))
+    y, hT, cT = oracle.forward(LSTM, 1, 1, 1, 1, [wi, wh, bi, bh], x, h0=np.full((1, 1, 1), h0v),
+                               c0=np.full((1, 1, 1), c0v), peepholes=[p], clip=clip)
+    h, c = h0v, c0v
+    hit, cmax = 0, 0.0
+    for t in range(T):
+        xv = float(x[t, 0, 0])
+        a = [wi[g, 0] * xv + bi[g] + wh[g, 0] * h + bh[g] for g in range(4)]
+        args = [a[0] + p[0, 0] * c, a[1] + p[1, 0] * c, a[2]]
+        hit += sum(abs(v) > clip for v in args)
+        c = sig(_clamp(args[1], clip)) * c + sig(_clamp(args[0], clip)) * math.tanh(_clamp(args[2], clip))
+        h = sig(_clamp(a[3] + p[2, 0] * c, clip)) * math.tanh(c)     # the cell state inside tanh(c) is not clipped
+        cmax = max(cmax, abs(c))
+        assert abs(y[t, 0, 0] - h) < 1e-14
+    assert hit >= 3 and cmax > clip          # the threshold was active, and a new c went beyond it
+    assert abs(cT[0, 0, 0] - c) < 1e-14
+    # GRU, both variants: r, z and the whole argument of n are clipped
+    wi, wh = rng.uniform(-2, 2, (3, 1)), rng.uniform(-2, 2, (3, 1))
+    bi, bh = rng.uniform(-1, 1, 3), rng.uniform(-1, 1, 3)
+    for variant in (0, 1):
+        y, hT, _ = oracle.forward(GRU, 1, 1, 1, 1, [wi, wh, bi, bh], x, h0=np.full((1, 1, 1), h0v),
+                                  gru_variant=variant, clip=clip)
+        h = h0v
+        for t in range(T):
+            xv = float(x[t, 0, 0])
+            r = sig(_clamp(wi[0, 0] * xv + bi[0] + wh[0, 0] * h + bh[0], clip))
+            z = sig(_clamp(wi[1, 0] * xv + bi[1] + wh[1, 0] * h + bh[1], clip))
+            if variant == 0:
+                n = math.tanh(_clamp(wi[2, 0] * xv + bi[2] + r * (wh[2, 0] * h + bh[2]), clip))
+            else:
+                n = math.tanh(_clamp(wi[2, 0] * xv + bi[2] + wh[2, 0] * (r * h) + bh[2], clip))
+            h = (1 - z) * n + z * h
+            assert abs(y[t, 0, 0] - h) < 1e-14
+
+
+def test_clip_closed_forms_and_identities(oracle):
+    rng = np.random.default_rng(34)
+    I, H, T, B = 3, 5, 7, 2
+    x = rng.standard_normal((T, B, I))
+    # biases of +-40 on every gate and a threshold of 1: every gate sits at its clipped value,
+    # i = f = o = sigma(1), g = tanh(1), so c_t = s c_{t-1} + s tanh(1), a geometric series
+    s, g = sig(1.0), math.tanh(1.0)
+    ws = [rng.uniform(-1, 1, (4 * H, I)), rng.uniform(-1, 1, (4 * H, H)), np.full(4 * H, 40.0), None]
+    c0 = rng.uniform(-1, 1, (1, B, H))
+    y, hT, cT = oracle.forward(LSTM, 1, 1, I, H, ws, x, c0=c0, clip=1.0)
+    c = c0[0].copy()
+    for t in range(T):
+        c = s * c + s * g
+        np.testing.assert_allclose(y[t], s * np.tanh(c), rtol=0, atol=1e-15)
+    np.testing.assert_allclose(cT[0], s ** T * c0[0] + s * g * (1 - s ** T) / (1 - s), rtol=0, atol=1e-14)
+    # the same with -40: i = f = o = sigma(-1), g = -tanh(1)
+    ws[2] = np.full(4 * H, -40.0)
+    s2 = sig(-1.0)
+    y, hT, cT = oracle.forward(LSTM, 1, 1, I, H, ws, x, c0=c0, clip=1.0)
+    np.testing.assert_allclose(cT[0], s2 ** T * c0[0] - s2 * g * (1 - s2 ** T) / (1 - s2), rtol=0, atol=1e-14)
+    # GRU with +40 everywhere and threshold 1: z = sigma(1), n = tanh(1): h_t = (1 - z) n + z h_{t-1}
+    wg = [rng.uniform(-1, 1, (3 * H, I)), rng.uniform(-1, 1, (3 * H, H)), np.full(3 * H, 40.0), None]
+    h0 = rng.uniform(-1, 1, (1, B, H))
+    for variant in (0, 1):
+        y, hT, _ = oracle.forward(GRU, 1, 1, I, H, wg, x, h0=h0, gru_variant=variant, clip=1.0)
+        np.testing.assert_allclose(hT[0], s ** T * h0[0] + (1 - s) * g * (1 - s ** T) / (1 - s), rtol=0, atol=1e-14)
+    # a threshold beyond every argument changes nothing, bit for bit; a tight one does
+    for cell in (LSTM, GRU):
+        ws = rand_weights(rng, cell, 2, 2, I, H)
+        ref = oracle.forward(cell, 2, 2, I, H, ws, x)
+        same = oracle.forward(cell, 2, 2, I, H, ws, x, clip=1e6)
+        tight = oracle.forward(cell, 2, 2, I, H, ws, x, clip=0.05)
+        assert np.array_equal(ref[0], same[0]) and np.array_equal(ref[1], same[1])
+        assert np.max(np.abs(ref[0] - tight[0])) > 1e-3
