@@ -46,8 +46,9 @@ def W_paper_grid():
     return W.paper_grid()
 
 
-def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool = False):
-    """name: one of the named workloads, or a workloads.Config."""
+def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool = False, plan=None, setup=None):
+    """name: one of the named workloads, or a workloads.Config.  plan: an rnn_plan (default: automatic).
+    setup(model, io, wl): called before the workspace is sized, to set options of the model."""
     import torch
     from paper_2307_11339_amd import harness, rnn, workloads as W
 
@@ -55,8 +56,10 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
     name = cfg.name
     t0 = time.time()
     wl = W.make_workload(cfg)
-    model = harness.DeviceModel(wl)
+    model = harness.DeviceModel(wl) if plan is None else harness.DeviceModel(wl, plan=plan)
     io = harness.DeviceIO(wl)
+    if setup is not None:
+        setup(model, io, wl)
     assert rnn.rnn_model_reserve(model.handle, cfg.T, cfg.B) == rnn.RNN_OK
     log("[bench] %s: inputs generated and uploaded in %.1f s" % (name, time.time() - t0))
     stream = torch.cuda.current_stream()
@@ -114,6 +117,43 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
             out["grid_us"] = float((tk.max() - tk.min()) / TICK_HZ * 1e6)
     model.close()
     return cfg, out
+
+
+def time_cell_variants():
+    """The cell variants and layouts beyond the plain time-major cell: what each costs.  Batch-first I/O on the
+    bidirectional workload (every plan works on a re-laid-out copy: one more pass over x and y); peephole weights
+    and a clipping threshold on the paper's own 12-layer model under the cellwise plan (the only plan that has
+    them), beside the plain cell under the same plan and under the automatic one."""
+    import numpy as np
+    import torch
+    from paper_2307_11339_amd import rnn, workloads as W
+
+    out = {}
+
+    def batch_first(model, io, wl):
+        c = wl.cfg
+        assert rnn.rnn_model_set_batch_first(model.handle, 1) == rnn.RNN_OK
+        io.x = io.x.transpose(0, 1).contiguous()
+        io.y = torch.empty((c.B, c.T, c.D * c.H), dtype=io.y.dtype, device="cuda")
+
+    _, r = time_workload("C4", steps=30, warmup=3, setup=batch_first)
+    out["C4_batch_first_ms"] = round(r["ms_per_step"], 4)
+
+    def options(model, io, wl):
+        c = wl.cfg
+        rng = np.random.default_rng(c.seed + 5)
+        ps = [rng.uniform(-1, 1, (3, c.H)).astype(np.float32) for _ in range(c.L * c.D)]
+        assert rnn.rnn_model_set_peepholes(model.handle, ps, 0) == rnn.RNN_OK
+        assert rnn.rnn_model_set_clip(model.handle, 3.0) == rnn.RNN_OK
+
+    base = W.paper_grid()[0]
+    _, r = time_workload(base, steps=5, warmup=1)
+    out["paper_base_ms"] = round(r["ms_per_step"], 4)
+    _, r = time_workload(base, steps=5, warmup=1, plan=rnn.RNN_PLAN_CELLWISE)
+    out["paper_base_cellwise_ms"] = round(r["ms_per_step"], 4)
+    _, r = time_workload(base, steps=5, warmup=1, setup=options)
+    out["paper_base_cellwise_peepholes_clip_ms"] = round(r["ms_per_step"], 4)
+    return out
 
 
 def time_projection_gemm(name: str, reps: int = 10):
@@ -309,6 +349,7 @@ def main() -> int:
 
     if not args.no_extra:
         line["projection_gemm"] = time_projection_gemm(args.workload)
+        line["cell_variants"] = time_cell_variants()
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)

@@ -117,6 +117,30 @@ int rnn_model_set_plan(rnn_model* model, int plan);
  * plan afterwards is refused). */
 int rnn_model_set_gru_reset_before(rnn_model* model, int on);
 
+/* The two optional terms that the ONNX LSTM / GRU operators (the format of the models the paper's
+ * system ingests, Section 1 and Section 4.1) add to the plain cell.  Both run under the cellwise
+ * plan only: RNN_EUNSUPPORTED while RNN_PLAN_WAVEFRONT is selected, and selecting that plan while
+ * either is set is refused.
+ *
+ * Clipping threshold: clip > 0 limits the argument of every gate activation (i, f, g, o including
+ * their peephole terms; r, z and the whole argument of n) to [-clip, +clip]; the cell state inside
+ * h = o * tanh(c) is not limited.  clip = 0 (the default) switches it off; negative or non-finite
+ * values are RNN_EINVAL. */
+int rnn_model_set_clip(rnn_model* model, float clip);
+
+/* Peephole weights, LSTM only (RNN_EUNSUPPORTED for a GRU): i = sigma(a_i + p_i * c_{t-1}),
+ * f = sigma(a_f + p_f * c_{t-1}), o = sigma(a_o + p_o * c_t).  peepholes: L*D pointers in order
+ * (layer, direction), each to 3*H fp32 values (p_i, p_f, p_o: H values each) in host memory, or in
+ * device memory when on_device != 0; a NULL entry means zeros.  The library copies them; the call
+ * waits for the device.  peepholes = NULL removes them (the plain cell again). */
+int rnn_model_set_peepholes(rnn_model* model, const float* const* peepholes, int on_device);
+
+/* on = 1: rnn_forward takes x as [B, T, I] and writes y as [B, T, D*H] (padded positions of a
+ * sequence still +0.0); the state tensors keep their layout.  Every plan works on time-major
+ * copies kept in the workspace, so this costs one more pass over x and y.  on = 0 (the default):
+ * time-major, as described at rnn_forward.  rnn_input_projection is not affected. */
+int rnn_model_set_batch_first(rnn_model* model, int on);
+
 /* Size the workspace now for forwards of T steps and B sequences under the current plan, so that
  * later rnn_forward calls of that shape allocate nothing.  Only what the plan chosen for (T, B)
  * touches is allocated (the paper's memory model, Section 3, Equation 4, counts exactly such

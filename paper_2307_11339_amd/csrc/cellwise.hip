@@ -5,7 +5,11 @@
 // figure): per cell one recurrent product (gemm.hip, M = batch) and one launch of the kernel
 // below, which adds the projection, applies the gate functions and updates the state.  The GRU
 // that applies the reset gate before the candidate's recurrent product needs two products per
-// cell with a pointwise kernel between them.
+// cell with a pointwise kernel between them.  The optional terms of the ONNX operators (peephole
+// weights, clipping threshold) exist in this plan only.  Also here: the kernel that changes the
+// layout of x and y for batch-first callers (used with every plan).
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -30,6 +34,29 @@ __global__ void state_export_kernel(const float* h_f32, const float* c_f32, floa
     if (i >= n) return;
     if (hT) hT[i] = h_f32[i];
     if (cT) cT[i] = c_f32[i];
+}
+
+// clip = 0: no clipping
+__device__ inline float limit(float v, float clip) { return clip > 0.0f ? fminf(fmaxf(v, -clip), clip) : v; }
+
+// The cell with the optional terms of the ONNX operators: peephole weights (LSTM: i and f see c_{t-1},
+// o sees the new c_t) and a clipping threshold on the argument of every gate activation (not on the
+// cell state inside o * tanh(c)).  pw = {p_i, p_f, p_o} of this unit.
+template <int CELL>
+__device__ inline float cell_update_ext(const float a[SLOTS], float h_prev, float& c, const float pw[3], float clip) {
+    if (CELL == CELL_LSTM) {
+        const float ig = sigmoid_f(limit(a[0] + pw[0] * c, clip));
+        const float fg = sigmoid_f(limit(a[1] + pw[1] * c, clip));
+        const float gg = tanh_f(limit(a[2], clip));
+        c = fg * c + ig * gg;
+        const float og = sigmoid_f(limit(a[3] + pw[2] * c, clip));
+        return og * tanh_f(c);
+    } else {
+        const float r = sigmoid_f(limit(a[0], clip));
+        const float z = sigmoid_f(limit(a[1], clip));
+        const float n = tanh_f(limit(a[2] + r * a[3], clip));
+        return (1.0f - z) * n + z * h_prev;
+    }
 }
 
 template <int CELL, int DT>
@@ -57,9 +84,15 @@ __global__ void cell_step_kernel(CellStepArgs a) {
     if (CELL == CELL_GRU && a.gh_rh) {
         // the candidate's recurrent part was computed from r * h_{t-1}: nothing left to scale
         const float nh = a.gh_rh[((size_t)b * a.H + u) * SLOTS + 3] + bs.w;
-        const float z = sigmoid_f(pre[1]);
-        const float n = tanh_f(pre[2] + nh);
+        const float z = sigmoid_f(limit(pre[1], a.clip));
+        const float n = tanh_f(limit(pre[2] + nh, a.clip));
         h = (1.0f - z) * n + z * a.h_f32[i];
+    } else if (a.peep != nullptr || a.clip > 0.0f) {
+        float pw[3] = {0.0f, 0.0f, 0.0f};
+        if (CELL == CELL_LSTM && a.peep != nullptr) {
+            pw[0] = a.peep[u]; pw[1] = a.peep[a.H + u]; pw[2] = a.peep[2 * a.H + u];
+        }
+        h = cell_update_ext<CELL>(pre, a.h_f32[i], c, pw, a.clip);
     } else {
         h = cell_update<CELL>(pre, a.h_f32[i], c);
     }
@@ -82,13 +115,38 @@ __global__ void gru_reset_kernel(CellStepArgs a) {
     if (i >= a.B * a.H) return;
     const int b = i / a.H, u = i % a.H;
     const size_t g = ((((size_t)a.t * a.B + b) * a.D + a.d) * a.H + u) * SLOTS;
-    const float r = sigmoid_f(a.gx[g] + a.gh[((size_t)b * a.H + u) * SLOTS] + a.bias[(size_t)u * SLOTS]);
+    const float r = sigmoid_f(limit(a.gx[g] + a.gh[((size_t)b * a.H + u) * SLOTS] + a.bias[(size_t)u * SLOTS], a.clip));
     const float rh = r * a.h_f32[i];
     if (DT == DT_BF16) ((bf16_t*)a.rh_st)[i] = f32_to_bf16(rh);
     else ((float*)a.rh_st)[i] = rh;
 }
 
+// dst[j][i][:] = src[i][j][:], rows of `units` elements of type V
+template <class V>
+__global__ void swap_outer_kernel(const V* __restrict__ src, V* __restrict__ dst, int n0, int n1, int units) {
+    const size_t total = (size_t)n0 * n1 * units;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t row = e / units, q = e - row * units;       // row of dst = j * n0 + i
+        const size_t j = row / n0, i = row - j * n0;
+        dst[e] = src[(i * n1 + j) * units + q];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_swap_outer(const void* src, void* dst, int n0, int n1, size_t row_bytes, hipStream_t stream) {
+    if (n0 < 1 || n1 < 1 || row_bytes == 0 || (row_bytes & 1)) return hipErrorInvalidValue;
+    const bool a16 = (((uintptr_t)src | (uintptr_t)dst | row_bytes) & 15) == 0;
+    const bool a4 = (((uintptr_t)src | (uintptr_t)dst | row_bytes) & 3) == 0;
+    const size_t unit = a16 ? 16 : a4 ? 4 : 2;
+    const size_t total = (size_t)n0 * n1 * (row_bytes / unit);
+    const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 64);
+    const int units = (int)(row_bytes / unit);
+    if (a16) swap_outer_kernel<uint4><<<blocks, 256, 0, stream>>>((const uint4*)src, (uint4*)dst, n0, n1, units);
+    else if (a4) swap_outer_kernel<uint32_t><<<blocks, 256, 0, stream>>>((const uint32_t*)src, (uint32_t*)dst, n0, n1, units);
+    else swap_outer_kernel<uint16_t><<<blocks, 256, 0, stream>>>((const uint16_t*)src, (uint16_t*)dst, n0, n1, units);
+    return hipGetLastError();
+}
 
 hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream) {
     const unsigned blocks = (unsigned)(((size_t)a.B * a.H + 255) / 256);

@@ -36,11 +36,17 @@ struct CellStepArgs {
     void* out;            // [T, B, D*H] storage type; this step writes row t, columns d*H..
     const int32_t* lengths;  // [B] or NULL
     int T;
+    const float* peep;    // NULL, or (LSTM) [3, H] peephole weights p_i, p_f, p_o of this layer and direction
+    float clip;           // clipping threshold of the gate arguments, 0 = none
 };
 hipError_t launch_cell_step(const CellStepArgs& a, hipStream_t stream);
 // GRU variant that applies the reset gate before the candidate's recurrent product: from gx, gh and
 // the bias compute r and write r * h_{t-1} (all sequences, storage type) to a.rh_st.
 hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream);
+
+// dst[j][i][:] = src[i][j][:] for i < n0, j < n1, rows of row_bytes bytes (a multiple of 2): the
+// batch-first <-> time-major change of layout of x and y.
+hipError_t launch_swap_outer(const void* src, void* dst, int n0, int n1, size_t row_bytes, hipStream_t stream);
 
 // ---- persistent wavefront kernel (wavefront.hip) -------------------------------------------
 constexpr int WF_MAX_LAYERS = 16;  // layers that may run concurrently in one launch

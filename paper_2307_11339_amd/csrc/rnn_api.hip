@@ -2,6 +2,7 @@
 // choice of execution plan.  All arithmetic of the forward pass runs in the HIP kernels.
 #include "../../include/rnn.h"
 
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -49,6 +50,12 @@ struct rnn_model {
     DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
     DevBuf rh_st, gh2;      // reset-before-product GRU (cellwise plan): r * h and the second product
     bool gru_reset_before = false;
+    float clip = 0.0f;          // clipping threshold of the gate arguments (cellwise plan only), 0 = none
+    std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM, cellwise plan only)
+    bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
+    DevBuf x_tm, y_tm;          // batch-first callers: time-major copies of x and y
+    // cell variants that only the cellwise plan implements
+    bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
     DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
     DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
     uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
@@ -96,6 +103,8 @@ void free_workspace(rnn_model* m) {
     dev_free(m->xblk);
     dev_free(m->rh_st);
     dev_free(m->gh2);
+    dev_free(m->x_tm);
+    dev_free(m->y_tm);
     m->workspace_bytes = 0;
 }
 
@@ -177,8 +186,8 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
 }
 
 int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
-    if (m->gru_reset_before && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
-    if (m->requested_plan == RNN_PLAN_CELLWISE || m->gru_reset_before) {
+    if (m->cellwise_only() && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    if (m->requested_plan == RNN_PLAN_CELLWISE || m->cellwise_only()) {
         plan = Plan();
         return RNN_OK;
     }
@@ -290,6 +299,8 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
                 a.c_f32 = (float*)m->c_f32.p + (size_t)g * per;
                 a.h_st = hst; a.out = out; a.lengths = lengths; a.T = T;
                 a.gh_rh = nullptr; a.rh_st = nullptr;
+                a.peep = m->peep.empty() ? nullptr : (const float*)m->peep[g].p;
+                a.clip = m->clip;
                 if (m->gru_reset_before) {  // r, then W_hh (r * h), whose candidate slot replaces gh's
                     a.rh_st = m->rh_st.p;
                     HIP_TRY(launch_gru_reset(a, st));
@@ -469,6 +480,10 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
         }
     }
     if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    if (rc == RNN_OK && m->batch_first) {
+        rc = grow(m, m->x_tm, rows * m->I * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->y_tm, rows * m->D * m->H * m->esize);
+    }
     return rc;
 }
 
@@ -654,6 +669,7 @@ void rnn_model_destroy(rnn_model* m) {
     for (auto& b : m->wih) dev_free(b);
     for (auto& b : m->whh) dev_free(b);
     for (auto& b : m->bias) dev_free(b);
+    for (auto& b : m->peep) dev_free(b);
     dev_free(m->status);
     for (auto& e : m->prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     delete m;
@@ -665,7 +681,7 @@ int rnn_model_set_plan(rnn_model* m, int plan) {
         return RNN_EINVAL;
     if (plan == RNN_PLAN_WAVEFRONT) {
         Plan p;
-        if (m->gru_reset_before || !choose_wavefront(m, 1, 1, p)) return RNN_EUNSUPPORTED;
+        if (m->cellwise_only() || !choose_wavefront(m, 1, 1, p)) return RNN_EUNSUPPORTED;
     }
     m->requested_plan = plan;
     return RNN_OK;
@@ -676,6 +692,50 @@ int rnn_model_set_gru_reset_before(rnn_model* m, int on) {
     if (m->cell != CELL_GRU) return on ? RNN_EUNSUPPORTED : RNN_OK;
     if (on && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     m->gru_reset_before = on != 0;
+    return RNN_OK;
+}
+
+int rnn_model_set_clip(rnn_model* m, float clip) {
+    if (!m || !(clip >= 0.0f) || !isfinite(clip)) return RNN_EINVAL;
+    if (clip > 0.0f && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    m->clip = clip;
+    return RNN_OK;
+}
+
+int rnn_model_set_peepholes(rnn_model* m, const float* const* peepholes, int on_device) {
+    if (!m) return RNN_EINVAL;
+    if (!peepholes) {   // back to the plain cell
+        if (!m->peep.empty()) HIP_TRY(hipDeviceSynchronize());   // no forward still reads them
+        for (auto& b : m->peep) { m->weight_bytes -= b.bytes; dev_free(b); }
+        m->peep.clear();
+        return RNN_OK;
+    }
+    if (m->cell != CELL_LSTM || m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    const size_t bytes = (size_t)3 * m->H * sizeof(float);
+    std::vector<DevBuf> fresh((size_t)m->L * m->D);
+    int rc = RNN_OK;
+    for (size_t g = 0; g < fresh.size() && rc == RNN_OK; ++g) {
+        rc = dev_alloc(fresh[g], bytes);
+        if (rc != RNN_OK) break;
+        hipError_t e = peepholes[g]
+            ? hipMemcpy(fresh[g].p, peepholes[g], bytes, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice)
+            : hipMemset(fresh[g].p, 0, bytes);
+        if (e != hipSuccess) { (void)hipGetLastError(); rc = RNN_EDEVICE; }
+    }
+    if (rc == RNN_OK && hipDeviceSynchronize() != hipSuccess) rc = RNN_EDEVICE;   // also: no forward still reads the old ones
+    if (rc != RNN_OK) {
+        for (auto& b : fresh) dev_free(b);
+        return rc;
+    }
+    for (auto& b : m->peep) { m->weight_bytes -= b.bytes; dev_free(b); }
+    m->peep.swap(fresh);
+    m->weight_bytes += bytes * m->peep.size();
+    return RNN_OK;
+}
+
+int rnn_model_set_batch_first(rnn_model* m, int on) {
+    if (!m || (on != 0 && on != 1)) return RNN_EINVAL;
+    m->batch_first = on != 0;
     return RNN_OK;
 }
 
@@ -699,9 +759,18 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     if (rc != RNN_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
-    if (plan.kind == RNN_PLAN_WAVEFRONT)
-        return forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
-    return forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);
+    void* y_caller = nullptr;
+    if (m->batch_first) {   // the plans work on time-major copies
+        HIP_TRY(launch_swap_outer(x, m->x_tm.p, B, T, (size_t)m->I * m->esize, st));
+        x = m->x_tm.p;
+        y_caller = y;
+        y = m->y_tm.p;
+    }
+    rc = (plan.kind == RNN_PLAN_WAVEFRONT) ? forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
+                                           : forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);
+    if (rc == RNN_OK && m->batch_first)
+        HIP_TRY(launch_swap_outer(y, y_caller, T, B, (size_t)m->D * m->H * m->esize, st));
+    return rc;
 }
 
 int rnn_input_projection(rnn_model* m, int layer, const void* in, float* gx, int rows,

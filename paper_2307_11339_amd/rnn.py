@@ -28,7 +28,8 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_forward", "rnn_input_projection", "rnn_model_check", "rnn_model_device_bytes",
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
-           "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit")
+           "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
+           "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first")
 
 _lib = None
 
@@ -67,6 +68,12 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_input_projection.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.rnn_model_check.restype = ci
     lib.rnn_model_check.argtypes = [vp]
+    lib.rnn_model_set_clip.restype = ci
+    lib.rnn_model_set_clip.argtypes = [vp, ctypes.c_float]
+    lib.rnn_model_set_peepholes.restype = ci
+    lib.rnn_model_set_peepholes.argtypes = [vp, ctypes.POINTER(vp), ci]
+    lib.rnn_model_set_batch_first.restype = ci
+    lib.rnn_model_set_batch_first.argtypes = [vp, ci]
     lib.rnn_model_set_spin_limit.restype = ci
     lib.rnn_model_set_spin_limit.argtypes = [vp, ctypes.c_uint]
     lib.rnn_model_device_bytes.restype = ctypes.c_size_t
@@ -146,6 +153,23 @@ def rnn_model_set_plan(model: int, plan: int) -> int:
 
 def rnn_model_set_gru_reset_before(model: int, on: int) -> int:
     return load_library().rnn_model_set_gru_reset_before(model, on)
+
+
+def rnn_model_set_clip(model: int, clip: float) -> int:
+    return load_library().rnn_model_set_clip(model, clip)
+
+
+def rnn_model_set_peepholes(model: int, peepholes: Optional[Sequence], on_device: int) -> int:
+    """peepholes: None, or L*D float32 tensors/arrays/None of 3*H values each."""
+    lib = load_library()
+    if peepholes is None:
+        return lib.rnn_model_set_peepholes(model, None, on_device)
+    arr = (ctypes.c_void_p * len(peepholes))(*[_ptr(q) for q in peepholes])
+    return lib.rnn_model_set_peepholes(model, arr, on_device)
+
+
+def rnn_model_set_batch_first(model: int, on: int) -> int:
+    return load_library().rnn_model_set_batch_first(model, on)
 
 
 def rnn_model_reserve(model: int, T: int, B: int) -> int:

@@ -309,6 +309,106 @@ def test_onnx_gate_order(gpu, oracle, cell):
     ref_model.close()
 
 
+@pytest.mark.parametrize("spec,clip,peep", [
+    (("lstm_opts_bf16", 0, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, True),
+    (("lstm_opts_f32", 0, 3, 1, 20, 64, 12, 5, 0, True, True), 0.4, True),
+    (("lstm_peep_only", 0, 2, 1, 64, 128, 8, 6, 1, True, True), 0.0, True),
+    (("lstm_clip_only", 0, 2, 1, 64, 128, 8, 6, 1, True, True), 0.3, False),
+    (("gru_clip_bf16", 1, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, False),
+    (("gru_clip_f32", 1, 2, 1, 12, 32, 8, 18, 0, True, True), 0.25, False),
+], ids=lambda v: v[0] if isinstance(v, tuple) else None)
+def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
+    """The optional terms of the ONNX operators (cellwise plan): peephole weights and the clipping
+    threshold of the gate arguments, against the oracle with the same terms; setting them is refused
+    where they do not exist, and taking them away restores the plain cell bit for bit."""
+    import torch
+    harness, rnn, W = gpu
+    wl = _small_workload(W, spec)
+    c = wl.cfg
+    rng = np.random.default_rng(c.seed + 99)
+    ps = [rng.uniform(-4, 4, (3, c.H)).astype(np.float32) for _ in range(c.L * c.D)] if peep else None
+    if ps is not None:
+        ps[-1] = None                          # a missing entry = zeros
+    model = harness.DeviceModel(wl)
+    io_plain, io = harness.DeviceIO(wl), harness.DeviceIO(wl)
+    harness.forward(model, io_plain)
+    torch.cuda.synchronize()
+    if clip:
+        assert rnn.rnn_model_set_clip(model.handle, clip) == rnn.RNN_OK
+    if ps is not None:
+        assert rnn.rnn_model_set_peepholes(model.handle, ps, 0) == rnn.RNN_OK
+    assert rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_EUNSUPPORTED
+    harness.forward(model, io)
+    ref = oracle.forward_workload(wl, nthreads=8, peepholes=ps, clip=clip)
+    _check(harness, wl, io, ref)
+    plain = oracle.forward_workload(wl, nthreads=8)
+    moved = float(np.max(np.abs(ref[0] - plain[0])))
+    assert moved > 3 * TOL[c.dtype]          # the terms were active: a kernel that ignored them would fail above
+    if ps is not None:   # the same from device memory
+        dev = [None if q is None else torch.from_numpy(q).cuda() for q in ps]
+        torch.cuda.synchronize()
+        assert rnn.rnn_model_set_peepholes(model.handle, dev, 1) == rnn.RNN_OK
+        y1 = io.y.clone()
+        harness.forward(model, io)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, io.y)
+    # back to the plain cell
+    assert rnn.rnn_model_set_clip(model.handle, 0.0) == rnn.RNN_OK
+    assert rnn.rnn_model_set_peepholes(model.handle, None, 0) == rnn.RNN_OK
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert torch.equal(io.y, io_plain.y) and torch.equal(io.hT, io_plain.hT)
+    # refusals
+    assert rnn.rnn_model_set_clip(model.handle, -1.0) == rnn.RNN_EINVAL
+    assert rnn.rnn_model_set_clip(model.handle, float("nan")) == rnn.RNN_EINVAL
+    if c.cell == 1:
+        assert rnn.rnn_model_set_peepholes(model.handle, [None] * (c.L * c.D), 0) == rnn.RNN_EUNSUPPORTED
+    if rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_OK:
+        assert rnn.rnn_model_set_clip(model.handle, 0.5) == rnn.RNN_EUNSUPPORTED
+        if c.cell == 0:
+            assert rnn.rnn_model_set_peepholes(model.handle, [None] * (c.L * c.D), 0) == rnn.RNN_EUNSUPPORTED
+    model.close()
+
+
+@pytest.mark.parametrize("name,plan", [("lstm_bf16_3layer", "auto"), ("gru_bf16_bidir", "auto"),
+                                       ("lstm_bf16_b299", "auto"), ("lstm_bf16_inside_sq", "auto"),
+                                       ("lstm_f32_4layer", "auto"), ("gru_f32_bidir", "cellwise")])
+def test_batch_first_layout(gpu, oracle, name, plan):
+    """rnn_model_set_batch_first: x as [B, T, I] and y as [B, T, D*H] give, element for element, what the
+    time-major call gives (same kernels on a re-laid-out copy), padded positions still +0.0 bits, the state
+    tensors unchanged; and one case against the oracle directly."""
+    import torch
+    harness, rnn, W = gpu
+    spec = [s for s in SMALL if s[0] == name][0]
+    wl = _small_workload(W, spec)
+    c = wl.cfg
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_CELLWISE if plan == "cellwise" else rnn.RNN_PLAN_AUTO)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_set_batch_first(model.handle, 1) == rnn.RNN_OK
+    x_bf = io.x.transpose(0, 1).contiguous()
+    y_bf = torch.full((c.B, c.T, c.D * c.H), 7.0, dtype=io.y.dtype, device="cuda")
+    hT, cT = torch.full_like(io.hT, 7.0), torch.full_like(io.cT, 7.0)
+    for _ in range(2):
+        assert rnn.rnn_forward(model.handle, x_bf, io.lengths, io.h0, io.c0, y_bf, hT, cT, c.T, c.B, None) == rnn.RNN_OK
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    assert torch.equal(y_bf.transpose(0, 1), io.y)
+    assert torch.equal(hT, io.hT) and (c.cell == 1 or torch.equal(cT, io.cT))
+    if name == "lstm_bf16_3layer":
+        ref = oracle.forward_workload(wl, nthreads=8)
+        err = float(np.max(np.abs(y_bf.float().cpu().numpy().astype(np.float64).transpose(1, 0, 2) - ref[0])))
+        assert err <= TOL[c.dtype]
+    assert rnn.rnn_model_set_batch_first(model.handle, 0) == rnn.RNN_OK
+    assert rnn.rnn_model_set_batch_first(model.handle, 2) == rnn.RNN_EINVAL
+    y2 = torch.full_like(io.y, 7.0)
+    assert rnn.rnn_forward(model.handle, io.x, io.lengths, io.h0, io.c0, y2, hT, cT, c.T, c.B, None) == rnn.RNN_OK
+    torch.cuda.synchronize()
+    assert torch.equal(y2, io.y)
+    model.close()
+
+
 @pytest.mark.parametrize("spec", [("gru_rb_bf16", 1, 2, 2, 40, 128, 9, 21, 1, True, True),
                                   ("gru_rb_f32", 1, 2, 1, 24, 64, 7, 5, 0, True, True)], ids=lambda s: s[0])
 def test_gru_reset_before_product(gpu, oracle, spec):
@@ -326,6 +426,11 @@ def test_gru_reset_before_product(gpu, oracle, spec):
     # the two variants really differ on this input, and switching back gives the default again
     other = oracle.forward_workload(wl, nthreads=8, gru_variant=0)
     assert float(np.max(np.abs(other[0] - ref[0]))) > 5e-2
+    # together with a clipping threshold (r, z and the whole argument of n are limited)
+    assert rnn.rnn_model_set_clip(model.handle, 0.4) == rnn.RNN_OK
+    harness.forward(model, io)
+    _check(harness, wl, io, oracle.forward_workload(wl, nthreads=8, gru_variant=1, clip=0.4))
+    assert rnn.rnn_model_set_clip(model.handle, 0.0) == rnn.RNN_OK
     assert rnn.rnn_model_set_gru_reset_before(model.handle, 0) == rnn.RNN_OK
     harness.forward(model, io)
     _check(harness, wl, io, other)
