@@ -41,6 +41,11 @@ def algorithmic_flops(cfg):
     return proj, rec
 
 
+def W_config(name):
+    from paper_2307_11339_amd import workloads as W
+    return W.CONFIGS[name]
+
+
 def W_paper_grid():
     from paper_2307_11339_amd import workloads as W
     return W.paper_grid()
@@ -336,6 +341,16 @@ def main() -> int:
                     e["step_over_lds_bound"] = round(e["step_us_p50"] / bound_us, 2)
             extra[name] = e
         line["workloads"] = extra
+
+    if not args.no_extra:
+        # latency of a single sequence through the shapes that are named with a batch (C1 and C3 have batch 1 as given)
+        b1 = {}
+        for name in ("C2", "C4", "C5"):
+            c1 = W_config(name).scaled(name=name + "/batch1", B=1)
+            _, r = time_workload(c1, steps=20, warmup=3, per_call=30)
+            b1[name] = {"p50_ms": round(r["p50_ms"], 4), "p90_ms": round(r["p90_ms"], 4),
+                        "ms_per_call": round(r["ms_per_step"], 4)}
+        line["batch1_latency"] = b1
 
     if not args.no_extra:
         # the paper's own model grid (Table 6): <layers, batch, io size, seq len>, fp32 LSTM
