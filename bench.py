@@ -161,6 +161,44 @@ def time_cell_variants():
     return out
 
 
+def time_graph_replay(names=("C1", "C2", "C3"), reps: int = 200):
+    """The forward pass recorded once into a HIP graph and replayed: ms per call back to back, beside the same
+    loop of eager calls (the difference is launch overhead: one graph launch instead of 2-3 kernel launches)."""
+    import torch
+    from paper_2307_11339_amd import harness, rnn, workloads as W
+
+    out = {}
+    for name in names:
+        wl = W.make_workload(W.CONFIGS[name])
+        model = harness.DeviceModel(wl)
+        io = harness.DeviceIO(wl)
+        for _ in range(5):
+            harness.forward(model, io)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            harness.forward(model, io)
+        torch.cuda.synchronize()
+
+        def loop(fn):
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - a) * 1e3 / reps
+
+        eager = loop(lambda: harness.forward(model, io))
+        replay = loop(graph.replay)
+        assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+        out[name] = {"eager_ms": round(eager, 4), "graph_replay_ms": round(replay, 4)}
+        del graph
+        model.close()
+    return out
+
+
 def time_projection_gemm(name: str, reps: int = 10):
     """The batched input projection X W_ih^T of one layer of the workload over all time steps, as a launch of its
     own (rnn_input_projection).  No named workload needs it any more (their input products run inside the
@@ -365,6 +403,7 @@ def main() -> int:
     if not args.no_extra:
         line["projection_gemm"] = time_projection_gemm(args.workload)
         line["cell_variants"] = time_cell_variants()
+        line["graph_replay"] = time_graph_replay()
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)

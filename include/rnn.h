@@ -167,6 +167,12 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  * more workspace than earlier calls or rnn_model_reserve provided (then it synchronises).
  * x and y must not overlap and must be 16-byte aligned (RNN_EINVAL otherwise: the kernels read and
  * write them in 16-byte pieces).  Inputs are not validated on the device beyond the clamping above.
+ * Stream capture: the call may be recorded into a HIP graph (`stream` in capture mode) provided the
+ * workspace already covers the shape (rnn_model_reserve, or an earlier call; RNN_EUNSUPPORTED
+ * otherwise, with nothing recorded): it then records kernels only, the first of which clear the
+ * model's step flags, because every replay reuses the tags chosen at capture time.  A replay counts
+ * as a forward in flight (one at a time per model), the pointers recorded are the ones passed here,
+ * and kernel timing (rnn_model_set_profiling) is not recorded.
  */
 int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,
                 const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream);

@@ -121,6 +121,11 @@ __global__ void gru_reset_kernel(CellStepArgs a) {
     else ((float*)a.rh_st)[i] = rh;
 }
 
+__global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
 // dst[j][i][:] = src[i][j][:], rows of `units` elements of type V
 template <class V>
 __global__ void swap_outer_kernel(const V* __restrict__ src, V* __restrict__ dst, int n0, int n1, int units) {
@@ -133,6 +138,15 @@ __global__ void swap_outer_kernel(const V* __restrict__ src, V* __restrict__ dst
 }
 
 }  // namespace
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    if (!p || (bytes & 3) || ((uintptr_t)p & 3)) return hipErrorInvalidValue;
+    const size_t words = bytes / 4;
+    const unsigned blocks = (unsigned)std::min<size_t>((words + 255) / 256, 256 * 32);
+    fill_zero_kernel<<<blocks, 256, 0, stream>>>((uint32_t*)p, words);
+    return hipGetLastError();
+}
 
 hipError_t launch_swap_outer(const void* src, void* dst, int n0, int n1, size_t row_bytes, hipStream_t stream) {
     if (n0 < 1 || n1 < 1 || row_bytes == 0 || (row_bytes & 1)) return hipErrorInvalidValue;

@@ -44,6 +44,10 @@ hipError_t launch_cell_step(const CellStepArgs& a, hipStream_t stream);
 // the bias compute r and write r * h_{t-1} (all sequences, storage type) to a.rh_st.
 hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream);
 
+// Zero `bytes` bytes (a multiple of 4) at the 4-byte aligned p with a kernel (a fill that may be
+// recorded into a stream capture, where memset nodes are avoided).
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+
 // dst[j][i][:] = src[i][j][:] for i < n0, j < n1, rows of row_bytes bytes (a multiple of 2): the
 // batch-first <-> time-major change of layout of x and y.
 hipError_t launch_swap_outer(const void* src, void* dst, int n0, int n1, size_t row_bytes, hipStream_t stream);

@@ -62,6 +62,7 @@ struct rnn_model {
     std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
     size_t workspace_bytes = 0;
     bool want_ticks = false;
+    bool capturing = false;     // the current rnn_forward is being recorded into a stream capture
     unsigned spin_limit = DEFAULT_SPIN_LIMIT;   // polls before a wait inside a persistent kernel is abandoned
 
     // optional profiling: HIP events around the kernels of each class
@@ -242,7 +243,7 @@ constexpr size_t PROF_MAX_SLOTS = 1 << 14;
 
 // Record the start of a profiled launch; returns the slot index or -1 when profiling is off.
 int prof_begin(rnn_model* m, int kind, hipStream_t st) {
-    if (!m->profiling || m->prof_used >= PROF_MAX_SLOTS) return -1;
+    if (!m->profiling || m->capturing || m->prof_used >= PROF_MAX_SLOTS) return -1;
     if (m->prof_used == m->prof.size()) {
         rnn_model::ProfSlot s;
         if (hipEventCreate(&s.a) != hipSuccess) { (void)hipGetLastError(); return -1; }
@@ -322,6 +323,7 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
 // and tagged words: tag 0 is never used by a launch).
 int grow(rnn_model* m, DevBuf& b, size_t bytes, bool zeroed = false) {
     if (b.bytes >= bytes) return RNN_OK;
+    if (m->capturing) return RNN_EUNSUPPORTED;   // no allocation and no waiting inside a stream capture
     HIP_TRY(hipDeviceSynchronize());
     m->workspace_bytes -= b.bytes;
     dev_free(b);
@@ -353,8 +355,8 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
                      bool x_from_state = false) {
     const bool tagged = plan.CT == 1 && plan.NCH == 1;
     if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
-        if (m->lseq.p) HIP_TRY(hipMemsetAsync(m->lseq.p, 0, m->lseq.bytes, st));
-        if (m->flags.p) HIP_TRY(hipMemsetAsync(m->flags.p, 0, m->flags.bytes, st));
+        HIP_TRY(launch_fill_zero(m->lseq.p, m->lseq.bytes, st));
+        HIP_TRY(launch_fill_zero(m->flags.p, m->flags.bytes, st));
         m->epoch = 1;
     }
     if (tagged) {
@@ -752,12 +754,23 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
     if (((uintptr_t)x | (uintptr_t)y) & 15) return RNN_EINVAL;
     if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    HIP_TRY(hipStreamIsCapturing(st, &capture));
+    m->capturing = capture != hipStreamCaptureStatusNone;
+    struct Done { rnn_model* m; ~Done() { m->capturing = false; } } done{m};
     Plan plan;
     int rc = resolve_plan(m, T, B, plan);
     if (rc != RNN_OK) return rc;
     rc = prepare_workspace(m, plan, T, B);   // no-op when rnn_model_reserve has seen this shape and plan
     if (rc != RNN_OK) return rc;
-    hipStream_t st = (hipStream_t)stream;
+    if (m->capturing) {
+        // The launches recorded now carry the tags chosen now, and every replay runs them again with
+        // the same tags: what the previous replay (or any other forward) left in the flag words and
+        // the tagged state words must not be taken for this run's, so a replay starts by clearing them.
+        HIP_TRY(launch_fill_zero(m->flags.p, m->flags.bytes, st));
+        HIP_TRY(launch_fill_zero(m->lseq.p, m->lseq.bytes, st));
+    }
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
     void* y_caller = nullptr;
     if (m->batch_first) {   // the plans work on time-major copies

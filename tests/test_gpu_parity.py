@@ -442,6 +442,53 @@ def test_gru_reset_before_product(gpu, oracle, spec):
     lstm.close()
 
 
+@pytest.mark.parametrize("name,plan", [("lstm_bf16_8layer_h256", "auto"),      # tag-in-data kernel
+                                       ("gru_bf16_bidir", "auto"),               # tag-in-data kernel, two launches
+                                       ("lstm_bf16_inside_sq", "auto"),          # inside-product kernel, one launch per layer
+                                       ("lstm_bf16_sidebyside_l4", "auto"),      # inside-product kernel, layers side by side
+                                       ("lstm_f32_fusedflag_l6_h32", "auto"),    # flag-vector kernel
+                                       ("lstm_f32_4layer", "cellwise")])
+def test_forward_recorded_into_a_graph(gpu, name, plan):
+    """rnn_forward recorded into a HIP graph: every replay (on new inputs, with eager forwards and
+    synchronisations between the replays) gives bit for bit what the eager call gives on the same inputs."""
+    import torch
+    harness, rnn, W = gpu
+    spec = [s for s in SMALL if s[0] == name][0]
+    wl = _small_workload(W, spec)
+    c = wl.cfg
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_CELLWISE if plan == "cellwise" else rnn.RNN_PLAN_AUTO)
+    io = harness.DeviceIO(wl)
+    _say("\n  case %s: capture" % name)
+    harness.forward(model, io)               # sizes the workspace; one-time set-up of the kernels
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        harness.forward(model, io)           # on the capturing stream: recorded, not run
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(c.seed % (2 ** 31))
+    for r in range(4):
+        # new input values in the same buffers (replays use the recorded pointers)
+        io.x.copy_(torch.randn(io.x.shape, generator=gen, device="cuda").to(io.x.dtype))
+        if io.h0 is not None:
+            io.h0.copy_(0.3 * torch.randn(io.h0.shape, generator=gen, device="cuda"))
+        harness.forward(model, io)           # eager, same inputs
+        torch.cuda.synchronize()
+        want = (io.y.clone(), io.hT.clone(), io.cT.clone())
+        for t in (io.y, io.hT, io.cT):
+            t.fill_(7.0)
+        _say("    replay %d" % r)
+        graph.replay()
+        if r == 2:
+            graph.replay()                   # two replays back to back
+        torch.cuda.synchronize()
+        assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+        assert torch.equal(io.y, want[0]) and torch.equal(io.hT, want[1])
+        assert c.cell == 1 or torch.equal(io.cT, want[2])
+    del graph
+    model.close()
+
+
 def test_kernel_runs_a_schedule_of_the_cell_graph(gpu):
     """The persistent kernel's own clock stamps (one per cell, taken when the cell is published), read as
     finish times, form a valid schedule of the cell graph that the host-side scheduler builds: no cell
