@@ -120,16 +120,84 @@ struct LLFetch {
     }
 };
 
+// A source too large to be fetched again and again (16 sequences x 64 or 128 words per wave) is
+// requested outright in segments: one load instruction covers one cache line (16 words, the units of
+// two to four producer workgroups) of 8 sequences, each is checked on its own, and only the
+// segments whose producers were late are requested again.  A step then costs one round trip when
+// everybody is on time, and a late producer costs its own segment only.  Needs QW % 16 == 0.
+template <class TR, int KB>
+__device__ inline void ll_wait_segments(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol,
+                                        int lane, uint32_t* stage, uint32_t epoch, unsigned* status,
+                                        unsigned spin_limit, bool& aborted) {
+    constexpr int QW = KB * TR::WORDS_PER_KW;
+    static_assert(QW % 16 == 0, "a sequence's quarter must be whole cache lines");
+    constexpr int LB = QW / 16;                         // cache lines per sequence and K quarter
+    constexpr int NI = 2 * LB;                          // instructions: two halves of 8 sequences each
+    constexpr int STRIDE = QW + 4;
+    const int sub = lane >> 3, pair = lane & 7;         // sequence inside the half, pair of words inside the line
+    uint32_t off[2];
+    uint32_t* dst[2];
+    bool mine[2];
+#pragma unroll
+    for (int hs = 0; hs < 2; ++hs) {
+        const int n = hs * 8 + sub;
+        mine[hs] = n < ncol;
+        off[hs] = base + (uint32_t)min(n, ncol - 1) * row_bytes + (uint32_t)pair * 16u;   // lanes past the end re-read the last sequence
+        dst[hs] = stage + min(n, ncol - 1) * STRIDE + 2 * pair;
+    }
+    const int nhalf = ncol > 8 ? 2 : 1;
+    u32x4 v[NI];
+    unsigned pending = 0;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+        if (i / LB < nhalf) {                           // uniform
+            v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off[i / LB] + (uint32_t)(i % LB) * 128u, 0, 16 /* sc1 */);
+            pending |= 1u << i;
+        }
+    unsigned spins = 0;
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            if (pending & (1u << i)) {                  // uniform
+                const bool ok = !mine[i / LB] || (v[i][1] == epoch && v[i][3] == epoch);
+                if (__all(ok)) {
+                    if (mine[i / LB]) *reinterpret_cast<uint2*>(dst[i / LB] + (i % LB) * 16) = make_uint2(v[i][0], v[i][2]);
+                    pending &= ~(1u << i);
+                }
+            }
+        if (pending == 0u || aborted) break;
+        if ((++spins & 63u) == 0u || spins == 8u) {
+            const unsigned st = ld_dev_u32(status);
+            if (st != 0u || spins >= spin_limit) {
+                st_dev_u32(status, 1u);
+                aborted = true;
+                break;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            if (pending & (1u << i))
+                v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off[i / LB] + (uint32_t)(i % LB) * 128u, 0, 16 /* sc1 */);
+    }
+}
+
 // Wait until the tagged words at `base` are complete and leave their payloads in the staging area.
 // When the source needs more than one load instruction, waiting is done on a single probe
 // instruction whose lanes sample the first word of every producer tile (4 hidden units written
 // by one wave of one workgroup) over the sequences of the block; the full fetch follows and is
 // repeated until every tag matches.
-template <class TR, int KB, bool OUTRIGHT = false>
+// MODE 1 (a compile-time choice of the launch): a source of two to four load instructions is fetched
+// outright first.  MODE 2: a larger source is fetched outright in segments, see ll_wait_segments.
+template <class TR, int KB, int MODE = 0>
 __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol, int lane,
                                uint32_t probe_rel, uint32_t* stage, uint32_t epoch, unsigned* status,
                                unsigned spin_limit, bool& aborted) {
     constexpr int QW = KB * TR::WORDS_PER_KW;           // tagged words per sequence in one K quarter
+    constexpr bool OUTRIGHT = MODE == 1;
+    if constexpr (MODE == 2) {
+        ll_wait_segments<TR, KB>(base, rsrc, row_bytes, ncol, lane, stage, epoch, status, spin_limit, aborted);
+        return;
+    }
     unsigned spins = 0;
     // Called after 8 unsuccessful probes or fetches (no wait of a healthy launch in its steady state
     // lasts that long) and then every 256 probes or 64 fetches: the poll budget and the status word
@@ -207,11 +275,12 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
 // XW: 0 = no x waves; otherwise x waves, XW = twice the ratio of input width to H of the launch's first
 // layer: 2 = as wide as the layer (also when that layer reads a projection), 1 = half as wide, 4 = twice as wide
 // (a bidirectional layer above the first, which reads [forward, backward] of the layer below).
-// XWO = XW + 8 when the h waves fetch a state of two to four load instructions outright (see ll_wait).
+// XWO = XW + 8 when the h waves fetch a state of two to four load instructions outright, XW + 16 when they
+// fetch a larger one outright in segments (see ll_wait).
 template <class TR, int CELL, int RT, int KB, int XWO>
 __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
     constexpr int XW = XWO & 7;
-    constexpr bool OUTRIGHT = (XWO & 8) != 0;
+    constexpr int WAIT_MODE = (XWO >> 3) & 3;        // how the h waves fetch the state, see ll_wait
     constexpr bool FUSED = XW > 0;
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
@@ -437,7 +506,7 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) acc[rt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-        ll_wait<TR, KB, OUTRIGHT>(own_off + (uint32_t)s * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
+        ll_wait<TR, KB, WAIT_MODE>(own_off + (uint32_t)s * slot_bytes + quarter_off, rsrc, row_bytes, ncol, lane,
                                   probe_rel, stage, epoch, p.status, p.spin_limit, aborted);
         ll_consume<TR, RT, KB>(wh, stage, ncol, lane, acc);
 
@@ -535,10 +604,12 @@ hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
     const size_t smem = (size_t)(XW ? 3 : 1) * 4 * RT * 64 * sizeof(f32x4) +
                         (size_t)(XW ? 8 : 4) * 16 * (QW + 4) * sizeof(uint32_t);
     auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, XWO>;
-    if (smem > 48 * 1024) {
+    static bool configured = false;
+    if (!configured && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
+        configured = true;
     }
     kern<<<dim3(grid), dim3(XW ? 512 : 256), smem, stream>>>(a);
     return hipGetLastError();
@@ -555,9 +626,12 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
     // the state of a step: min(16, B) sequences x one K quarter; two to four load instructions (128 words
     // each) are fetched outright
     constexpr int QW = KB * TR::WORDS_PER_KW;
+    const int total = (a.B < 16 ? a.B : 16) * QW;
     if constexpr (QW <= 64) {
-        const int total = (a.B < 16 ? a.B : 16) * QW;
         if (total > 128 && total <= 512) return launch_ll_cell2<TR, RT, KB, XW + 8>(a, stream);
+    }
+    if constexpr (QW >= 64 && QW % 16 == 0) {   // more than four load instructions: outright in segments
+        if (total > 512) return launch_ll_cell2<TR, RT, KB, XW + 16>(a, stream);
     }
     return launch_ll_cell2<TR, RT, KB, XW>(a, stream);
 }

@@ -81,6 +81,9 @@ SMALL = [
     ("gru_bf16_bidir_half_h128", 1, 2, 2, 64, 128, 8, 5, 1, True, False),
     ("lstm_bf16_20layer_h256", 0, 20, 1, 256, 256, 6, 2, 1, True, True),     # two launches: the second reads the first's output
     ("gru_bf16_sq_h128_t1", 1, 2, 1, 128, 128, 1, 3, 1, False, True),          # a single step, input read by the x waves
+    # a state of more than four load instructions per wave (16 sequences x 64 or 128 words): fetched outright in
+    # segments; a last block of 5 sequences, a second half of 4
+    ("lstm_bf16_bidir_h512_b37", 0, 2, 2, 64, 512, 6, 37, 1, True, True),
     ("lstm_bf16_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True),    # large batch: flag-vector kernel, two chains per workgroup
     ("gru_bf16_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True),  # large batch, both directions
     ("lstm_bf16_b299", 0, 2, 1, 64, 512, 6, 299, 1, True, True),    # batch not a multiple of 4: padded rows in the blocked state
