@@ -630,7 +630,12 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
     if constexpr (QW <= 64) {
         if (total > 128 && total <= 512) return launch_ll_cell2<TR, RT, KB, XW + 8>(a, stream);
     }
-    if constexpr (QW >= 64 && QW % 16 == 0) {   // more than four load instructions: outright in segments
+    // More than four load instructions: outright in segments, where that was measured to pay: quarters of
+    // 64 words (512 units in bf16), 9 to 16 sequences (2 layers x 2 directions x 512 units, batch 64: 1.35 ->
+    // 1.22 ms; batch 9 and 12 likewise 3 %).  Quarters of 128 words lose with it (4 layers x 1024 units at batch
+    // 6: 0.36 -> 0.64 ms, batch 16: 0.58 -> 0.68), and so do sources of up to four instructions (batch 4:
+    // 0.35 -> 0.46), which keep the probe word.
+    if constexpr (QW == 64) {
         if (total > 512) return launch_ll_cell2<TR, RT, KB, XW + 16>(a, stream);
     }
     return launch_ll_cell2<TR, RT, KB, XW>(a, stream);
