@@ -186,8 +186,10 @@ __device__ inline void ll_wait_segments(uint32_t base, __amdgpu_buffer_rsrc_t rs
 // instruction whose lanes sample the first word of every producer tile (4 hidden units written
 // by one wave of one workgroup) over the sequences of the block; the full fetch follows and is
 // repeated until every tag matches.
-// MODE 1 (a compile-time choice of the launch): a source of two to four load instructions is fetched
-// outright first.  MODE 2: a larger source is fetched outright in segments, see ll_wait_segments.
+// MODE is a compile-time choice of the launch.  1: a source of two to four load instructions is fetched
+// outright first.  2: a larger source is fetched outright in segments, see ll_wait_segments.  3: the
+// source is known to fit one load instruction (the generic path carries a uniform branch per possible
+// instruction, up to 16 of them, on the way in and on the way out of every fetch).
 template <class TR, int KB, int MODE = 0>
 __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int ncol, int lane,
                                uint32_t probe_rel, uint32_t* stage, uint32_t epoch, unsigned* status,
@@ -209,13 +211,23 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
             aborted = true;
         }
     };
+    if constexpr (MODE == 3) {
+        // the whole source is one load instruction: no code for the others
+        for (;;) {
+            LLFetch<QW, 1> f;
+            f.issue(rsrc, base, row_bytes, ncol, lane);
+            const bool ok = f.land(ncol, lane, epoch, stage);
+            if (ok || aborted) break;
+            if ((++spins & 63u) == 0u || spins == 8u) give_up();
+        }
+        return;
+    }
     if (ncol * QW > 128) {
         // A source of two to four load instructions is first fetched outright: the waves of a layer are
         // aligned by the second barrier of the step, and a request issued right after one's own stores
         // comes back about when everybody's have landed, so it usually succeeds and the step pays one
-        // round trip instead of two (2-layer GRU, 512 units, batch 8: 0.223 -> 0.190 ms).  Larger sources
-        // (16 sequences x 512 units: 3.15 against 1.35 ms) and any retry wait on the probe word.  (A
-        // compile-time choice of the launch: merely carrying the code costs the other paths 3-8 %.)
+        // round trip instead of two (2-layer GRU, 512 units, batch 8: 0.223 -> 0.190 ms).  Any retry
+        // waits on the probe word.
         if constexpr (OUTRIGHT) {
             LLFetch<QW> f;
             f.issue(rsrc, base, row_bytes, ncol, lane);
@@ -275,8 +287,7 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
 // XW: 0 = no x waves; otherwise x waves, XW = twice the ratio of input width to H of the launch's first
 // layer: 2 = as wide as the layer (also when that layer reads a projection), 1 = half as wide, 4 = twice as wide
 // (a bidirectional layer above the first, which reads [forward, backward] of the layer below).
-// XWO = XW + 8 when the h waves fetch a state of two to four load instructions outright, XW + 16 when they
-// fetch a larger one outright in segments (see ll_wait).
+// XWO = XW + 8 * (mode of the h waves' state fetch, see ll_wait).
 template <class TR, int CELL, int RT, int KB, int XWO>
 __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
     constexpr int XW = XWO & 7;
@@ -364,7 +375,7 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
             // x_t = state of the layer below after its step t = slot t + 1 of its sequence (t == s when
             // D == 1).  A quarter that fits a few load instructions is requested a step early and stays
             // in flight across the barriers; a larger one is fetched after them.
-            constexpr int XNI = (16 * QW + 127) / 128 < 4 ? (16 * QW + 127) / 128 : 4;
+            constexpr int XNI = WAIT_MODE == 3 ? 1 : ((16 * QW + 127) / 128 < 4 ? (16 * QW + 127) / 128 : 4);   // mode 3: one instruction covers it
             const bool early = ncol * QW <= 128 * XNI;
             LLFetch<QW, XNI, true> xq;
             if (early) xq.issue(rsrc, slot_bytes + quarter_off, row_bytes, ncol, lane);
@@ -375,7 +386,7 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
                 }
                 const uint32_t xbase = (uint32_t)(sx + 1) * slot_bytes + quarter_off;
                 if (!(early && xq.land(ncol, lane, epoch, stage)))
-                    ll_wait<TR, KB>(xbase, rsrc, row_bytes, ncol, lane, probe_rel, stage, epoch, p.status, p.spin_limit, aborted);
+                    ll_wait<TR, KB, WAIT_MODE == 3 ? 3 : 0>(xbase, rsrc, row_bytes, ncol, lane, probe_rel, stage, epoch, p.status, p.spin_limit, aborted);
                 if (early) xq.issue(rsrc, (uint32_t)min(sx + 2, T) * slot_bytes + quarter_off, row_bytes, ncol, lane);
                 __builtin_amdgcn_sched_barrier(0);
                 f32x4 acc[RT];
@@ -627,6 +638,13 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
     // each) are fetched outright
     constexpr int QW = KB * TR::WORDS_PER_KW;
     const int total = (a.B < 16 ? a.B : 16) * QW;
+    // One load instruction per wave and source: the lean fetch loop (mode 3), for layers of at least 512 units
+    // and for launches of a single layer.  Measured against the generic loop: 4 layers x 1024 units at batch 1
+    // 0.267 -> 0.233 ms, 8 such layers 1.96 -> 1.70, 2 x 512 units 0.192 -> 0.181, one layer of 128 units
+    // 0.048 -> 0.047; but stacks of 4 to 12 narrow layers (64 to 256 units) in one launch lose 6-13 % with it:
+    // there the waves of every upper layer spin on the layer below, and the generic loop's extra
+    // instructions pace those polls, whose traffic delays the stores everybody waits for.
+    if (total <= 128 && (a.H >= 512 || a.LP * a.D == 1)) return launch_ll_cell2<TR, RT, KB, XW + 24>(a, stream);
     if constexpr (QW <= 64) {
         if (total > 128 && total <= 512) return launch_ll_cell2<TR, RT, KB, XW + 8>(a, stream);
     }
