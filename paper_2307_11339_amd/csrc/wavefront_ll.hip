@@ -196,6 +196,10 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
                                unsigned spin_limit, bool& aborted) {
     constexpr int QW = KB * TR::WORDS_PER_KW;           // tagged words per sequence in one K quarter
     constexpr bool OUTRIGHT = MODE == 1;
+    // load instructions the source can take: mode 1 promises at most four (each possible instruction is a
+    // uniform branch on the way in and on the way out of a fetch)
+    constexpr int NI_ALL = (16 * QW + 127) / 128;
+    constexpr int NI = (OUTRIGHT && NI_ALL > 4) ? 4 : NI_ALL;
     if constexpr (MODE == 2) {
         ll_wait_segments<TR, KB>(base, rsrc, row_bytes, ncol, lane, stage, epoch, status, spin_limit, aborted);
         return;
@@ -229,7 +233,7 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
         // round trip instead of two (2-layer GRU, 512 units, batch 8: 0.223 -> 0.190 ms).  Any retry
         // waits on the probe word.
         if constexpr (OUTRIGHT) {
-            LLFetch<QW> f;
+            LLFetch<QW, NI> f;
             f.issue(rsrc, base, row_bytes, ncol, lane);
             if (f.land(ncol, lane, epoch, stage)) return;
         }
@@ -240,7 +244,7 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
         }
     }
     for (;;) {
-        LLFetch<QW> f;
+        LLFetch<QW, NI> f;
         f.issue(rsrc, base, row_bytes, ncol, lane);
         const bool ok = f.land(ncol, lane, epoch, stage);
         if (ok || aborted) break;
