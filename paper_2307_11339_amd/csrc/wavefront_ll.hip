@@ -230,8 +230,8 @@ __device__ inline void ll_wait(uint32_t base, __amdgpu_buffer_rsrc_t rsrc, uint3
         // A source of two to four load instructions is first fetched outright: the waves of a layer are
         // aligned by the second barrier of the step, and a request issued right after one's own stores
         // comes back about when everybody's have landed, so it usually succeeds and the step pays one
-        // round trip instead of two (2-layer GRU, 512 units, batch 8: 0.223 -> 0.190 ms).  Any retry
-        // waits on the probe word.
+        // round trip instead of two (2-layer GRU, 512 units, batch 8: 0.223 -> 0.190 ms; 4 layers of 1024
+        // units at batch 2: 0.323 -> 0.265).  Any retry waits on the probe word.
         if constexpr (OUTRIGHT) {
             LLFetch<QW, NI> f;
             f.issue(rsrc, base, row_bytes, ncol, lane);
@@ -649,7 +649,7 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
     // there the waves of every upper layer spin on the layer below, and the generic loop's extra
     // instructions pace those polls, whose traffic delays the stores everybody waits for.
     if (total <= 128 && (a.H >= 512 || a.LP * a.D == 1)) return launch_ll_cell2<TR, RT, KB, XW + 24>(a, stream);
-    if constexpr (QW <= 64) {
+    if constexpr (QW <= 128) {
         if (total > 128 && total <= 512) return launch_ll_cell2<TR, RT, KB, XW + 8>(a, stream);
     }
     // More than four load instructions: outright in segments, where that was measured to pay: quarters of

@@ -68,6 +68,7 @@ SMALL = [
     # for the input product): taller tiles, a quarter too large to be requested a step early, fp32
     ("lstm_bf16_8layer_h256", 0, 8, 1, 48, 256, 12, 3, 1, True, True),     # 8 layers x 16 workgroups, 16-row tiles x 4
     ("gru_bf16_2layer_h1024_b12", 1, 2, 1, 40, 1024, 6, 12, 1, True, True),  # x fetched after the barriers (12 x 128 words per wave)
+    ("lstm_bf16_2layer_h1024_b3", 0, 2, 1, 1024, 1024, 5, 3, 1, True, True),  # 3 x 128 words per wave: three instructions, fetched outright
     ("lstm_f32_6layer_h128", 0, 6, 1, 24, 128, 9, 5, 0, True, True),
     ("gru_bf16_4layer_h512_t1", 1, 4, 1, 32, 512, 1, 2, 1, False, True),   # a single step
     # input as wide as the layer: the first layer of the launch multiplies the plain input itself (no projection)
