@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) acc[rt][ct] = TR::mfma(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
+                for (int ct = 0; ct < CT; ++ct) TR::mfma_acc_a(wh[rt][kb], hbuf[kb][ct], acc[rt][ct]);
             // a little past half way the flag word this lane will poll is requested: by then it has
             // usually become visible (measured: earlier and the check fails too often, later and
             // the word comes back behind too many x fragments), and its round trip hides behind
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             load_x(cn, sn, kb);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (TR::HAS_ACC_A) wait_mfma_results();
     };
 
     // x comes from HBM, and every load a wave has in flight holds back the store acknowledgement

@@ -55,6 +55,15 @@ struct TraitsBf16 {
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
     }
+    // c += a x b with the A operand read from the accumulation registers (on gfx950 a matrix
+    // instruction may take A or B from either half of the register file).  Resident weights beyond the
+    // 256 vector registers live there; written this way they are operands, not spilled values that must
+    // be copied back before every use.  The compiler does not see inside: the caller keeps dependent
+    // instructions apart and waits (wait_mfma_results) before anything else reads c.
+    static __device__ inline void mfma_acc_a(const frag& a, const frag& b, f32x4& c) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "a"(a), "v"(b));
+    }
+    static constexpr bool HAS_ACC_A = true;
     typedef uint64_t piece;  // 4 consecutive units of one sequence
     static __device__ inline void store_piece_dev(elem* dst, piece v) { st_dev_u64(dst, v); }
     // Write the state value and the output value of the 4 units held by lanes n, n+16, n+32,
@@ -105,6 +114,8 @@ struct TraitsF32 {
     static __device__ inline f32x4 mfma(frag a, frag b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
     }
+    static __device__ inline void mfma_acc_a(const frag& a, const frag& b, f32x4& c) { c = mfma(a, b, c); }
+    static constexpr bool HAS_ACC_A = false;
     struct __attribute__((aligned(16))) piece { uint64_t lo, hi; };  // 4 consecutive units of one sequence
     static __device__ inline void store_piece_dev(elem* dst, piece v) {
         st_dev_u64(dst, v.lo);
@@ -129,6 +140,11 @@ struct TraitsF32 {
     static __device__ inline elem zero() { return 0.0f; }
 };
 
+
+// After a run of mfma_acc_a: the results may be read 24 wait states after the last of them was issued
+// (more than the deepest matrix pipeline needs; the compiler, which inserts such waits for the
+// instructions it knows, cannot see these).
+__device__ inline void wait_mfma_results() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
 
 // Wait until the `n` flag words at `row` carry `epoch` (n <= 64, one word per lane).  Returns
 // false when the wait was abandoned (poll budget exhausted, or another workgroup gave up).
