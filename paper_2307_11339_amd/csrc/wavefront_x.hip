@@ -30,6 +30,20 @@ namespace rnn {
 
 namespace {
 
+// How many of the KB K blocks of a wave's W_ih slice stay in (accumulation) registers instead of LDS.
+// Beside the RT * KB fragments of W_hh a lane has room for about 192 weight registers in all; what
+// fits there needs no LDS read in the input part, whose A fragments otherwise keep LDS as busy as the
+// matrix unit (four 1 KiB reads per eight matrix instructions and wave).  Only where the matrix
+// instruction can take A from those registers, and for the interleaved-chain shapes.
+template <class TR, int RT, int KB, int NCH>
+constexpr int wx_register_blocks() {
+    if (!TR::HAS_ACC_A || NCH != 2) return 0;
+    constexpr int regs_per_frag = (int)(sizeof(typename TR::frag) / 4);
+    constexpr int room = 192 - RT * KB * regs_per_frag;
+    constexpr int fit = room > 0 ? room / (RT * regs_per_frag) : 0;
+    return fit < KB ? fit : KB;
+}
+
 // MULTI: the launch runs p.LP layers side by side, one group of workgroups each; a layer above the first
 // of the launch reads the state sequence of the group below as its x, behind that group's flags, so the
 // groups settle on successive anti-diagonals of the layer x time grid (paper Section 2.2).
@@ -41,9 +55,11 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     constexpr int KW = TR::KW;
     constexpr int NTILE = RT * CT;                 // 16x16 output tiles per chain
     constexpr int NOWN = (NTILE + 3) / 4;          // tiles of a chain finished by one wave
+    constexpr int KBR = wx_register_blocks<TR, RT, KB, NCH>();   // K blocks of the W_ih slice held in registers
+    constexpr int KBL = KB - KBR;                  // ... and in LDS
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
-    frag* wxl = reinterpret_cast<frag*>(smem_raw + (size_t)4 * NTILE * 64 * sizeof(f32x4));  // [4][RT][KB][64]
+    frag* wxl = reinterpret_cast<frag*>(smem_raw + (size_t)4 * NTILE * 64 * sizeof(f32x4));  // [4][RT][KBL][64]
 
     __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
@@ -69,7 +85,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 
     // ---- resident weights: W_hh fragments in registers, W_ih fragments in LDS ------------------
     frag wh[RT][KB];
-    frag* wx_mine = wxl + (size_t)w * RT * KB * 64 + lane;
+    frag wxr[RT][KBR > 0 ? KBR : 1];               // W_ih K blocks KBL.. (register slots)
+    frag* wx_mine = wxl + (size_t)w * RT * KBL * 64 + lane;
     {
         const elem* whh = static_cast<const elem*>(p.whh[g]);
         const elem* wih = static_cast<const elem*>(p.wih[g]);
@@ -80,7 +97,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             for (int kb = 0; kb < KB; ++kb) {
                 const int k = w * kq + ((kb + rot_k) & (KB - 1)) * KW + TR::koff(lane);
                 wh[rt][kb] = TR::load(whh + row * H + k);
-                wx_mine[(rt * KB + kb) * 64] = TR::load(wih + row * H + k);
+                if (kb < KBL) wx_mine[(rt * KBL + kb) * 64] = TR::load(wih + row * H + k);
+                else wxr[rt][kb - KBL] = TR::load(wih + row * H + k);
             }
         }
     }
@@ -209,21 +227,33 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // x the x fragments.  The scheduling barriers keep the compiler from sinking each LDS read to
     // its first use, which would expose the LDS latency once per fragment.
     auto input_part = [&](f32x4 (&acc)[RT][CT], const uint64_t* xflag, uint64_t& seenx) {
-        frag abuf[2][RT];
+        if (KBL == 0) {
+            // the first matrix instructions read the freshly zeroed accumulators from inside an asm
+            // statement: keep two wait states between those writes and them
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) abuf[0][rt] = wx_mine[(rt * KB + 0) * 64];
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) asm volatile("s_nop 1" : "+a"(acc[rt][ct]));
+        }
+        frag abuf[2][RT];
+        if (KBL > 0) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) abuf[0][rt] = wx_mine[(rt * KBL + 0) * 64];
+        }
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            if (kb + 1 < KB) {
+            if (kb + 1 < KBL) {
 #pragma unroll
-                for (int rt = 0; rt < RT; ++rt) abuf[(kb + 1) & 1][rt] = wx_mine[(rt * KB + kb + 1) * 64];
+                for (int rt = 0; rt < RT; ++rt) abuf[(kb + 1) & 1][rt] = wx_mine[(rt * KBL + kb + 1) * 64];
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
+                for (int ct = 0; ct < CT; ++ct) {
+                    if (kb < KBL) acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
+                    else TR::mfma_acc_a(wxr[rt][kb - KBL], xbuf[kb][ct], acc[rt][ct]);   // the recurrent part follows: no wait here
+                }
             if (NCH > 1 && kb == KB / 8 && w == 0) store_pending_flag(1);
             // (a layer above the first of the launch) the flag word of the group below for the x fragments
             // that the recurrent part is about to request
@@ -468,9 +498,10 @@ __global__ __launch_bounds__(256) void to_blocked_kernel(const uint4* __restrict
     }
 }
 
-template <class TR, int RT, int CT, int KB>
+template <class TR, int RT, int CT, int KB, int NCH>
 constexpr size_t lds_bytes() {
-    return (size_t)4 * RT * CT * 64 * sizeof(f32x4) + (size_t)4 * RT * KB * 64 * sizeof(typename TR::frag);
+    return (size_t)4 * RT * CT * 64 * sizeof(f32x4) +
+           (size_t)4 * RT * (KB - wx_register_blocks<TR, RT, KB, NCH>()) * 64 * sizeof(typename TR::frag);
 }
 
 int device_lds_limit() {
@@ -493,7 +524,7 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if ((size_t)a.Bp * a.H * sizeof(typename TR::elem) >= ((size_t)1 << 31)) return hipErrorInvalidValue;  // 32-bit lane offsets
     if (a.Bp < a.B || a.Bp % 4 != 0) return hipErrorInvalidValue;
     const int grid = a.LP * a.nrb * (a.ncb / NCH);
-    constexpr size_t smem = lds_bytes<TR, RT, CT, KB>();
+    constexpr size_t smem = lds_bytes<TR, RT, CT, KB, NCH>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
     auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, MULTI>;
     static bool configured = false;
@@ -554,7 +585,7 @@ bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_
     const int KB = H / (4 * kw);
 #define X(TR, rt, ct, kb, nch)                                                               \
     if (DtOf<TR>::value == dtype && RT == rt && CT == ct && KB == kb && NCH == nch)          \
-        return lds_bytes<TR, rt, ct, kb>() <= lds_limit;
+        return lds_bytes<TR, rt, ct, kb, nch>() <= lds_limit;
     RNN_WFX_VARIANTS(X)
 #undef X
     return false;
