@@ -31,7 +31,7 @@ namespace rnn {
 namespace {
 
 // How many of the KB K blocks of a wave's W_ih slice stay in (accumulation) registers instead of LDS.
-// Beside the RT * KB fragments of W_hh a lane has room for about 192 weight registers in all; what
+// Beside the RT * KB fragments of W_hh a lane has room for 224 weight registers in all (256 accumulation registers less the 32 accumulators); what
 // fits there needs no LDS read in the input part, whose A fragments otherwise keep LDS as busy as the
 // matrix unit (four 1 KiB reads per eight matrix instructions and wave).  Only where the matrix
 // instruction can take A from those registers, and for the interleaved-chain shapes.
@@ -39,7 +39,7 @@ template <class TR, int RT, int KB, int NCH>
 constexpr int wx_register_blocks() {
     if (!TR::HAS_ACC_A || NCH != 2) return 0;
     constexpr int regs_per_frag = (int)(sizeof(typename TR::frag) / 4);
-    constexpr int room = 192 - RT * KB * regs_per_frag;
+    constexpr int room = 224 - RT * KB * regs_per_frag;
     constexpr int fit = room > 0 ? room / (RT * regs_per_frag) : 0;
     return fit < KB ? fit : KB;
 }
