@@ -33,7 +33,10 @@ namespace {
 // How many of the KB K blocks of a wave's W_ih slice stay in (accumulation) registers instead of LDS.
 // Beside the RT * KB fragments of W_hh a lane has room for 224 weight registers in all (256 accumulation registers less the 32 accumulators); what
 // fits there needs no LDS read in the input part, whose A fragments otherwise keep LDS as busy as the
-// matrix unit (four 1 KiB reads per eight matrix instructions and wave).  Only where the matrix
+// matrix unit (four 1 KiB reads per eight matrix instructions and wave).  (With all 256 accumulation
+// registers given to weights and the accumulators in vector registers instead, both slices of 1024 units
+// would fit, but matrix instructions whose C operand sits in the vector registers run much slower here:
+// 2 layers of 512 units at batch 512 take 1.83 ms that way against 1.36.)  Only where the matrix
 // instruction can take A from those registers, and for the interleaved-chain shapes.
 template <class TR, int RT, int KB, int NCH>
 constexpr int wx_register_blocks() {
