@@ -45,8 +45,9 @@ def test_medium_batch_layers_side_by_side():
     # a narrower first layer runs alone behind its projection, the three above it side by side
     rc, plan, sep = _query(sq.scaled(I=64))
     assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and plan["launches"] == 2 and sep == [1, 0, 0, 0]
-    # without the LDS for W_ih the layers still share a launch, the first one projects
-    rc, plan, sep = _query(sq, lds=64 * 1024)
+    # without the LDS for the part of W_ih that does not fit the registers (64 KiB are needed beside the exchange
+    # buffer) the layers still share a launch, the first one projects
+    rc, plan, sep = _query(sq, lds=48 * 1024)
     assert rc == rnn.RNN_OK and plan["layers_per_launch"] == 4 and plan["launches"] == 1 and sep == [1, 0, 0, 0]
 
 
@@ -74,11 +75,14 @@ def test_fewer_compute_units_mean_more_launches():
 
 
 def test_inside_product_needs_lds_for_the_weights():
-    """Large batch, one layer per launch: W_ih lives in LDS; without enough LDS the layer projects."""
+    """Large batch, one layer per launch: a quarter of the W_ih slice lives in LDS (32 KiB beside the 32 KiB
+    exchange buffer); without that much LDS the layer projects."""
     c = W.CONFIGS["C5"]
-    rc, plan, sep = _query(c, lds=64 * 1024)
+    rc, plan, sep = _query(c, lds=48 * 1024)
     assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
     assert sep == [1] * 8
+    rc, plan, sep = _query(c, lds=64 * 1024)
+    assert rc == rnn.RNN_OK and sep == [0] * 8
 
 
 def test_invariants_over_random_shapes():
