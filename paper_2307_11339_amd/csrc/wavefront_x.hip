@@ -6,10 +6,11 @@
 // Same decomposition and step protocol as the flag-vector kernel (a workgroup owns RT*4 hidden
 // units for NCH chains of CT*16 sequences, the four waves split K, a vector of flag words per
 // step, a write-once blocked state sequence).  What differs:
-//   - the workgroup's W_ih slice lives in LDS next to the partial-sum exchange buffer, laid out
-//     fragment by fragment exactly as the MFMA reads its A operand (each wave reads back only what
-//     it wrote itself); W_hh stays in registers, because the recurrent product is the part of a
-//     step that sits on the dependency chain;
+//   - W_hh stays in registers, because the recurrent product is the part of a step that sits on
+//     the dependency chain; the workgroup's W_ih slice follows it into the accumulation registers
+//     as far as they reach (wx_register_blocks), and the rest lives in LDS next to the partial-sum
+//     exchange buffer, laid out fragment by fragment exactly as the MFMA reads its A operand (each
+//     wave reads back only what it wrote itself);
 //   - x has the layout of a state sequence (blocked by 16 units): a layer above the first reads
 //     the state sequence of the layer below directly (and a layer that is not the last keeps no
 //     other output), the first layer reads a re-laid-out copy of the caller's x.  Fragment loads
