@@ -694,7 +694,8 @@ hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     X(LLBf16, 4, 1) X(LLBf16, 4, 2) X(LLBf16, 4, 4) X(LLBf16, 4, 8)               \
     X(LLF32, 1, 2) X(LLF32, 1, 4) X(LLF32, 1, 8)                                  \
     X(LLF32, 2, 2) X(LLF32, 2, 4) X(LLF32, 2, 8)                                  \
-    X(LLF32, 4, 2) X(LLF32, 4, 4) X(LLF32, 4, 8)
+    X(LLF32, 4, 2) X(LLF32, 4, 4) X(LLF32, 4, 8)                                  \
+    X(LLF32, 1, 16) X(LLF32, 2, 16) X(LLF32, 4, 16) X(LLF32, 2, 32) X(LLF32, 4, 32)
 
 template <class TR> struct LLDtOf;
 template <> struct LLDtOf<LLBf16> { static constexpr int value = DT_BF16; };

@@ -80,6 +80,11 @@ SMALL = [
     ("lstm_f32_half_h64", 0, 1, 1, 32, 64, 7, 33, 0, True, True),
     ("lstm_bf16_bidir_sq_h256", 0, 2, 2, 256, 256, 9, 20, 1, True, True),
     ("gru_bf16_bidir_half_h128", 1, 2, 2, 64, 128, 8, 5, 1, True, False),
+    # fp32 layers of 256 and 512 units (tag-in-data kernel: 16 and 32 K blocks of 4 per wave)
+    ("lstm_f32_2layer_sq_h256", 0, 2, 1, 256, 256, 7, 5, 0, True, True),
+    ("gru_f32_3layer_h512", 1, 3, 1, 100, 512, 5, 3, 0, True, True),
+    ("lstm_f32_half_h256", 0, 2, 1, 128, 256, 6, 1, 0, False, True),
+    ("gru_f32_bidir_h256_b20", 1, 2, 2, 256, 256, 5, 20, 0, True, True),
     ("lstm_bf16_20layer_h256", 0, 20, 1, 256, 256, 6, 2, 1, True, True),     # two launches: the second reads the first's output
     ("gru_bf16_sq_h128_t1", 1, 2, 1, 128, 128, 1, 3, 1, False, True),          # a single step, input read by the x waves
     # a state of more than four load instructions per wave (16 sequences x 64 or 128 words): fetched outright in
