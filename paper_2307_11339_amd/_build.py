@@ -9,10 +9,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librnn_mi355x.so")
-SOURCES = ["rnn_api.hip", "gemm.hip", "cellwise.hip", "wavefront.hip", "wavefront_x.hip", "wavefront_ll.hip", "schedule.hip"]
-HEADERS = ["common.h", "kernels.h", "wf_traits.h", os.path.join("..", "..", "include", "rnn.h"),
+SOURCES = ["rnn_api.hip", "gemm.hip", "cellwise.hip", "wavefront.hip", "wavefront_x.hip", "wavefront_ll.hip", "wavefront_ll_b.hip",
+           "wavefront_ll_c.hip", "schedule.hip"]
+HEADERS = ["common.h", "kernels.h", "wf_traits.h", "wavefront_ll.hip", os.path.join("..", "..", "include", "rnn.h"),
            os.path.join("..", "..", "include", "rnn_schedule.h")]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unused-const-variable",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
@@ -33,7 +34,7 @@ def _compile(src: str, obj: str) -> None:
         sys.stderr.write(out + "\n")
 
 
-def build(force: bool = True, jobs: int = 4) -> str:
+def build(force: bool = True, jobs: int = 6) -> str:
     """Compile every kernel source and link librnn_mi355x.so.  With force=False nothing is
     done when the library is newer than all sources."""
     deps = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.normpath(os.path.join(CSRC, h)) for h in HEADERS]

@@ -23,6 +23,13 @@
 // Every wait is bounded (poll budget, shared status word), so the grid always drains.
 #include "wf_traits.h"
 
+// The variants of this kernel are compiled in three translation units so that the build runs in
+// parallel: this file is part 0 (and holds the public functions); wavefront_ll_b.hip and
+// wavefront_ll_c.hip include it with RNN_LL_PART set to 1 and 2.
+#ifndef RNN_LL_PART
+#define RNN_LL_PART 0
+#endif
+
 namespace rnn {
 namespace {
 
@@ -260,7 +267,7 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
                                   f32x4 (&acc)[RT]) {
     constexpr int QW = KB * TR::WORDS_PER_KW;
     constexpr int STRIDE = QW + 4;
-    constexpr int G = KB < 4 ? KB : 4;                  // fragments per group
+    constexpr int G = KB % 4 == 0 ? 4 : KB % 3 == 0 ? 3 : KB % 2 == 0 ? 2 : 1;   // fragments per group (a divisor of KB)
     // B operand fragments from the staging area: lane (n, q) reads sequence min(n, ncol-1)
     const uint32_t* mine = stage + min(lane & 15, ncol - 1) * STRIDE + TR::word_of(TR::koff(lane));
     typename TR::frag f[2][G];
@@ -649,7 +656,7 @@ hipError_t launch_ll_cell(const WavefrontArgs& a, hipStream_t stream) {
     // there the waves of every upper layer spin on the layer below, and the generic loop's extra
     // instructions pace those polls, whose traffic delays the stores everybody waits for.
     if (total <= 128 && (a.H >= 512 || a.LP * a.D == 1)) return launch_ll_cell2<TR, RT, KB, XW + 24>(a, stream);
-    if constexpr (QW <= 128) {
+    if constexpr (QW <= 256) {
         if (total > 128 && total <= 512) return launch_ll_cell2<TR, RT, KB, XW + 8>(a, stream);
     }
     // More than four load instructions: outright in segments, where that was measured to pay: quarters of
@@ -687,21 +694,56 @@ hipError_t launch_ll_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     return launch_ll_cell<TR, RT, KB, 0>(a, stream);
 }
 
-// (dtype traits, RT, KB) combinations that are compiled; KB = H / (4 * KW), CT is always 1.
-#define RNN_LL_VARIANTS(X)                                                       \
+// (dtype traits, RT, KB) combinations that are compiled; KB = H / (4 * KW), CT is always 1.  bf16: layers of
+// 128 * KB units; fp32: 16 * KB units.  The taller tiles stop where the weight fragments of a wave (RT * KB,
+// four registers each in bf16) no longer fit beside its other registers.
+#define RNN_LL_VARIANTS_0(X)                                                     \
     X(LLBf16, 1, 1) X(LLBf16, 1, 2) X(LLBf16, 1, 4) X(LLBf16, 1, 8)               \
     X(LLBf16, 2, 1) X(LLBf16, 2, 2) X(LLBf16, 2, 4) X(LLBf16, 2, 8)               \
-    X(LLBf16, 4, 1) X(LLBf16, 4, 2) X(LLBf16, 4, 4) X(LLBf16, 4, 8)               \
+    X(LLBf16, 4, 1) X(LLBf16, 4, 2) X(LLBf16, 4, 4) X(LLBf16, 4, 8)
+#define RNN_LL_VARIANTS_1(X)                                                     \
     X(LLF32, 1, 2) X(LLF32, 1, 4) X(LLF32, 1, 8)                                  \
     X(LLF32, 2, 2) X(LLF32, 2, 4) X(LLF32, 2, 8)                                  \
     X(LLF32, 4, 2) X(LLF32, 4, 4) X(LLF32, 4, 8)                                  \
     X(LLF32, 1, 16) X(LLF32, 2, 16) X(LLF32, 4, 16) X(LLF32, 2, 32) X(LLF32, 4, 32)
+#define RNN_LL_VARIANTS_2(X)                                                     \
+    X(LLBf16, 1, 3) X(LLBf16, 2, 3) X(LLBf16, 4, 3)                               \
+    X(LLBf16, 1, 5) X(LLBf16, 2, 5) X(LLBf16, 4, 5)                               \
+    X(LLBf16, 1, 6) X(LLBf16, 2, 6) X(LLBf16, 4, 6)                               \
+    X(LLBf16, 1, 10) X(LLBf16, 2, 10) X(LLBf16, 1, 12) X(LLBf16, 2, 12)           \
+    X(LLBf16, 1, 16) X(LLBf16, 2, 16)
+#define RNN_LL_VARIANTS(X) RNN_LL_VARIANTS_0(X) RNN_LL_VARIANTS_1(X) RNN_LL_VARIANTS_2(X)
+#if RNN_LL_PART == 0
+#define RNN_LL_VARIANTS_HERE(X) RNN_LL_VARIANTS_0(X)
+#elif RNN_LL_PART == 1
+#define RNN_LL_VARIANTS_HERE(X) RNN_LL_VARIANTS_1(X)
+#else
+#define RNN_LL_VARIANTS_HERE(X) RNN_LL_VARIANTS_2(X)
+#endif
 
 template <class TR> struct LLDtOf;
 template <> struct LLDtOf<LLBf16> { static constexpr int value = DT_BF16; };
 template <> struct LLDtOf<LLF32> { static constexpr int value = DT_F32; };
 
+// the variants compiled in this translation unit
+hipError_t launch_here(const WavefrontArgs& a, hipStream_t stream, int KB) {
+#define X(TR, rt, kb)                                                 \
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb)       \
+        return launch_ll_cell_fused<TR, rt, kb>(a, stream);
+    RNN_LL_VARIANTS_HERE(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
+
+#if RNN_LL_PART == 1
+hipError_t launch_wavefront_ll_part1(const WavefrontArgs& a, hipStream_t stream, int KB) { return launch_here(a, stream, KB); }
+#elif RNN_LL_PART == 2
+hipError_t launch_wavefront_ll_part2(const WavefrontArgs& a, hipStream_t stream, int KB) { return launch_here(a, stream, KB); }
+#else
+hipError_t launch_wavefront_ll_part1(const WavefrontArgs& a, hipStream_t stream, int KB);
+hipError_t launch_wavefront_ll_part2(const WavefrontArgs& a, hipStream_t stream, int KB);
 
 bool wavefront_ll_variant_exists(int dtype, int RT, int H) {
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
@@ -718,10 +760,17 @@ hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream) {
     const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
     if (a.H % (4 * kw) != 0 || a.CT != 1) return hipErrorInvalidValue;
     const int KB = a.H / (4 * kw);
-#define X(TR, rt, kb)                                                 \
-    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb)       \
-        return launch_ll_cell_fused<TR, rt, kb>(a, stream);
-    RNN_LL_VARIANTS(X)
+#define X(TR, rt, kb) \
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_here(a, stream, KB);
+    RNN_LL_VARIANTS_0(X)
+#undef X
+#define X(TR, rt, kb) \
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_wavefront_ll_part1(a, stream, KB);
+    RNN_LL_VARIANTS_1(X)
+#undef X
+#define X(TR, rt, kb) \
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_wavefront_ll_part2(a, stream, KB);
+    RNN_LL_VARIANTS_2(X)
 #undef X
     return hipErrorInvalidValue;
 }
@@ -740,5 +789,7 @@ hipError_t launch_wavefront_ll_init(int dtype, const float* h0, int l0, int LP, 
 size_t wavefront_ll_words(int dtype, int groups, int T, int B, int H) {
     return (size_t)groups * (size_t)(T + 1) * B * (dtype == DT_BF16 ? H / 2 : H);
 }
+
+#endif  // RNN_LL_PART == 0
 
 }  // namespace rnn

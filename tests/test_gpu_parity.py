@@ -85,6 +85,14 @@ SMALL = [
     ("gru_f32_3layer_h512", 1, 3, 1, 100, 512, 5, 3, 0, True, True),
     ("lstm_f32_half_h256", 0, 2, 1, 128, 256, 6, 1, 0, False, True),
     ("gru_f32_bidir_h256_b20", 1, 2, 2, 256, 256, 5, 20, 0, True, True),
+    # bf16 layers whose width is not 128 times a power of two (3, 5, 6, 10, 12 K blocks per wave), and 2048 units
+    ("lstm_bf16_2layer_sq_h384", 0, 2, 1, 384, 384, 6, 5, 1, True, True),
+    ("gru_bf16_2layer_half_h640", 1, 2, 1, 320, 640, 5, 3, 1, True, True),
+    ("lstm_bf16_3layer_sq_h768_b20", 0, 3, 1, 768, 768, 5, 20, 1, True, True),
+    ("lstm_bf16_bidir_sq_h768", 0, 2, 2, 768, 768, 5, 4, 1, True, True),
+    ("gru_bf16_2layer_sq_h1280", 1, 2, 1, 1280, 1280, 4, 2, 1, True, True),
+    ("lstm_bf16_2layer_sq_h1536", 0, 2, 1, 1536, 1536, 4, 3, 1, True, True),
+    ("lstm_bf16_2layer_sq_h2048", 0, 2, 1, 2048, 2048, 4, 2, 1, True, True),
     ("lstm_bf16_20layer_h256", 0, 20, 1, 256, 256, 6, 2, 1, True, True),     # two launches: the second reads the first's output
     ("gru_bf16_sq_h128_t1", 1, 2, 1, 128, 128, 1, 3, 1, False, True),          # a single step, input read by the x waves
     # a state of more than four load instructions per wave (16 sequences x 64 or 128 words): fetched outright in
