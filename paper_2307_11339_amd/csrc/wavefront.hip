@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     const int kq = H / 4;                           // K range of one wave inside each part
 
     // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
-    const int rot_k = rb & (KB - 1);
+    const int rot_k = rb % KB;
     const int rot_c = (rb / KB) % CT;
 
     // ---- resident weights: A operand fragments ---------------------------------------------
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
-                const int k = w * kq + ((kb + rot_k) & (KB - 1)) * KW + TR::koff(lane);
+                const int k = w * kq + wrap_kb<KB>(kb + rot_k) * KW + TR::koff(lane);
                 wh[rt][kb] = TR::load(whh + row * H + k);
                 if (FUSED) wx[rt][kb] = TR::load(wih + row * H + k);
             }
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
         const elem* hprev = hseq + (size_t)s * Bp * H;  // state after step s-1
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb) {
-            const int kr = (kb + rot_k) & (KB - 1);
+            const int kr = wrap_kb<KB>(kb + rot_k);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 if (LINEAR_K)
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
 #pragma unroll
                         for (int ct = 0; ct < CT; ++ct)
                             xbuf[kb][ct] = TR::load(reinterpret_cast<const elem*>(
-                                xs + (size_t)((kb + rot_k) & (KB - 1)) * KW * sizeof(elem) + xoff[c][ct]));
+                                xs + (size_t)wrap_kb<KB>(kb + rot_k) * KW * sizeof(elem) + xoff[c][ct]));
                     mma_part<TR, RT, CT, KB>(wx, xbuf, acc);
                 }
             }
@@ -391,7 +391,10 @@ hipError_t launch_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     X(TraitsBf16, 1, 4, 1, 1) X(TraitsBf16, 1, 4, 2, 1) X(TraitsBf16, 1, 4, 4, 1) \
     X(TraitsBf16, 4, 4, 4, 1) X(TraitsBf16, 4, 4, 8, 1)                           \
     X(TraitsBf16, 4, 2, 4, 2) X(TraitsBf16, 4, 2, 8, 2)                           \
-    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)
+    X(TraitsBf16, 4, 4, 3, 1) X(TraitsBf16, 4, 4, 5, 1) X(TraitsBf16, 4, 4, 6, 1) \
+    X(TraitsBf16, 4, 2, 3, 2) X(TraitsBf16, 4, 2, 5, 2) X(TraitsBf16, 4, 2, 6, 2) \
+    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)    \
+    X(TraitsF32, 1, 4, 16, 1) X(TraitsF32, 1, 4, 32, 1)
 
 template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };

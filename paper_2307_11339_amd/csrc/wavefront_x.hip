@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     const int kq = H / 4;                           // K range of one wave inside each part
 
     // per-workgroup rotation of the K blocks and of the column tiles (see load_part)
-    const int rot_k = rb & (KB - 1);
+    const int rot_k = rb % KB;
     const int rot_c = (rb / KB) % CT;
 
     // ---- resident weights: W_hh fragments in registers, W_ih fragments in LDS ------------------
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             const size_t row = (size_t)(rb * RT + rt) * 16 + (lane & 15);
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) {
-                const int k = w * kq + ((kb + rot_k) & (KB - 1)) * KW + TR::koff(lane);
+                const int k = w * kq + wrap_kb<KB>(kb + rot_k) * KW + TR::koff(lane);
                 wh[rt][kb] = TR::load(whh + row * H + k);
                 if (kb < KBL) wx_mine[(rt * KBL + kb) * 64] = TR::load(wih + row * H + k);
                 else wxr[rt][kb - KBL] = TR::load(wih + row * H + k);
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             hoff[c][ct] = (uint32_t)(hseq_off(kbase, bcol[c][ct], Bp) * sizeof(elem));
         }
     auto blocked_ptr = [&](const elem* step, int c, int ct, int kb) -> const elem* {
-        const int kr = (kb + rot_k) & (KB - 1);
+        const int kr = wrap_kb<KB>(kb + rot_k);
         if (LINEAR_K)
             return reinterpret_cast<const elem*>(reinterpret_cast<const char*>(step) +
                                                  (size_t)kr * KW * Bp * sizeof(elem) + hoff[c][ct]);
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
             } else {
                 constexpr int NLD = KB * CT;
-                static_assert(NLD < 64, "vmcnt has six bits");
+                static_assert(NCH == 1 || NLD < 64, "vmcnt has six bits");   // (the counted wait is used with several chains only)
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
             }
             asm volatile("" ::: "memory");
@@ -574,7 +574,10 @@ hipError_t launch_cell(const WavefrontArgs& a, hipStream_t stream) {
     X(TraitsBf16, 1, 4, 1, 1) X(TraitsBf16, 1, 4, 2, 1) X(TraitsBf16, 1, 4, 4, 1) \
     X(TraitsBf16, 4, 4, 4, 1) X(TraitsBf16, 4, 4, 8, 1)                           \
     X(TraitsBf16, 4, 2, 4, 2) X(TraitsBf16, 4, 2, 8, 2)                           \
-    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)
+    X(TraitsBf16, 4, 4, 3, 1) X(TraitsBf16, 4, 4, 5, 1) X(TraitsBf16, 4, 4, 6, 1) \
+    X(TraitsBf16, 4, 2, 3, 2) X(TraitsBf16, 4, 2, 5, 2) X(TraitsBf16, 4, 2, 6, 2) \
+    X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)    \
+    X(TraitsF32, 1, 4, 16, 1) X(TraitsF32, 1, 4, 32, 1)
 
 template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };

@@ -186,6 +186,13 @@ __device__ inline void flag_span(int k0, int kn, int H, int line_units, int rb_u
     count = (hi - lo + rb_units - 1) / rb_units;
 }
 
+// i modulo KB for 0 <= i < 2 * KB (KB is a compile-time constant, usually a power of two)
+template <int KB>
+__device__ inline int wrap_kb(int i) {
+    if constexpr ((KB & (KB - 1)) == 0) return i & (KB - 1);
+    else return i >= KB ? i - KB : i;
+}
+
 // Activation fragments of one part (h_{t-1} or x_t) for CT column tiles: buf[kb][ct].  src[ct]
 // points at this lane's first K element of the sequence in column tile ct.  Register slot kb
 // holds K block (kb + rot) mod KB: workgroups that read the same activations at the same
@@ -194,11 +201,10 @@ __device__ inline void flag_span(int k0, int kn, int H, int line_units, int rb_u
 template <class TR, int CT, int KB>
 __device__ inline void load_part(const typename TR::elem* const (&src)[CT], int rot,
                                  typename TR::frag (&buf)[KB][CT]) {
-    static_assert((KB & (KB - 1)) == 0, "KB must be a power of two");
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) buf[kb][ct] = TR::load(src[ct] + ((kb + rot) & (KB - 1)) * TR::KW);
+        for (int ct = 0; ct < CT; ++ct) buf[kb][ct] = TR::load(src[ct] + wrap_kb<KB>(kb + rot) * TR::KW);
 }
 
 // acc[rt][ct] += W[rt][:] (resident fragments) x the loaded activation fragments

@@ -112,7 +112,13 @@ SMALL = [
     ("lstm_bf16_inside_t1", 0, 2, 1, 512, 512, 1, 512, 1, False, True),    # a single step: nothing to pipeline
     ("gru_bf16_inside_t2", 1, 2, 1, 512, 512, 2, 497, 1, True, True),      # two steps, ragged lengths 1..2, ragged batch
     ("lstm_bf16_inside_1layer", 0, 1, 1, 512, 512, 19, 512, 1, True, False),  # one layer: input re-laid out, output written
-    ("lstm_f32_inside_b501", 0, 2, 1, 128, 128, 6, 501, 0, True, True),    # odd batch in fp32: padded rows in the blocked state
+    ("lstm_f32_inside_b501", 0, 2, 1, 128, 128, 6, 501, 0, True, True),
+    # widths that are not 128 times a power of two (3, 5, 6 K blocks per wave) at a large batch
+    ("lstm_bf16_inside_sq_h768", 0, 2, 1, 768, 768, 7, 300, 1, True, True),
+    ("lstm_bf16_inside_h768_i64", 0, 2, 1, 64, 768, 6, 290, 1, True, True),       # first layer: projection + flag-vector kernel
+    ("gru_bf16_inside_sq_h384", 1, 2, 1, 384, 384, 9, 512, 1, True, True),
+    ("lstm_bf16_inside_sq_h640", 0, 2, 1, 640, 640, 5, 256, 1, True, False),
+    ("lstm_bf16_sidebyside_h768_l4", 0, 4, 1, 768, 768, 6, 64, 1, True, True),    # odd batch in fp32: padded rows in the blocked state
     # Wide layers at a medium batch: several layers share one launch of the flag-vector kernel, the upper
     # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.
     ("lstm_bf16_fusedflag_l4", 0, 4, 1, 64, 1024, 5, 40, 1, True, True),    # 4 layers x 64 workgroups, tiles of 64 sequences
