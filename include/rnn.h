@@ -167,6 +167,8 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  * more workspace than earlier calls or rnn_model_reserve provided (then it synchronises).
  * x and y must not overlap and must be 16-byte aligned (RNN_EINVAL otherwise: the kernels read and
  * write them in 16-byte pieces).  Inputs are not validated on the device beyond the clamping above.
+ * A batch that no single persistent launch can hold (for example more than 256 sequences at 1024 units)
+ * is run in passes over blocks of sequences, through copies in the workspace; results are the same.
  * Stream capture: the call may be recorded into a HIP graph (`stream` in capture mode) provided the
  * workspace already covers the shape (rnn_model_reserve, or an earlier call; RNN_EUNSUPPORTED
  * otherwise, with nothing recorded): it then records kernels only, the first of which clear the
@@ -251,6 +253,10 @@ size_t rnn_model_device_bytes(const rnn_model* model);
  *            the persistent kernels the workgroup tile (16-row tiles, 16-sequence column tiles per
  *            chain, chains per workgroup), row blocks, chains (column blocks) and the number of
  *            recurrent launches per forward pass; zeros where the cellwise plan has no such figure.
+ *            A batch larger than one persistent launch can hold runs in passes over blocks of
+ *            sequences (they do not interact): the figures then describe one full pass (its row and
+ *            column blocks say how many sequences: 16 * column tiles * chains), and the launch count
+ *            covers all passes.
  *   separate_projection[num_layers] (may be NULL): 1 where W_ih x_t of that layer is a projection
  *            launch of its own, 0 where it is computed inside the recurrent kernel.
  * Returns RNN_EINVAL / RNN_EUNSUPPORTED for the shapes rnn_model_create rejects and for a requested

@@ -126,6 +126,16 @@ __global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
         p[i] = 0u;
 }
 
+template <class V>
+__global__ void copy_2d_kernel(const char* __restrict__ src, size_t src_pitch, char* __restrict__ dst, size_t dst_pitch,
+                               int rows, int units) {
+    const size_t total = (size_t)rows * units;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / units, q = e - r * units;
+        reinterpret_cast<V*>(dst + r * dst_pitch)[q] = reinterpret_cast<const V*>(src + r * src_pitch)[q];
+    }
+}
+
 // dst[j][i][:] = src[i][j][:], rows of `units` elements of type V
 template <class V>
 __global__ void swap_outer_kernel(const V* __restrict__ src, V* __restrict__ dst, int n0, int n1, int units) {
@@ -145,6 +155,24 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
     const size_t words = bytes / 4;
     const unsigned blocks = (unsigned)std::min<size_t>((words + 255) / 256, 256 * 32);
     fill_zero_kernel<<<blocks, 256, 0, stream>>>((uint32_t*)p, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_2d(const void* src, size_t src_pitch, void* dst, size_t dst_pitch, int rows, size_t row_bytes,
+                          hipStream_t stream) {
+    if (rows < 1 || row_bytes == 0) return hipSuccess;
+    if (!src || !dst || (row_bytes & 1)) return hipErrorInvalidValue;
+    const uintptr_t all = (uintptr_t)src | (uintptr_t)dst | src_pitch | dst_pitch | row_bytes;
+    const size_t unit = (all & 15) == 0 ? 16 : (all & 3) == 0 ? 4 : 2;
+    if (all & (unit - 1)) return hipErrorInvalidValue;
+    const int units = (int)(row_bytes / unit);
+    const size_t total = (size_t)rows * units;
+    const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 64);
+    const char* s = (const char*)src;
+    char* d = (char*)dst;
+    if (unit == 16) copy_2d_kernel<uint4><<<blocks, 256, 0, stream>>>(s, src_pitch, d, dst_pitch, rows, units);
+    else if (unit == 4) copy_2d_kernel<uint32_t><<<blocks, 256, 0, stream>>>(s, src_pitch, d, dst_pitch, rows, units);
+    else copy_2d_kernel<uint16_t><<<blocks, 256, 0, stream>>>(s, src_pitch, d, dst_pitch, rows, units);
     return hipGetLastError();
 }
 

@@ -48,6 +48,11 @@ hipError_t launch_gru_reset(const CellStepArgs& a, hipStream_t stream);
 // recorded into a stream capture, where memset nodes are avoided).
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 
+// `rows` rows of row_bytes bytes (a multiple of 2) from src (rows src_pitch bytes apart) to dst (dst_pitch):
+// a block of sequences out of, or back into, a [.., B, ..] tensor.
+hipError_t launch_copy_2d(const void* src, size_t src_pitch, void* dst, size_t dst_pitch, int rows, size_t row_bytes,
+                          hipStream_t stream);
+
 // dst[j][i][:] = src[i][j][:] for i < n0, j < n1, rows of row_bytes bytes (a multiple of 2): the
 // batch-first <-> time-major change of layout of x and y.
 hipError_t launch_swap_outer(const void* src, void* dst, int n0, int n1, size_t row_bytes, hipStream_t stream);

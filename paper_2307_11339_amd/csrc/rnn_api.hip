@@ -27,6 +27,9 @@ struct Plan {
     // the first layer runs in a launch of its own (it needs a projection, the layers above it run side
     // by side in the inside-product kernel): launches are {0}, {1..LP}, {LP+1..2LP}, ...
     bool first_alone = false;
+    // > 0: the batch is larger than one pass of this plan can hold; it runs in passes of `chunk` sequences
+    // (sequences are independent) through copies in the workspace, the last pass with a plan of its own
+    int chunk = 0;
 };
 
 }  // namespace
@@ -54,6 +57,7 @@ struct rnn_model {
     std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM, cellwise plan only)
     bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
     DevBuf x_tm, y_tm;          // batch-first callers: time-major copies of x and y
+    DevBuf x_ck, y_ck, st_ck[4];   // a batch run in passes: the pass's x, y, h0, c0, hT, cT
     // cell variants that only the cellwise plan implements
     bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
     DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
@@ -106,6 +110,9 @@ void free_workspace(rnn_model* m) {
     dev_free(m->gh2);
     dev_free(m->x_tm);
     dev_free(m->y_tm);
+    dev_free(m->x_ck);
+    dev_free(m->y_ck);
+    for (auto& b : m->st_ck) dev_free(b);
     m->workspace_bytes = 0;
 }
 
@@ -186,13 +193,22 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     return false;
 }
 
-int resolve_plan(const rnn_model* m, int T, int B, Plan& plan) {
+// may_chunk: a batch that no persistent launch can hold may be split into passes
+int resolve_plan(const rnn_model* m, int T, int B, Plan& plan, bool may_chunk = true) {
     if (m->cellwise_only() && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     if (m->requested_plan == RNN_PLAN_CELLWISE || m->cellwise_only()) {
         plan = Plan();
         return RNN_OK;
     }
     if (choose_wavefront(m, T, B, plan)) return RNN_OK;
+    if (may_chunk) {
+        // the largest multiple of 16 sequences below B that has a plan (every workgroup's tiles full)
+        for (int bc = ((B - 1) / 16) * 16; bc >= 16; bc -= 16)
+            if (choose_wavefront(m, T, bc, plan)) {
+                plan.chunk = bc;
+                return RNN_OK;
+            }
+    }
     if (m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     plan = Plan();
     return RNN_OK;
@@ -445,7 +461,7 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
 // plan touches is allocated (the paper's memory model, Section 3, Equation 4, charges a model with
 // its weights, outputs and temporaries; this is the temporaries part).
-int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
+int prepare_workspace_pass(rnn_model* m, const Plan& plan, int T, int B) {
     const size_t rows = (size_t)T * B;
     const size_t state = (size_t)m->L * m->D * B * m->H;
     const bool wavefront = plan.kind == RNN_PLAN_WAVEFRONT;
@@ -482,7 +498,33 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
         }
     }
     if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    return rc;
+}
+
+// The workspace of a whole call: that of one pass (of the last, shorter pass too, whose plan may differ),
+// the copies a batch run in passes goes through, and the time-major copies of a batch-first caller.
+int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
+    int rc;
+    if (plan.chunk == 0) {
+        rc = prepare_workspace_pass(m, plan, T, B);
+    } else {
+        Plan one = plan;
+        one.chunk = 0;
+        rc = prepare_workspace_pass(m, one, T, plan.chunk);
+        const int tail = B % plan.chunk;
+        if (rc == RNN_OK && tail != 0) {
+            Plan last;
+            rc = resolve_plan(m, T, tail, last, false);
+            if (rc == RNN_OK) rc = prepare_workspace_pass(m, last, T, tail);
+        }
+        const size_t rows = (size_t)T * plan.chunk;
+        if (rc == RNN_OK) rc = grow(m, m->x_ck, rows * m->I * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->y_ck, rows * m->D * m->H * m->esize);
+        for (int i = 0; i < 4 && rc == RNN_OK; ++i)
+            rc = grow(m, m->st_ck[i], (size_t)m->L * m->D * plan.chunk * m->H * sizeof(float));
+    }
     if (rc == RNN_OK && m->batch_first) {
+        const size_t rows = (size_t)T * B;
         rc = grow(m, m->x_tm, rows * m->I * m->esize);
         if (rc == RNN_OK) rc = grow(m, m->y_tm, rows * m->D * m->H * m->esize);
     }
@@ -532,6 +574,49 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         const int rc = launch_recurrent(m, plan, l0, LP, T, B, (const float*)m->gx.p, y, lengths, h0,
                                         c0, hT, cT, st);
         if (rc != RNN_OK) return rc;
+    }
+    return RNN_OK;
+}
+
+int forward_one_pass(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths, const float* h0,
+                     const float* c0, void* y, float* hT, float* cT, int T, int B, hipStream_t st) {
+    return (plan.kind == RNN_PLAN_WAVEFRONT) ? forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
+                                             : forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);
+}
+
+// A batch larger than one persistent launch can hold: passes of plan.chunk sequences, each gathered
+// into contiguous copies, run, and scattered back (the sequences of a batch do not interact).
+int forward_in_passes(rnn_model* m, const Plan& plan, const void* x, const int32_t* lengths, const float* h0,
+                      const float* c0, void* y, float* hT, float* cT, int T, int B, hipStream_t st) {
+    const size_t xrow = (size_t)m->I * m->esize, yrow = (size_t)m->D * m->H * m->esize;
+    const size_t srow = (size_t)m->H * sizeof(float);
+    const int groups = m->L * m->D;
+    for (int b0 = 0; b0 < B; b0 += plan.chunk) {
+        const int bc = (B - b0 < plan.chunk) ? B - b0 : plan.chunk;
+        Plan pass = plan;
+        pass.chunk = 0;
+        if (bc != plan.chunk) {
+            const int rc = resolve_plan(m, T, bc, pass, false);
+            if (rc != RNN_OK) return rc;
+        }
+        HIP_TRY(launch_copy_2d((const char*)x + b0 * xrow, B * xrow, m->x_ck.p, bc * xrow, T, bc * xrow, st));
+        float* h0p = nullptr; float* c0p = nullptr;
+        if (h0) {
+            h0p = (float*)m->st_ck[0].p;
+            HIP_TRY(launch_copy_2d((const char*)h0 + b0 * srow, B * srow, h0p, bc * srow, groups, bc * srow, st));
+        }
+        if (c0) {
+            c0p = (float*)m->st_ck[1].p;
+            HIP_TRY(launch_copy_2d((const char*)c0 + b0 * srow, B * srow, c0p, bc * srow, groups, bc * srow, st));
+        }
+        float* hTp = hT ? (float*)m->st_ck[2].p : nullptr;
+        float* cTp = cT ? (float*)m->st_ck[3].p : nullptr;
+        const int rc = forward_one_pass(m, pass, m->x_ck.p, lengths ? lengths + b0 : nullptr, h0p, c0p, m->y_ck.p, hTp,
+                                        cTp, T, bc, st);
+        if (rc != RNN_OK) return rc;
+        HIP_TRY(launch_copy_2d(m->y_ck.p, bc * yrow, (char*)y + b0 * yrow, B * yrow, T, bc * yrow, st));
+        if (hT) HIP_TRY(launch_copy_2d(hTp, bc * srow, (char*)hT + b0 * srow, B * srow, groups, bc * srow, st));
+        if (cT) HIP_TRY(launch_copy_2d(cTp, bc * srow, (char*)cT + b0 * srow, B * srow, groups, bc * srow, st));
     }
     return RNN_OK;
 }
@@ -779,8 +864,8 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
         y_caller = y;
         y = m->y_tm.p;
     }
-    rc = (plan.kind == RNN_PLAN_WAVEFRONT) ? forward_wavefront(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
-                                           : forward_cellwise(m, x, lengths, h0, c0, y, hT, cT, T, B, st);
+    rc = plan.chunk > 0 ? forward_in_passes(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
+                        : forward_one_pass(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
     if (rc == RNN_OK && m->batch_first)
         HIP_TRY(launch_swap_outer(y, y_caller, T, B, (size_t)m->D * m->H * m->esize, st));
     return rc;
@@ -881,7 +966,7 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
     plan_out[4] = wavefront ? plan.NCH : 0;
     plan_out[5] = wavefront ? plan.nrb : 0;
     plan_out[6] = wavefront ? plan.ncb : 0;
-    plan_out[7] = wavefront ? launch_count(&m, plan) : num_layers;
+    plan_out[7] = wavefront ? launch_count(&m, plan) * (plan.chunk > 0 ? (B + plan.chunk - 1) / plan.chunk : 1) : num_layers;
     if (separate_projection)
         for (int l = 0; l < num_layers; ++l)
             separate_projection[l] = !wavefront ? 1 : input_product_inside(&m, plan, l, T) ? 0 : first_of_launch(&m, plan, l) ? 1 : 0;

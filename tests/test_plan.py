@@ -85,6 +85,47 @@ def test_inside_product_needs_lds_for_the_weights():
     assert rc == rnn.RNN_OK and sep == [0] * 8
 
 
+def test_widths_covered_by_the_persistent_kernels():
+    """A wave's K quarter is a whole number of MFMA K blocks (32 values in bf16, 4 in fp32); which block counts are
+    compiled decides between a persistent kernel and one cell at a time."""
+    def kind(H, B, dtype=W.BF16, L=2, D=1, I=None):
+        c = W.Config("w", W.LSTM, L=L, D=D, I=H if I is None else I, H=H, T=32, B=B, dtype=dtype, seed=1)
+        rc, plan, _ = _query(c)
+        assert rc == rnn.RNN_OK
+        return plan["kind"]
+    for H in (128, 256, 384, 512, 640, 768, 1024):          # small and large batches
+        assert kind(H, 1) == rnn.RNN_PLAN_WAVEFRONT and kind(H, 300) == rnn.RNN_PLAN_WAVEFRONT, H
+    for H in (1280, 1536, 2048):                            # tag-in-data kernel only: large batches in many passes
+        assert kind(H, 1) == rnn.RNN_PLAN_WAVEFRONT and kind(H, 8) == rnn.RNN_PLAN_WAVEFRONT, H
+        assert kind(H, 300) == rnn.RNN_PLAN_WAVEFRONT, H
+    for H in (64, 192, 896, 1152):                          # not compiled / not a multiple of 128
+        assert kind(H, 1) == rnn.RNN_PLAN_CELLWISE, H
+    for H in (32, 64, 128, 256, 512):                       # fp32: multiples of 16 up to 512 units
+        assert kind(H, 2, dtype=W.F32) == rnn.RNN_PLAN_WAVEFRONT, H
+    assert kind(48, 2, dtype=W.F32) == rnn.RNN_PLAN_CELLWISE
+    assert kind(1024, 2, dtype=W.F32) == rnn.RNN_PLAN_CELLWISE
+
+
+def test_batches_beyond_one_launch_run_in_passes():
+    """1024 units: a launch holds 256 sequences (64 row blocks x 4 groups of 2 chains of 32).  A larger batch runs in
+    passes of the largest block of sequences that has a plan; the figures describe one pass, the launch count all."""
+    c = W.CONFIGS["C5"]
+    rc, plan, sep = _query(c, B=1000)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert (plan["row_tiles"], plan["col_tiles"], plan["chains"], plan["row_blocks"], plan["col_blocks"]) == (4, 2, 2, 64, 8)
+    assert plan["launches"] == 8 * 4 and sep == [0] * 8          # 256 + 256 + 256 + 232 sequences
+    rc, whole, _ = _query(c, B=256)
+    assert whole["launches"] == 8 and whole["col_blocks"] == 8
+    # 2048 units: 256 workgroups per layer hold one block of 16 sequences
+    wide = W.Config("wide", W.LSTM, L=1, D=1, I=2048, H=2048, T=8, B=40, dtype=W.BF16, seed=1)
+    rc, plan, _ = _query(wide)
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (256, 1, 3)
+    # the cellwise plan is never split
+    rc, plan, _ = _query(c, plan=rnn.RNN_PLAN_CELLWISE, B=1000)
+    assert plan["kind"] == rnn.RNN_PLAN_CELLWISE and plan["launches"] == 8
+
+
 def test_invariants_over_random_shapes():
     rng = random.Random(20230711)
     seen_kinds = set()
@@ -105,11 +146,16 @@ def test_invariants_over_random_shapes():
         lp, rt, ct, nch = plan["layers_per_launch"], plan["row_tiles"], plan["col_tiles"], plan["chains"]
         plain = -(-c.L // lp)                           # launches of lp layers each
         first_alone = 1 + -(-(c.L - 1) // lp)           # the first layer alone behind its projection, then lp each
-        assert plan["launches"] == plain or (lp > 1 and c.D == 1 and c.I != c.H and sep[0] == 1 and
-                                             plan["launches"] == first_alone)
+        per_pass = [plain] + ([first_alone] if lp > 1 and c.D == 1 and c.I != c.H and sep[0] == 1 else [])
+        held = plan["col_blocks"] * ct * 16             # sequences one pass holds
+        if held >= c.B:
+            assert plan["launches"] in per_pass
+        else:                                           # a batch beyond one launch: passes over blocks of sequences
+            assert any(plan["launches"] % k == 0 and plan["launches"] // k >= 2 and (plan["launches"] // k) * held >= c.B
+                       for k in per_pass)
         assert c.D == 1 or lp == 1                      # bidirectional layers cannot share a launch
         assert plan["row_blocks"] * rt * 4 == c.H       # 16 gate rows = 4 hidden units per tile
-        assert plan["col_blocks"] * ct * 16 >= c.B and plan["col_blocks"] % nch == 0
+        assert plan["col_blocks"] % nch == 0
         # all workgroups of a launch are resident at once: at most one per compute unit
         assert lp * c.D * plan["row_blocks"] * (plan["col_blocks"] // nch) <= cus
         # only the first layer of a launch can need a projection launch
