@@ -81,6 +81,11 @@ enum rnn_plan { RNN_PLAN_AUTO = 0, RNN_PLAN_CELLWISE = 1, RNN_PLAN_WAVEFRONT = 2
  * free them when the call returns.  The call synchronises the device.
  * Supported shapes: hidden_size a multiple of 4 for RNN_F32 and a multiple of 8 for RNN_BF16,
  * input_size a multiple of 8 for RNN_BF16; otherwise RNN_EUNSUPPORTED.
+ * The persistent kernels exist for certain hidden sizes (bf16: 128 x {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+ * fp32: 16 x {2, 4, 8, 16, 32}).  A model of another hidden size below the largest of them is held and run at
+ * the next such size: the added units have zero weights, zero biases and a zero initial state, stay at zero
+ * and reach nothing, and y, hT, cT are returned at the caller's size; rnn_model_device_bytes counts the padded
+ * weights.  Larger models run one cell at a time (the cellwise plan).
  */
 int rnn_model_create(rnn_model** out, int cell, int num_layers, int input_size, int hidden_size,
                      int num_directions, int dtype, const void* const* weights,
@@ -186,6 +191,8 @@ int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const f
  * in (DEVICE, [rows, I_l], dtype, row-major) -> gx (DEVICE, [rows, D, H, 4], fp32).
  * Slot s is i,f,g,o for LSTM and r,z,n,(zero) for GRU.  No bias is added.  Asynchronous on
  * `stream`.  Exposed so the projection can be tested and measured on its own.
+ * RNN_EUNSUPPORTED for a model that runs at a padded width (see rnn_model_create): it has no projection
+ * in the caller's layout.
  */
 int rnn_input_projection(rnn_model* model, int layer, const void* in, float* gx, int rows,
                          void* stream);

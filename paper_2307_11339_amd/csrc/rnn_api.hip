@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -39,7 +40,8 @@ struct Plan {
 constexpr unsigned DEFAULT_SPIN_LIMIT = 1u << 22;
 
 struct rnn_model {
-    int cell, L, I, H, D, dtype;
+    int cell, L, I, H, D, dtype;   // H: the width the kernels work with (Hu padded, see padded_width)
+    int Hu = 0;                    // the caller's hidden size
     int device = 0;
     int num_cus = 0;
     size_t lds_limit = 0;   // LDS bytes one workgroup may use
@@ -58,6 +60,7 @@ struct rnn_model {
     bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
     DevBuf x_tm, y_tm;          // batch-first callers: time-major copies of x and y
     DevBuf x_ck, y_ck, st_ck[4];   // a batch run in passes: the pass's x, y, h0, c0, hT, cT
+    DevBuf y_pad, st_pad[4];       // a padded model: y, h0, c0, hT, cT at the padded width
     // cell variants that only the cellwise plan implements
     bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
     DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
@@ -112,6 +115,8 @@ void free_workspace(rnn_model* m) {
     dev_free(m->y_tm);
     dev_free(m->x_ck);
     dev_free(m->y_ck);
+    dev_free(m->y_pad);
+    for (auto& b : m->st_pad) dev_free(b);
     for (auto& b : m->st_ck) dev_free(b);
     m->workspace_bytes = 0;
 }
@@ -523,12 +528,35 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
         for (int i = 0; i < 4 && rc == RNN_OK; ++i)
             rc = grow(m, m->st_ck[i], (size_t)m->L * m->D * plan.chunk * m->H * sizeof(float));
     }
+    if (rc == RNN_OK && m->H != m->Hu) {
+        rc = grow(m, m->y_pad, (size_t)T * B * m->D * m->H * m->esize);
+        for (int i = 0; i < 4 && rc == RNN_OK; ++i)
+            rc = grow(m, m->st_pad[i], (size_t)m->L * m->D * B * m->H * sizeof(float));
+    }
     if (rc == RNN_OK && m->batch_first) {
         const size_t rows = (size_t)T * B;
         rc = grow(m, m->x_tm, rows * m->I * m->esize);
-        if (rc == RNN_OK) rc = grow(m, m->y_tm, rows * m->D * m->H * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->y_tm, rows * m->D * m->Hu * m->esize);
     }
     return rc;
+}
+
+// The persistent kernels exist for certain widths only (a wave's K quarter is a whole number of MFMA K
+// blocks, and only some block counts are compiled).  Any other width is padded up to the next one that
+// has them: the added units get zero weights, zero biases and a zero initial state, so they stay at zero
+// (LSTM: c = 0.5 * 0 + 0.5 * tanh(0), h = 0.5 * tanh(0); GRU: h = 0.5 * tanh(0) + 0.5 * 0) and, their
+// columns of W_hh and of the next layer's W_ih being zero as well, reach nothing.  Returns H when H is
+// covered or beyond every compiled width.
+int padded_width(int dtype, int H) {
+    static const int bf16_blocks[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};   // x 128 units
+    static const int f32_blocks[] = {2, 4, 8, 16, 32};                      // x 16 units
+    const int unit = dtype == DT_BF16 ? 128 : 16;
+    const int* blocks = dtype == DT_BF16 ? bf16_blocks : f32_blocks;
+    const int n = dtype == DT_BF16 ? 10 : 5;
+    const int need = (H + unit - 1) / unit;
+    for (int i = 0; i < n; ++i)
+        if (blocks[i] >= need) return blocks[i] * unit;
+    return H;
 }
 
 // Shapes the library accepts (rnn_model_create_ordered, rnn_plan_query).
@@ -647,7 +675,8 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
 
     rnn_model* m = new (std::nothrow) rnn_model();
     if (!m) return RNN_ENOMEM;
-    m->cell = cell; m->L = num_layers; m->I = input_size; m->H = hidden_size;
+    m->cell = cell; m->L = num_layers; m->I = input_size; m->Hu = hidden_size;
+    m->H = padded_width(dtype, hidden_size);
     m->D = num_directions; m->dtype = dtype;
     m->esize = (dtype == RNN_BF16) ? 2 : 4;
     int rc = RNN_OK;
@@ -676,16 +705,25 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
         }
         return src.data();
     };
-    auto pack_matrix = [&](const void* wsrc, int K, bool recurrent, unsigned char* dst) -> int {
-        const unsigned char* s = fetch(wsrc, (size_t)G * H * K * m->esize);
+    const int Hu = m->Hu;
+    // Rows: the caller's [G*Hu, Ku] matrix; packed: [H units][SLOTS][K].  `parts` pieces of `piece`
+    // columns each (the halves [forward, backward] of a layer's input, or one piece for anything else)
+    // land `piece_to` columns apart, so that a padded layer below is read at its padded positions;
+    // rows of added units and the columns between the pieces stay zero.
+    auto pack_matrix = [&](const void* wsrc, bool recurrent, int parts, int piece, int piece_to,
+                           unsigned char* dst) -> int {
+        const int Ku = parts * piece, K = parts * piece_to;
+        const unsigned char* s = fetch(wsrc, (size_t)G * Hu * Ku * m->esize);
         if (!s) return RNN_EDEVICE;
-        const size_t rowb = (size_t)K * m->esize;
-        for (int u = 0; u < H; ++u)
+        const size_t rowb = (size_t)K * m->esize, srowb = (size_t)Ku * m->esize;
+        for (int u = 0; u < Hu; ++u)
             for (int sl = 0; sl < SLOTS; ++sl) {
-                const int r = source_row(cell, recurrent, H, u, sl, gate_order);
+                const int r = source_row(cell, recurrent, Hu, u, sl, gate_order);
+                if (r < 0) continue;                    // dst starts out zeroed
                 unsigned char* d = dst + ((size_t)u * SLOTS + sl) * rowb;
-                if (r < 0) memset(d, 0, rowb);
-                else memcpy(d, s + (size_t)r * rowb, rowb);
+                for (int q = 0; q < parts; ++q)
+                    memcpy(d + (size_t)q * piece_to * m->esize, s + (size_t)r * srowb + (size_t)q * piece * m->esize,
+                           (size_t)piece * m->esize);
             }
         return RNN_OK;
     };
@@ -694,7 +732,8 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
         const size_t one = (size_t)SLOTS * H * K * m->esize;
         packed.assign(one * D, 0);
         for (int d = 0; d < D && rc == RNN_OK; ++d)
-            rc = pack_matrix(weights[(l * D + d) * 4 + 0], K, false, packed.data() + one * d);
+            rc = (l == 0) ? pack_matrix(weights[(l * D + d) * 4 + 0], false, 1, K, K, packed.data() + one * d)
+                          : pack_matrix(weights[(l * D + d) * 4 + 0], false, D, Hu, H, packed.data() + one * d);
         if (rc == RNN_OK) rc = dev_alloc(m->wih[l], one * D);
         if (rc == RNN_OK && hipMemcpy(m->wih[l].p, packed.data(), one * D, hipMemcpyHostToDevice) != hipSuccess)
             rc = RNN_EDEVICE;
@@ -703,14 +742,14 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
             const int g = l * D + d;
             const size_t hb = (size_t)SLOTS * H * H * m->esize;
             packed.assign(hb, 0);
-            rc = pack_matrix(weights[g * 4 + 1], H, true, packed.data());
+            rc = pack_matrix(weights[g * 4 + 1], true, 1, Hu, H, packed.data());
             if (rc == RNN_OK) rc = dev_alloc(m->whh[g], hb);
             if (rc == RNN_OK && hipMemcpy(m->whh[g].p, packed.data(), hb, hipMemcpyHostToDevice) != hipSuccess)
                 rc = RNN_EDEVICE;
             m->weight_bytes += hb;
             if (rc != RNN_OK) break;
             // biases: LSTM folds b_ih + b_hh per gate; GRU keeps b_in and b_hn apart
-            const size_t bb = (size_t)G * H * m->esize;
+            const size_t bb = (size_t)G * Hu * m->esize;
             std::vector<unsigned char> bi(bb, 0), bh(bb, 0);
             if (weights[g * 4 + 2]) {
                 const unsigned char* s = fetch(weights[g * 4 + 2], bb);
@@ -722,10 +761,11 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
                 if (!s) { rc = RNN_EDEVICE; break; }
                 memcpy(bh.data(), s, bb);
             }
-            for (int u = 0; u < H; ++u)
+            std::fill(bias_host.begin(), bias_host.end(), 0.0f);
+            for (int u = 0; u < Hu; ++u)
                 for (int sl = 0; sl < SLOTS; ++sl) {
-                    const int ri = source_row(cell, false, H, u, sl, gate_order);
-                    const int rh = source_row(cell, true, H, u, sl, gate_order);
+                    const int ri = source_row(cell, false, Hu, u, sl, gate_order);
+                    const int rh = source_row(cell, true, Hu, u, sl, gate_order);
                     float v = 0.0f;
                     if (ri >= 0) v += elem_to_f32(bi.data(), ri, dtype);
                     if (rh >= 0) v += elem_to_f32(bh.data(), rh, dtype);
@@ -804,9 +844,10 @@ int rnn_model_set_peepholes(rnn_model* m, const float* const* peepholes, int on_
     for (size_t g = 0; g < fresh.size() && rc == RNN_OK; ++g) {
         rc = dev_alloc(fresh[g], bytes);
         if (rc != RNN_OK) break;
-        hipError_t e = peepholes[g]
-            ? hipMemcpy(fresh[g].p, peepholes[g], bytes, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice)
-            : hipMemset(fresh[g].p, 0, bytes);
+        hipError_t e = hipMemset(fresh[g].p, 0, bytes);   // added units: zero weights
+        for (int k = 0; k < 3 && e == hipSuccess && peepholes[g]; ++k)
+            e = hipMemcpy((float*)fresh[g].p + (size_t)k * m->H, peepholes[g] + (size_t)k * m->Hu,
+                          (size_t)m->Hu * sizeof(float), on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice);
         if (e != hipSuccess) { (void)hipGetLastError(); rc = RNN_EDEVICE; }
     }
     if (rc == RNN_OK && hipDeviceSynchronize() != hipSuccess) rc = RNN_EDEVICE;   // also: no forward still reads the old ones
@@ -864,16 +905,48 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
         y_caller = y;
         y = m->y_tm.p;
     }
+    const bool padded = m->H != m->Hu;
+    void* y_plain = y;             // time-major output at the caller's width
+    float* hT_caller = hT;
+    float* cT_caller = cT;
+    const size_t srow_u = (size_t)m->Hu * sizeof(float), srow = (size_t)m->H * sizeof(float);
+    const int state_rows = m->L * m->D * B;
+    if (padded) {                  // the plans work at the padded width: states in, y and states out
+        y = m->y_pad.p;
+        if (h0) {
+            HIP_TRY(launch_fill_zero(m->st_pad[0].p, (size_t)state_rows * srow, st));
+            HIP_TRY(launch_copy_2d(h0, srow_u, m->st_pad[0].p, srow, state_rows, srow_u, st));
+            h0 = (const float*)m->st_pad[0].p;
+        }
+        if (c0) {
+            HIP_TRY(launch_fill_zero(m->st_pad[1].p, (size_t)state_rows * srow, st));
+            HIP_TRY(launch_copy_2d(c0, srow_u, m->st_pad[1].p, srow, state_rows, srow_u, st));
+            c0 = (const float*)m->st_pad[1].p;
+        }
+        if (hT) hT = (float*)m->st_pad[2].p;
+        if (cT) cT = (float*)m->st_pad[3].p;
+    }
     rc = plan.chunk > 0 ? forward_in_passes(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
                         : forward_one_pass(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
-    if (rc == RNN_OK && m->batch_first)
-        HIP_TRY(launch_swap_outer(y, y_caller, T, B, (size_t)m->D * m->H * m->esize, st));
-    return rc;
+    if (rc != RNN_OK) return rc;
+    if (padded) {
+        const size_t yrow = (size_t)m->D * m->H * m->esize, yrow_u = (size_t)m->D * m->Hu * m->esize;
+        for (int d = 0; d < m->D; ++d)
+            HIP_TRY(launch_copy_2d((const char*)y + (size_t)d * m->H * m->esize, yrow,
+                                   (char*)y_plain + (size_t)d * m->Hu * m->esize, yrow_u, T * B,
+                                   (size_t)m->Hu * m->esize, st));
+        if (hT_caller) HIP_TRY(launch_copy_2d(hT, srow, hT_caller, srow_u, state_rows, srow_u, st));
+        if (cT_caller) HIP_TRY(launch_copy_2d(cT, srow, cT_caller, srow_u, state_rows, srow_u, st));
+    }
+    if (m->batch_first)
+        HIP_TRY(launch_swap_outer(y_plain, y_caller, T, B, (size_t)m->D * m->Hu * m->esize, st));
+    return RNN_OK;
 }
 
 int rnn_input_projection(rnn_model* m, int layer, const void* in, float* gx, int rows,
                          void* stream) {
     if (!m || !in || !gx || rows < 1 || layer < 0 || layer >= m->L) return RNN_EINVAL;
+    if (m->H != m->Hu) return RNN_EUNSUPPORTED;   // a padded model has no projection in the caller's layout
     const int K = m->layer_input(layer);
     const int N = m->D * SLOTS * m->H;
     HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[layer].p, K, gx, N, rows, N, K,
@@ -950,7 +1023,8 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
     int rc = check_model_shape(cell, num_layers, input_size, hidden_size, num_directions, dtype);
     if (rc != RNN_OK) return rc;
     rnn_model m;   // shape and device figures only: no buffer is touched
-    m.cell = cell; m.L = num_layers; m.I = input_size; m.H = hidden_size; m.D = num_directions; m.dtype = dtype;
+    m.cell = cell; m.L = num_layers; m.I = input_size; m.Hu = hidden_size; m.H = padded_width(dtype, hidden_size);
+    m.D = num_directions; m.dtype = dtype;
     m.esize = (dtype == RNN_BF16) ? 2 : 4;
     m.num_cus = compute_units;
     m.lds_limit = lds_bytes;

@@ -62,7 +62,12 @@ SMALL = [
     ("lstm_f32_4layer", 0, 4, 1, 20, 64, 10, 3, 0, True, True),
     ("gru_f32_bidir", 1, 2, 2, 12, 32, 8, 18, 0, True, True),
     ("lstm_f32_wide", 0, 1, 1, 64, 128, 5, 70, 0, False, False),
-    ("lstm_bf16_oddshape", 0, 2, 1, 24, 72, 5, 4, 1, True, True),   # H not a multiple of 128: cellwise only
+    ("lstm_bf16_oddshape", 0, 2, 1, 24, 72, 5, 4, 1, True, True),   # H not a multiple of 128: runs padded to 128 units
+    # widths between the compiled ones run padded to the next one (zero weights and zero state in the added units)
+    ("gru_bf16_padded_h200_bidir", 1, 2, 2, 40, 200, 6, 9, 1, True, True),     # 200 -> 256, both directions: [fwd | bwd] re-spaced
+    ("lstm_f32_padded_h100", 0, 3, 1, 100, 100, 7, 5, 0, True, True),          # fp32 100 -> 128
+    ("lstm_f32_padded_h20", 0, 2, 1, 12, 20, 8, 3, 0, True, True),             # fp32 20 -> 32
+    ("lstm_bf16_padded_h896_inside", 0, 2, 1, 896, 896, 5, 130, 1, True, True),  # 896 -> 1024 at a large batch
     ("lstm_bf16_t1", 0, 2, 1, 64, 128, 1, 2, 1, False, True),
     # small batches, several layers in one launch of the tag-in-data kernel (fused layers have their own waves
     # for the input product): taller tiles, a quarter too large to be requested a step early, fp32
@@ -342,6 +347,7 @@ def test_onnx_gate_order(gpu, oracle, cell):
     (("lstm_clip_only", 0, 2, 1, 64, 128, 8, 6, 1, True, True), 0.3, False),
     (("gru_clip_bf16", 1, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, False),
     (("gru_clip_f32", 1, 2, 1, 12, 32, 8, 18, 0, True, True), 0.25, False),
+    (("lstm_opts_padded_h72", 0, 2, 2, 24, 72, 6, 5, 1, True, True), 0.6, True),      # 72 -> 128 units: padded peephole weights
 ], ids=lambda v: v[0] if isinstance(v, tuple) else None)
 def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
     """The optional terms of the ONNX operators (cellwise plan): peephole weights and the clipping
@@ -398,7 +404,8 @@ def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
 
 @pytest.mark.parametrize("name,plan", [("lstm_bf16_3layer", "auto"), ("gru_bf16_bidir", "auto"),
                                        ("lstm_bf16_b299", "auto"), ("lstm_bf16_inside_sq", "auto"),
-                                       ("lstm_f32_4layer", "auto"), ("gru_f32_bidir", "cellwise")])
+                                       ("lstm_f32_4layer", "auto"), ("gru_f32_bidir", "cellwise"),
+                                       ("gru_bf16_padded_h200_bidir", "auto")])
 def test_batch_first_layout(gpu, oracle, name, plan):
     """rnn_model_set_batch_first: x as [B, T, I] and y as [B, T, D*H] give, element for element, what the
     time-major call gives (same kernels on a re-laid-out copy), padded positions still +0.0 bits, the state
@@ -473,7 +480,8 @@ def test_gru_reset_before_product(gpu, oracle, spec):
                                        ("lstm_bf16_inside_sq", "auto"),          # inside-product kernel, one launch per layer
                                        ("lstm_bf16_sidebyside_l4", "auto"),      # inside-product kernel, layers side by side
                                        ("lstm_f32_fusedflag_l6_h32", "auto"),    # flag-vector kernel
-                                       ("lstm_f32_4layer", "cellwise")])
+                                       ("lstm_f32_4layer", "cellwise"),
+                                       ("lstm_f32_padded_h100", "auto")])
 def test_forward_recorded_into_a_graph(gpu, name, plan):
     """rnn_forward recorded into a HIP graph: every replay (on new inputs, with eager forwards and
     synchronisations between the replays) gives bit for bit what the eager call gives on the same inputs."""

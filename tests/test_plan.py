@@ -56,11 +56,15 @@ def test_cellwise_requested_or_forced():
     rc, plan, sep = _query(c, plan=rnn.RNN_PLAN_CELLWISE)
     assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_CELLWISE
     assert sep == [1] * c.L and plan["launches"] == c.L
-    # a width no persistent kernel is compiled for: AUTO falls back to cellwise, WAVEFRONT is refused
-    odd = W.Config("odd", W.LSTM, L=2, D=1, I=24, H=72, T=5, B=4, dtype=W.BF16, seed=1)
+    # a width beyond every persistent kernel: AUTO falls back to cellwise, WAVEFRONT is refused
+    odd = W.Config("odd", W.LSTM, L=2, D=1, I=24, H=4096, T=5, B=4, dtype=W.BF16, seed=1)
     rc, plan, _ = _query(odd)
     assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_CELLWISE
     assert _query(odd, plan=rnn.RNN_PLAN_WAVEFRONT)[0] == rnn.RNN_EUNSUPPORTED
+    # a width between two compiled ones is padded up to the next: 72 units run as 128 (row blocks count padded units)
+    rc, plan, _ = _query(odd.scaled(H=72))
+    assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert plan["row_blocks"] * plan["row_tiles"] * 4 == 128
 
 
 def test_fewer_compute_units_mean_more_launches():
@@ -98,11 +102,12 @@ def test_widths_covered_by_the_persistent_kernels():
     for H in (1280, 1536, 2048):                            # tag-in-data kernel only: large batches in many passes
         assert kind(H, 1) == rnn.RNN_PLAN_WAVEFRONT and kind(H, 8) == rnn.RNN_PLAN_WAVEFRONT, H
         assert kind(H, 300) == rnn.RNN_PLAN_WAVEFRONT, H
-    for H in (64, 192, 896, 1152):                          # not compiled / not a multiple of 128
-        assert kind(H, 1) == rnn.RNN_PLAN_CELLWISE, H
+    for H in (64, 192, 896, 1152, 1800):                    # padded up to 128, 256, 1024, 1280, 2048 units
+        assert kind(H, 1) == rnn.RNN_PLAN_WAVEFRONT, H
+    assert kind(2056, 1) == rnn.RNN_PLAN_CELLWISE           # beyond the widest compiled
     for H in (32, 64, 128, 256, 512):                       # fp32: multiples of 16 up to 512 units
         assert kind(H, 2, dtype=W.F32) == rnn.RNN_PLAN_WAVEFRONT, H
-    assert kind(48, 2, dtype=W.F32) == rnn.RNN_PLAN_CELLWISE
+    assert kind(48, 2, dtype=W.F32) == rnn.RNN_PLAN_WAVEFRONT   # as 64
     assert kind(1024, 2, dtype=W.F32) == rnn.RNN_PLAN_CELLWISE
 
 
@@ -154,7 +159,8 @@ def test_invariants_over_random_shapes():
             assert any(plan["launches"] % k == 0 and plan["launches"] // k >= 2 and (plan["launches"] // k) * held >= c.B
                        for k in per_pass)
         assert c.D == 1 or lp == 1                      # bidirectional layers cannot share a launch
-        assert plan["row_blocks"] * rt * 4 == c.H       # 16 gate rows = 4 hidden units per tile
+        assert plan["row_blocks"] * rt * 4 >= c.H       # 16 gate rows = 4 hidden units per tile (of the padded width)
+        assert plan["row_blocks"] * rt * 4 <= max(2 * c.H, 128)
         assert plan["col_blocks"] % nch == 0
         # all workgroups of a launch are resident at once: at most one per compute unit
         assert lp * c.D * plan["row_blocks"] * (plan["col_blocks"] // nch) <= cus
