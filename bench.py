@@ -199,6 +199,28 @@ def time_graph_replay(names=("C1", "C2", "C3"), reps: int = 200):
     return out
 
 
+def time_other_widths():
+    """Shapes outside the named workloads that exercise the rest of the plan logic: widths that are not 128 times a
+    power of two, 2048 units, a width that runs padded, a batch that runs in passes.  ms per forward."""
+    from paper_2307_11339_amd import workloads as W
+
+    shapes = {
+        "lstm_4x768_T128_B1": dict(L=4, I=768, H=768, T=128, B=1),
+        "lstm_2x768_T64_B300": dict(L=2, I=768, H=768, T=64, B=300),
+        "lstm_2x2048_T128_B1": dict(L=2, I=2048, H=2048, T=128, B=1),
+        "lstm_2x1536_T128_B8": dict(L=2, I=1536, H=1536, T=128, B=8),
+        "lstm_2x200_T128_B8_padded_to_256": dict(L=2, I=200, H=200, T=128, B=8),
+        "lstm_2x1024_T64_B300_two_passes": dict(L=2, I=1024, H=1024, T=64, B=300),
+        "lstm_2x512_T128_B512": dict(L=2, I=512, H=512, T=128, B=512),
+    }
+    out = {}
+    for i, (name, kw) in enumerate(shapes.items()):
+        c = W.Config(name, W.LSTM, D=1, dtype=W.BF16, seed=W.BASE_SEED + 300 + i, **kw)
+        _, r = time_workload(c, steps=10, warmup=2)
+        out[name] = round(r["ms_per_step"], 4)
+    return out
+
+
 def time_projection_gemm(name: str, reps: int = 10):
     """The batched input projection X W_ih^T of one layer of the workload over all time steps, as a launch of its
     own (rnn_input_projection).  No named workload needs it any more (their input products run inside the
@@ -404,6 +426,7 @@ def main() -> int:
         line["projection_gemm"] = time_projection_gemm(args.workload)
         line["cell_variants"] = time_cell_variants()
         line["graph_replay"] = time_graph_replay()
+        line["other_widths"] = time_other_widths()
 
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)
