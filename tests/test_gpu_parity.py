@@ -126,7 +126,8 @@ SMALL = [
     ("lstm_bf16_sidebyside_h768_l4", 0, 4, 1, 768, 768, 6, 64, 1, True, True),
     # more sequences than one persistent launch holds: passes over blocks of sequences (256 + 44; 16 + 2)
     ("lstm_bf16_inside_passes_b300", 0, 2, 1, 1024, 1024, 5, 300, 1, True, True),
-    ("gru_bf16_passes_h2048_b18", 1, 1, 1, 2048, 2048, 3, 18, 1, True, True),    # odd batch in fp32: padded rows in the blocked state
+    ("gru_bf16_passes_h2048_b18", 1, 1, 1, 2048, 2048, 3, 18, 1, True, True),
+    ("lstm_bf16_padded_h896_inside_passes", 0, 1, 1, 896, 896, 3, 300, 1, True, True),   # padded to 1024 and 256 + 44 sequences    # odd batch in fp32: padded rows in the blocked state
     # Wide layers at a medium batch: several layers share one launch of the flag-vector kernel, the upper
     # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.
     ("lstm_bf16_fusedflag_l4", 0, 4, 1, 64, 1024, 5, 40, 1, True, True),    # 4 layers x 64 workgroups, tiles of 64 sequences
