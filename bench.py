@@ -304,7 +304,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this library runs on one GPU; --gpus %d is not supported "
-                         "(batch sharding across GPUs needs no kernel change, see DESIGN.md)\n" % args.gpus)
+                         "(sequences are independent: splitting the batch across GPUs needs no kernel change)\n" % args.gpus)
         return 2
 
     import torch
