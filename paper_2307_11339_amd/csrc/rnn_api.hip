@@ -135,7 +135,9 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     const int col_tiles = (B + 15) / 16;
     const int lp_max = (m->D == 1) ? (m->L < WF_MAX_LAYERS ? m->L : WF_MAX_LAYERS) : 1;
     // {row tiles, column tiles per chain, chains per workgroup}
-    static const int cand[][3] = {{1, 1, 1}, {2, 1, 1}, {4, 1, 1}, {1, 4, 1}, {4, 2, 2}, {4, 4, 1}};
+    // ({2, 2, 2}: 8 hidden units per workgroup, for layers of more than 1024 units, whose slices of 16 units
+    // no longer fit a workgroup's registers)
+    static const int cand[][3] = {{1, 1, 1}, {2, 1, 1}, {4, 1, 1}, {1, 4, 1}, {4, 2, 2}, {4, 4, 1}, {2, 2, 2}};
     for (int launches = (m->L + lp_max - 1) / lp_max; launches <= m->L; ++launches) {
         const int LP = (m->L + launches - 1) / launches;
         const int budget = m->num_cus / (LP * m->D);
@@ -145,6 +147,7 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
         for (int c = 0; c < (int)(sizeof(cand) / sizeof(cand[0])); ++c) {
             const int RT = cand[c][0], CT = cand[c][1], NCH = cand[c][2];
             if (row_tiles % RT) continue;
+            if (RT == 2 && CT == 2 && m->H <= 1024) continue;
             const bool tagged = (CT == 1 && NCH == 1);  // single tile of 16 sequences: tag-in-data kernel
             // several layers of large tiles side by side: the inside-product kernel when every layer's
             // input is H wide, else the flag-vector kernel with a projection for the first layer

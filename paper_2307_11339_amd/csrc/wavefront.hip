@@ -393,6 +393,7 @@ hipError_t launch_cell_fused(const WavefrontArgs& a, hipStream_t stream) {
     X(TraitsBf16, 4, 2, 4, 2) X(TraitsBf16, 4, 2, 8, 2)                           \
     X(TraitsBf16, 4, 4, 3, 1) X(TraitsBf16, 4, 4, 5, 1) X(TraitsBf16, 4, 4, 6, 1) \
     X(TraitsBf16, 4, 4, 1, 1) X(TraitsBf16, 4, 4, 2, 1) X(TraitsBf16, 4, 2, 1, 2) X(TraitsBf16, 4, 2, 2, 2) \
+    X(TraitsBf16, 2, 2, 10, 2) X(TraitsBf16, 2, 2, 12, 2)                                                      \
     X(TraitsBf16, 4, 2, 3, 2) X(TraitsBf16, 4, 2, 5, 2) X(TraitsBf16, 4, 2, 6, 2) \
     X(TraitsF32, 1, 4, 2, 1) X(TraitsF32, 1, 4, 4, 1) X(TraitsF32, 1, 4, 8, 1)    \
     X(TraitsF32, 1, 4, 16, 1) X(TraitsF32, 1, 4, 32, 1)

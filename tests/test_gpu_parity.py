@@ -127,6 +127,10 @@ SMALL = [
     # more sequences than one persistent launch holds: passes over blocks of sequences (256 + 44; 16 + 2)
     ("lstm_bf16_inside_passes_b300", 0, 2, 1, 1024, 1024, 5, 300, 1, True, True),
     ("gru_bf16_passes_h2048_b18", 1, 1, 1, 2048, 2048, 3, 18, 1, True, True),
+    # more than 1024 units at a large batch: workgroups of 8 units (x inside; a narrower first layer projects)
+    ("lstm_bf16_inside_sq_h2048_b64", 0, 2, 1, 2048, 2048, 3, 64, 1, True, True),
+    ("gru_bf16_inside_h1280_i64_b100", 1, 2, 1, 64, 1280, 4, 100, 1, True, True),     # 64 + 36 sequences
+    ("lstm_bf16_inside_sq_h1536_b50", 0, 1, 1, 1536, 1536, 4, 50, 1, True, False),
     ("lstm_bf16_padded_h896_inside_passes", 0, 1, 1, 896, 896, 3, 300, 1, True, True),   # padded to 1024 and 256 + 44 sequences    # odd batch in fp32: padded rows in the blocked state
     # Wide layers at a medium batch: several layers share one launch of the flag-vector kernel, the upper
     # ones fused (x_t taken from the layer below as it is produced).  Checked on sampled sequences.

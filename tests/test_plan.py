@@ -121,10 +121,20 @@ def test_batches_beyond_one_launch_run_in_passes():
     assert plan["launches"] == 8 * 4 and sep == [0] * 8          # 256 + 256 + 256 + 232 sequences
     rc, whole, _ = _query(c, B=256)
     assert whole["launches"] == 8 and whole["col_blocks"] == 8
-    # 2048 units: 256 workgroups per layer hold one block of 16 sequences
-    wide = W.Config("wide", W.LSTM, L=1, D=1, I=2048, H=2048, T=8, B=40, dtype=W.BF16, seed=1)
+    # 1536 units: 192 workgroups of 8 units hold two chains of 32 sequences
+    wide = W.Config("wide", W.LSTM, L=1, D=1, I=1536, H=1536, T=8, B=40, dtype=W.BF16, seed=1)
     rc, plan, _ = _query(wide)
     assert rc == rnn.RNN_OK and plan["kind"] == rnn.RNN_PLAN_WAVEFRONT
+    assert (plan["row_tiles"], plan["col_tiles"], plan["chains"]) == (2, 2, 2)
+    assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (192, 2, 1)
+    rc, plan, _ = _query(wide.scaled(B=200))
+    assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (192, 2, 4)     # 64 + 64 + 64 + 8 sequences
+    # with 16 sequences or fewer the tag-in-data kernel, one block
+    rc, plan, _ = _query(wide.scaled(B=9))
+    assert (plan["row_tiles"], plan["col_tiles"], plan["chains"], plan["row_blocks"], plan["launches"]) == (2, 1, 1, 192, 1)
+    # 2048 units: no large-batch tile fits the registers; 256 workgroups of the tag-in-data kernel hold 16 sequences
+    rc, plan, _ = _query(wide.scaled(H=2048, I=2048))
+    assert (plan["row_tiles"], plan["col_tiles"], plan["chains"]) == (2, 1, 1)
     assert (plan["row_blocks"], plan["col_blocks"], plan["launches"]) == (256, 1, 3)
     # the cellwise plan is never split
     rc, plan, _ = _query(c, plan=rnn.RNN_PLAN_CELLWISE, B=1000)
