@@ -213,6 +213,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             if (loads_behind == 0) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
             } else {
+                // (counts every memory operation of the wave: a variant of this kernel must not spill
+                // registers to memory, which the build checks)
                 constexpr int NLD = KB * CT;
                 static_assert(NCH == 1 || NLD < 64, "vmcnt has six bits");   // (the counted wait is used with several chains only)
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
