@@ -73,6 +73,7 @@ SMALL = [
     # for the input product): taller tiles, a quarter too large to be requested a step early, fp32
     ("lstm_bf16_8layer_h256", 0, 8, 1, 48, 256, 12, 3, 1, True, True),     # 8 layers x 16 workgroups, 16-row tiles x 4
     ("gru_bf16_2layer_h1024_b12", 1, 2, 1, 40, 1024, 6, 12, 1, True, True),  # x fetched after the barriers (12 x 128 words per wave)
+    ("lstm_bf16_4layer_sq_h1024_b1", 0, 4, 1, 1024, 1024, 7, 1, 1, False, True),   # one load instruction per wave: the lean fetch loop
     ("lstm_bf16_2layer_h1024_b3", 0, 2, 1, 1024, 1024, 5, 3, 1, True, True),  # 3 x 128 words per wave: three instructions, fetched outright
     ("lstm_f32_6layer_h128", 0, 6, 1, 24, 128, 9, 5, 0, True, True),
     ("gru_bf16_4layer_h512_t1", 1, 4, 1, 32, 512, 1, 2, 1, False, True),   # a single step
@@ -195,6 +196,7 @@ def test_small_shapes(gpu, oracle, spec, plan):
 
 # models whose upper layers wait a long time at the start of a launch (the layers below have to get there first)
 @pytest.mark.parametrize("name", ["lstm_bf16_8layer_h256", "lstm_f32_6layer_h128",    # tag-in-data kernel
+                                  "lstm_bf16_4layer_sq_h1024_b1",                      # ... its lean fetch loop
                                   "lstm_bf16_sidebyside_l4",                           # inside-product kernel
                                   "lstm_f32_fusedflag_l6_h32"])                        # flag-vector kernel
 def test_abandoned_wait_is_reported_and_the_model_recovers(gpu, oracle, name):
