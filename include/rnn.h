@@ -23,7 +23,10 @@
  *   - every function returning int returns an rnn_status; nothing throws; on failure outputs
  *     passed by pointer are left untouched;
  *   - a model belongs to the HIP device that was current when it was created, and at most one
- *     rnn_forward may be in flight per model (its workspace and step flags are per model).
+ *     rnn_forward may be in flight per model (its workspace and step flags are per model);
+ *   - the one-time set-up of a kernel variant (its LDS size, how many workgroups fit the GPU) is kept per
+ *     process: calls into the library are made from one thread at a time, and the GPUs of a process are
+ *     of one kind.
  */
 #ifndef RNN_MI355X_H
 #define RNN_MI355X_H
