@@ -74,6 +74,7 @@ SMALL = [
     ("lstm_bf16_8layer_h256", 0, 8, 1, 48, 256, 12, 3, 1, True, True),     # 8 layers x 16 workgroups, 16-row tiles x 4
     ("gru_bf16_2layer_h1024_b12", 1, 2, 1, 40, 1024, 6, 12, 1, True, True),  # x fetched after the barriers (12 x 128 words per wave)
     ("lstm_bf16_4layer_sq_h1024_b1", 0, 4, 1, 1024, 1024, 7, 1, 1, False, True),   # one load instruction per wave: the lean fetch loop
+    ("gru_bf16_3layer_h1024_b6", 1, 3, 1, 1024, 1024, 5, 6, 1, True, True),   # 6 x 128 words per wave: probe word, then the generic fetch of six instructions
     ("lstm_bf16_2layer_h1024_b3", 0, 2, 1, 1024, 1024, 5, 3, 1, True, True),  # 3 x 128 words per wave: three instructions, fetched outright
     ("lstm_f32_6layer_h128", 0, 6, 1, 24, 128, 9, 5, 0, True, True),
     ("gru_bf16_4layer_h512_t1", 1, 4, 1, 32, 512, 1, 2, 1, False, True),   # a single step
