@@ -346,8 +346,10 @@ def test_bounds(oracle):
 
 
 # ---------------------------------------------------------------- P11: brute force, tiny
-def _brute(cell, L, D, I, H, ws, x, lengths, h0, c0):
-    """Whole network with Python floats; time is the outer loop and every product is spelled out."""
+def _brute(cell, L, D, I, H, ws, x, lengths, h0, c0, gru_variant=0):
+    """Whole network with Python floats; time is the outer loop and every product is spelled out.
+    gru_variant 1: the candidate's recurrent product runs over r_k * h_k, with the reset gate of
+    every unit k computed first (each unit's own r multiplies that unit's own previous state)."""
     T, B, _ = x.shape
     G = 4 if cell == LSTM else 3
     cur = [[[float(v) for v in x[t, b]] for b in range(B)] for t in range(T)]
@@ -377,7 +379,19 @@ def _brute(cell, L, D, I, H, ws, x, lengths, h0, c0):
                         a.append(sx)
                         ah.append(sh)
                     hn = [0.0] * H
+                    if cell != LSTM and gru_variant == 1:
+                        # reset gates of all units first, then W_hn (r * h) term by term
+                        r_all = [sig(a[k] + ah[k]) for k in range(H)]
+                        for j in range(H):
+                            sh = float(bh[2 * H + j])
+                            for k in range(H):
+                                sh = sh + float(Wh[2 * H + j, k]) * (r_all[k] * hs[b][k])
+                            z_ = sig(a[H + j] + ah[H + j])
+                            n_ = math.tanh(a[2 * H + j] + sh)
+                            hn[j] = (1 - z_) * n_ + z_ * hs[b][j]
                     for j in range(H):
+                        if cell != LSTM and gru_variant == 1:
+                            break
                         if cell == LSTM:
                             i_ = sig(a[j] + ah[j]); f_ = sig(a[H + j] + ah[H + j])
                             g_ = math.tanh(a[2 * H + j] + ah[2 * H + j]); o_ = sig(a[3 * H + j] + ah[3 * H + j])
@@ -396,17 +410,17 @@ def _brute(cell, L, D, I, H, ws, x, lengths, h0, c0):
     return np.array(cur), np.array([hT[i] for i in range(L * D)]), np.array([cT[i] for i in range(L * D)])
 
 
-@pytest.mark.parametrize("cell", [LSTM, GRU])
-def test_brute_force_tiny(oracle, cell):
+@pytest.mark.parametrize("cell,variant,H", [(LSTM, 0, 2), (GRU, 0, 2), (GRU, 1, 2), (GRU, 1, 3)])
+def test_brute_force_tiny(oracle, cell, variant, H):
     rng = np.random.default_rng(13)
-    L, D, I, H, T, B = 2, 2, 2, 2, 3, 2
+    L, D, I, T, B = 2, 2, 2, 3, 2
     ws = rand_weights(rng, cell, L, D, I, H, scale=1.0)
     x = rng.standard_normal((T, B, I))
     lengths = np.array([3, 2], dtype=np.int32)
     h0 = rng.uniform(-1, 1, (L * D, B, H))
     c0 = rng.uniform(-1, 1, (L * D, B, H))
-    y, hT, cT = oracle.forward(cell, L, D, I, H, ws, x, lengths, h0, c0)
-    yb, hb, cb = _brute(cell, L, D, I, H, ws, x, lengths, h0, c0)
+    y, hT, cT = oracle.forward(cell, L, D, I, H, ws, x, lengths, h0, c0, gru_variant=variant)
+    yb, hb, cb = _brute(cell, L, D, I, H, ws, x, lengths, h0, c0, gru_variant=variant)
     np.testing.assert_allclose(y, yb, rtol=0, atol=1e-13)
     np.testing.assert_allclose(hT, hb, rtol=0, atol=1e-13)
     if cell == LSTM:
@@ -542,6 +556,60 @@ def test_peephole_closed_form_and_identities(oracle):
         assert np.array_equal(got[1][0], ref[1][0])                  # (layer 0, forward) does not
     with pytest.raises(ValueError):
         oracle.forward(GRU, 1, 1, I, H, rand_weights(rng, GRU, 1, 1, I, H), x, peepholes=[np.zeros((3, H))])
+
+
+def test_peephole_input_gate_per_unit(oracle):
+    # f = 0 and o = 1 by bias, W_hh = 0, the i/f/o rows of W_ih zero: every unit j runs the scalar recursion
+    # c_t = sigma(b_i[j] + p_i[j] c_{t-1}) tanh(W_g[j] x_t + b_g[j]),  h_t = tanh(c_t), with g far from zero,
+    # so a p_i taken from another unit (or applied to another unit's c) changes the result
+    rng = np.random.default_rng(35)
+    I, H, T, B = 2, 4, 6, 2
+    x = rng.standard_normal((T, B, I))
+    wi = np.zeros((4 * H, I)); wi[2 * H:3 * H] = rng.uniform(-2, 2, (H, I))
+    bi = np.zeros(4 * H)
+    bi[0:H] = rng.uniform(-1, 1, H); bi[H:2 * H] = -40.0; bi[2 * H:3 * H] = rng.uniform(-1, 1, H); bi[3 * H:] = 40.0
+    p = np.zeros((3, H)); p[0] = [2.5, -1.5, 0.75, -3.0]
+    c0 = rng.uniform(-1, 1, (1, B, H))
+    y, hT, cT = oracle.forward(LSTM, 1, 1, I, H, [wi, np.zeros((4 * H, H)), bi, None], x, c0=c0, peepholes=[p])
+    for b in range(B):
+        for j in range(H):
+            c = float(c0[0, b, j])
+            for t in range(T):
+                g = math.tanh(sum(float(wi[2 * H + j, k]) * float(x[t, b, k]) for k in range(I)) + float(bi[2 * H + j]))
+                c = sig(float(bi[j]) + float(p[0, j]) * c) * g
+                assert abs(y[t, b, j] - math.tanh(c)) < 1e-14
+            assert abs(cT[0, b, j] - c) < 1e-14
+    # the units really differ: with p_i rotated by one unit the result moves
+    q = p.copy(); q[0] = np.roll(p[0], 1)
+    y2, _, _ = oracle.forward(LSTM, 1, 1, I, H, [wi, np.zeros((4 * H, H)), bi, None], x, c0=c0, peepholes=[q])
+    assert np.max(np.abs(y2 - y)) > 1e-3
+
+
+def test_peephole_all_gates_active_matrix_form(oracle):
+    # every term alive, distinct weights per unit, 3 units, two directions: the cell written with
+    # matrix-vector products over all units at once (a different routine from the oracle's scalar dots)
+    rng = np.random.default_rng(36)
+    I, H, T, B, D = 3, 3, 5, 2, 2
+    ws = rand_weights(rng, LSTM, 1, D, I, H, scale=1.0)
+    ps = [rng.uniform(-2, 2, (3, H)) for _ in range(D)]
+    x = rng.standard_normal((T, B, I))
+    h0 = rng.uniform(-1, 1, (D, B, H)); c0 = rng.uniform(-1, 1, (D, B, H))
+    lengths = np.array([5, 3], dtype=np.int32)
+    y, hT, cT = oracle.forward(LSTM, 1, D, I, H, ws, x, lengths, h0, c0, peepholes=ps)
+    s = lambda v: 1.0 / (1.0 + np.exp(-v))
+    for d in range(D):
+        Wi, Wh, bi, bh = ws[4 * d:4 * d + 4]
+        for b in range(B):
+            n = int(lengths[b])
+            h, c = h0[d, b].copy(), c0[d, b].copy()
+            for t in (range(n) if d == 0 else range(n - 1, -1, -1)):
+                a = Wi @ x[t, b] + bi + Wh @ h + bh
+                i_ = s(a[:H] + ps[d][0] * c); f_ = s(a[H:2 * H] + ps[d][1] * c)
+                c = f_ * c + i_ * np.tanh(a[2 * H:3 * H])
+                h = s(a[3 * H:] + ps[d][2] * c) * np.tanh(c)
+                np.testing.assert_allclose(y[t, b, d * H:(d + 1) * H], h, rtol=0, atol=1e-14)
+            np.testing.assert_allclose(hT[d, b], h, rtol=0, atol=1e-14)
+            np.testing.assert_allclose(cT[d, b], c, rtol=0, atol=1e-14)
 
 
 def test_clip_scalar_recursion(oracle):
