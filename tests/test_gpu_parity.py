@@ -716,10 +716,10 @@ def test_C4_sampled_sequences(gpu, oracle, plan):
     _run_named(gpu, oracle, "C4", plan, sample=rows)
 
 
-@pytest.mark.parametrize("index", [0, 3, 9])
+@pytest.mark.parametrize("index", list(range(13)))
 def test_paper_grid_models(gpu, oracle, index):
-    """Models of the paper's own evaluation grid (Table 6: <layers, batch, io size, seq len>, here the
-    baseline <12, 8, 64, 96>, the 16-layer and the io-128 variants), fp32, all layers in one launch."""
+    """Every model of the paper's own evaluation grid (Table 6: <layers, batch, io size, seq len>: the
+    baseline <12, 8, 64, 96> and its twelve one-parameter variants), fp32, all layers in one launch."""
     harness, rnn, W = gpu
     cfg = W.paper_grid()[index]
     wl = W.make_workload(cfg)
@@ -735,5 +735,23 @@ def test_paper_grid_models(gpu, oracle, index):
 
 def test_C5_sampled_sequences(gpu, oracle):
     """Full-size C5 (the throughput workload, in the launch configuration the benchmark times);
-    the oracle recomputes 3 of the 256 sequences through all 8 layers and 512 steps."""
-    _run_named(gpu, oracle, "C5", 0, sample=[0, 131, 255])
+    the oracle recomputes 10 of the 256 sequences through all 8 layers and 512 steps: one in each of
+    the eight 32-sequence chains of the launch, plus the last lane of the first 16-sequence tile, the
+    first lane of the second and the last lane of the last."""
+    _run_named(gpu, oracle, "C5", 0, sample=[0, 15, 16, 36, 72, 109, 145, 182, 218, 255])
+
+
+@pytest.mark.parametrize("name", ["C2", "C4", "C5"])
+def test_one_sequence_through_a_named_model(gpu, oracle, name):
+    """The batch-1 latency shapes the benchmark times: sequence 0 of C2, C4 and C5 run as a batch of its
+    own (C5: 8 layers of 1024 units at batch 1 take two launches of 4 layers), every element compared."""
+    harness, rnn, W = gpu
+    wl = W.make_workload(W.CONFIGS[name]).take_batch([0])
+    _say("\n  one sequence of %s" % name)
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_AUTO)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    ref = oracle.forward_workload(wl, nthreads=16)
+    _check(harness, wl, io, ref)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    model.close()
