@@ -53,7 +53,8 @@ enum rnn_status {
     RNN_EINVAL = 1,       /* NULL where a pointer is required, size <= 0, bad enum value */
     RNN_EUNSUPPORTED = 2, /* shape outside what the kernels support (see rnn_model_create) */
     RNN_ENOMEM = 3,       /* host or device allocation failed */
-    RNN_EDEVICE = 4       /* a HIP call failed, or a previous forward reported a stalled step */
+    RNN_EDEVICE = 4,      /* a HIP call failed, or a previous forward reported a stalled step */
+    RNN_ESCRATCH = 5      /* rnn_forward_static: the shape needs more workspace than the static array holds */
 };
 
 /* How the cell grid is executed.
@@ -186,6 +187,28 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  */
 int rnn_forward(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,
                 const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream);
+
+/*
+ * rnn_forward for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as rnn_forward, but
+ * the call allocates and frees nothing, whatever shape it is given: its workspace (tagged state words, step
+ * flags, inter-layer activations, projection and layout copies: everything rnn_forward keeps in the model's
+ * own workspace) is laid out, per call, in one static device array of RNN_STATIC_SCRATCH_MIB mebibytes that
+ * every GPU the library runs on holds from the first rnn_model_create on it until the process ends.
+ *   - A shape whose plan needs more than that returns RNN_ESCRATCH with nothing enqueued (for example C3 of the
+ *     named workloads needs about 3 MiB, a 2-layer bidirectional model of 512 units on 64 sequences of 256 steps
+ *     about 140 MiB); RNN_EDEVICE if the array's address could not be obtained when the model was created.
+ *   - All models of a device share the array, which keeps what the last call left: the call clears, on
+ *     `stream`, the parts that must start at zero (step flags, tagged words).  Two calls that overlap in time
+ *     on one GPU (different streams or different models) race on it and give undefined results; calls on one
+ *     stream, or otherwise ordered, are fine.  It does not touch the workspace rnn_forward uses, so the two
+ *     entry points may be mixed on one model (still one forward in flight per model).
+ *   - Kernel timing (rnn_model_set_profiling) records only into event pairs that earlier rnn_forward calls
+ *     created; otherwise the call goes untimed.
+ */
+#define RNN_STATIC_SCRATCH_MIB 64
+int rnn_forward_static(rnn_model* model, const void* x, const int32_t* lengths, const float* h0,
+                       const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream);
 
 /*
  * The input projection alone, for all time steps at once (the step that does not depend on the

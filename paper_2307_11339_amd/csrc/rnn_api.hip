@@ -35,6 +35,32 @@ struct Plan {
 
 }  // namespace
 
+// Workspace of rnn_forward_static: callers that cannot allocate device memory run on pieces of this array.
+// Every GPU the library runs on holds its own copy until the process ends.  In host code the array's name
+// is only a handle for hipGetSymbolAddress; the address the kernels get is looked up once per device
+// (static_scratch_of) and kept.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)RNN_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+char* scratch_ptr[MAX_DEVICES];   // per device: address of that device's copy of `scratch`, NULL = not looked up yet
+
+// Address of the current device's copy of the static array (device must be the current HIP device).
+char* static_scratch_of(int device) {
+    if (device < 0 || device >= MAX_DEVICES) return nullptr;
+    if (!scratch_ptr[device]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_ptr[device] = (char*)p;
+    }
+    return scratch_ptr[device];
+}
+}  // namespace
+
 // About three seconds of polling: far beyond any wait of a healthy launch, short enough that a launch
 // whose workgroups are not all resident (which would otherwise never end) drains.
 constexpr unsigned DEFAULT_SPIN_LIMIT = 1u << 22;
@@ -52,21 +78,30 @@ struct rnn_model {
     std::vector<DevBuf> wih, whh, bias;
     size_t weight_bytes = 0;
 
-    DevBuf gx, hseq, flags, status, h_f32, c_f32, h_st, gh, ticks;
-    DevBuf rh_st, gh2;      // reset-before-product GRU (cellwise plan): r * h and the second product
+    DevBuf status;          // one word, raised by a kernel whose wait gave up (rnn_model_check)
     bool gru_reset_before = false;
     float clip = 0.0f;          // clipping threshold of the gate arguments (cellwise plan only), 0 = none
     std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM, cellwise plan only)
     bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
-    DevBuf x_tm, y_tm;          // batch-first callers: time-major copies of x and y
-    DevBuf x_ck, y_ck, st_ck[4];   // a batch run in passes: the pass's x, y, h0, c0, hT, cT
-    DevBuf y_pad, st_pad[4];       // a padded model: y, h0, c0, hT, cT at the padded width
     // cell variants that only the cellwise plan implements
     bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
-    DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
-    DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
+    // Everything a forward pass keeps in device memory besides the weights.
+    struct Workspace {
+        DevBuf gx, hseq, flags, h_f32, c_f32, h_st, gh, ticks;
+        DevBuf rh_st, gh2;      // reset-before-product GRU (cellwise plan): r * h and the second product
+        DevBuf x_tm, y_tm;          // batch-first callers: time-major copies of x and y
+        DevBuf x_ck, y_ck, st_ck[4];   // a batch run in passes: the pass's x, y, h0, c0, hT, cT
+        DevBuf y_pad, st_pad[4];       // a padded model: y, h0, c0, hT, cT at the padded width
+        DevBuf xblk;            // the caller's x in the layout of a state sequence (first layer of width H only)
+        DevBuf lseq;            // tagged state sequences of the tag-in-data kernel (grown on demand)
+        std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
+    };
+    Workspace ws;           // allocated on demand, owned by the model
+    Workspace ws_static;    // rnn_forward_static: the same buffers as pieces of the device's static array, per call
+    // rnn_forward_static: the device's static array and how much of it this call has handed out
+    struct Arena { char* base = nullptr; size_t used = 0; bool on = false; hipStream_t stream = nullptr; } arena;
+    char* scratch = nullptr;   // this device's copy of the static array (NULL: the lookup failed)
     uint32_t epoch = 0;     // tag of the most recent tag-in-data launch
-    std::vector<DevBuf> ybuf;  // L-1 inter-layer activations
     size_t workspace_bytes = 0;
     bool want_ticks = false;
     bool capturing = false;     // the current rnn_forward is being recorded into a stream capture
@@ -103,21 +138,20 @@ void dev_free(DevBuf& b) {
 }
 
 void free_workspace(rnn_model* m) {
-    dev_free(m->gx); dev_free(m->hseq); dev_free(m->flags); dev_free(m->h_f32);
-    dev_free(m->c_f32); dev_free(m->h_st); dev_free(m->gh); dev_free(m->ticks);
-    for (auto& b : m->ybuf) dev_free(b);
-    m->ybuf.clear();
-    dev_free(m->lseq);
-    dev_free(m->xblk);
-    dev_free(m->rh_st);
-    dev_free(m->gh2);
-    dev_free(m->x_tm);
-    dev_free(m->y_tm);
-    dev_free(m->x_ck);
-    dev_free(m->y_ck);
-    dev_free(m->y_pad);
-    for (auto& b : m->st_pad) dev_free(b);
-    for (auto& b : m->st_ck) dev_free(b);
+    dev_free(m->ws.gx); dev_free(m->ws.hseq); dev_free(m->ws.flags); dev_free(m->ws.h_f32);
+    dev_free(m->ws.c_f32); dev_free(m->ws.h_st); dev_free(m->ws.gh); dev_free(m->ws.ticks);
+    for (auto& b : m->ws.ybuf) dev_free(b);
+    dev_free(m->ws.lseq);
+    dev_free(m->ws.xblk);
+    dev_free(m->ws.rh_st);
+    dev_free(m->ws.gh2);
+    dev_free(m->ws.x_tm);
+    dev_free(m->ws.y_tm);
+    dev_free(m->ws.x_ck);
+    dev_free(m->ws.y_ck);
+    dev_free(m->ws.y_pad);
+    for (auto& b : m->ws.st_pad) dev_free(b);
+    for (auto& b : m->ws.st_ck) dev_free(b);
     m->workspace_bytes = 0;
 }
 
@@ -269,6 +303,7 @@ constexpr size_t PROF_MAX_SLOTS = 1 << 14;
 int prof_begin(rnn_model* m, int kind, hipStream_t st) {
     if (!m->profiling || m->capturing || m->prof_used >= PROF_MAX_SLOTS) return -1;
     if (m->prof_used == m->prof.size()) {
+        if (m->arena.on) return -1;   // a call that must not allocate records into existing event pairs only
         rnn_model::ProfSlot s;
         if (hipEventCreate(&s.a) != hipSuccess) { (void)hipGetLastError(); return -1; }
         if (hipEventCreate(&s.b) != hipSuccess) { (void)hipGetLastError(); (void)hipEventDestroy(s.a); return -1; }
@@ -298,46 +333,46 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
                      hipStream_t st) {
     const size_t per = (size_t)B * m->H;
     const size_t state = (size_t)m->L * m->D * per;
-    HIP_TRY(launch_state_init(m->dtype, h0, c0, (float*)m->h_f32.p, (float*)m->c_f32.p,
-                              m->h_st.p, state, st));
+    HIP_TRY(launch_state_init(m->dtype, h0, c0, (float*)m->ws.h_f32.p, (float*)m->ws.c_f32.p,
+                              m->ws.h_st.p, state, st));
     const int N4 = SLOTS * m->H;
     for (int l = 0; l < m->L; ++l) {
-        const void* in = (l == 0) ? x : m->ybuf[l - 1].p;
-        void* out = (l == m->L - 1) ? y : m->ybuf[l].p;
+        const void* in = (l == 0) ? x : m->ws.ybuf[l - 1].p;
+        void* out = (l == m->L - 1) ? y : m->ws.ybuf[l].p;
         const int K = m->layer_input(l);
         const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
-        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l].p, K, (float*)m->gx.p, m->D * N4,
+        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l].p, K, (float*)m->ws.gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
         prof_end(m, ps, st);
         for (int s = 0; s < T; ++s) {
             for (int d = 0; d < m->D; ++d) {
                 const int g = l * m->D + d;
-                float* gh = (float*)m->gh.p + (size_t)d * B * N4;
-                void* hst = (char*)m->h_st.p + (size_t)g * per * m->esize;
+                float* gh = (float*)m->ws.gh.p + (size_t)d * B * N4;
+                void* hst = (char*)m->ws.h_st.p + (size_t)g * per * m->esize;
                 HIP_TRY(launch_gemm_nt(m->dtype, hst, m->H, m->whh[g].p, m->H, gh, N4, B, N4,
                                        m->H, st));
                 CellStepArgs a;
                 a.cell = m->cell; a.dtype = m->dtype;
                 a.B = B; a.H = m->H; a.D = m->D; a.d = d; a.t = d ? (T - 1 - s) : s;
-                a.gx = (const float*)m->gx.p; a.gh = gh; a.bias = (const float*)m->bias[g].p;
-                a.h_f32 = (float*)m->h_f32.p + (size_t)g * per;
-                a.c_f32 = (float*)m->c_f32.p + (size_t)g * per;
+                a.gx = (const float*)m->ws.gx.p; a.gh = gh; a.bias = (const float*)m->bias[g].p;
+                a.h_f32 = (float*)m->ws.h_f32.p + (size_t)g * per;
+                a.c_f32 = (float*)m->ws.c_f32.p + (size_t)g * per;
                 a.h_st = hst; a.out = out; a.lengths = lengths; a.T = T;
                 a.gh_rh = nullptr; a.rh_st = nullptr;
                 a.peep = m->peep.empty() ? nullptr : (const float*)m->peep[g].p;
                 a.clip = m->clip;
                 if (m->gru_reset_before) {  // r, then W_hh (r * h), whose candidate slot replaces gh's
-                    a.rh_st = m->rh_st.p;
+                    a.rh_st = m->ws.rh_st.p;
                     HIP_TRY(launch_gru_reset(a, st));
-                    HIP_TRY(launch_gemm_nt(m->dtype, m->rh_st.p, m->H, m->whh[g].p, m->H, (float*)m->gh2.p, N4, B,
+                    HIP_TRY(launch_gemm_nt(m->dtype, m->ws.rh_st.p, m->H, m->whh[g].p, m->H, (float*)m->ws.gh2.p, N4, B,
                                            N4, m->H, st));
-                    a.gh_rh = (const float*)m->gh2.p;
+                    a.gh_rh = (const float*)m->ws.gh2.p;
                 }
                 HIP_TRY(launch_cell_step(a, st));
             }
         }
     }
-    HIP_TRY(launch_state_export((const float*)m->h_f32.p, (const float*)m->c_f32.p, hT,
+    HIP_TRY(launch_state_export((const float*)m->ws.h_f32.p, (const float*)m->ws.c_f32.p, hT,
                                 m->cell == CELL_LSTM ? cT : nullptr, state, st));
     return RNN_OK;
 }
@@ -347,6 +382,17 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
 // and tagged words: tag 0 is never used by a launch).
 int grow(rnn_model* m, DevBuf& b, size_t bytes, bool zeroed = false) {
     if (b.bytes >= bytes) return RNN_OK;
+    if (m->arena.on) {
+        // rnn_forward_static: the buffer is the next piece of the device's static array (256-byte aligned);
+        // the array keeps what the last call left, so what must start at zero is cleared on the stream
+        const size_t at = (m->arena.used + 255) & ~(size_t)255;
+        if (bytes > STATIC_SCRATCH_BYTES || at > STATIC_SCRATCH_BYTES - bytes) return RNN_ESCRATCH;
+        b.p = m->arena.base + at;
+        b.bytes = bytes;
+        m->arena.used = at + bytes;
+        if (zeroed) HIP_TRY(launch_fill_zero(b.p, (bytes + 3) & ~(size_t)3, m->arena.stream));
+        return RNN_OK;
+    }
     if (m->capturing) return RNN_EUNSUPPORTED;   // no allocation and no waiting inside a stream capture
     HIP_TRY(hipDeviceSynchronize());
     m->workspace_bytes -= b.bytes;
@@ -367,7 +413,7 @@ inline size_t blocked_rows(int B) { return ((size_t)B + 3) & ~(size_t)3; }
 // T + 1 slots of blocked_rows(B) * H elements, so a layer can read the finished sequence of the
 // layer below.
 void* state_region(rnn_model* m, int l0, int T, int B) {
-    return (char*)m->hseq.p + (size_t)l0 * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
+    return (char*)m->ws.hseq.p + (size_t)l0 * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
 }
 
 // One persistent launch: layers [l0, l0 + LP) over all T steps.
@@ -379,13 +425,13 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
                      bool x_from_state = false) {
     const bool tagged = plan.CT == 1 && plan.NCH == 1;
     if (++m->epoch == 0) {  // the tag wrapped: start over from cleared buffers
-        HIP_TRY(launch_fill_zero(m->lseq.p, m->lseq.bytes, st));
-        HIP_TRY(launch_fill_zero(m->flags.p, m->flags.bytes, st));
+        HIP_TRY(launch_fill_zero(m->ws.lseq.p, m->ws.lseq.bytes, st));
+        HIP_TRY(launch_fill_zero(m->ws.flags.p, m->ws.flags.bytes, st));
         m->epoch = 1;
     }
     if (tagged) {
         HIP_TRY(launch_wavefront_ll_init(m->dtype, h0, l0, LP, m->D, T, B, m->H,
-                                         (uint64_t*)m->lseq.p, m->epoch, st));
+                                         (uint64_t*)m->ws.lseq.p, m->epoch, st));
     } else {
         HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, (int)blocked_rows(B), m->H,
                                       state_region(m, l0, T, B), st));
@@ -403,7 +449,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
             a.wih[ll * m->D + d] = m->wih[l].p;  // fused layers have D = 1
             a.bias[ll * m->D + d] = (const float*)m->bias[l * m->D + d].p;
         }
-        char* base = (char*)((l == m->L - 1) ? y : m->ybuf[l].p);
+        char* base = (char*)((l == m->L - 1) ? y : m->ws.ybuf[l].p);
         a.out[ll] = base;
         // a layer whose consumer reads the state sequence instead keeps no separate output
         if (!tagged && (xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
@@ -415,19 +461,19 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         a.xin = (const char*)state_region(m, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
     a.hseq = state_region(m, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
-    a.flagv = (uint64_t*)m->flags.p;
+    a.flagv = (uint64_t*)m->ws.flags.p;
     // the launch must stay inside the buffers the workspace holds (a kernel never checks)
     if (tagged) {
-        if (wavefront_ll_words(m->dtype, LP * m->D, T, B, m->H) * sizeof(uint64_t) > m->lseq.bytes) return RNN_EDEVICE;
+        if (wavefront_ll_words(m->dtype, LP * m->D, T, B, m->H) * sizeof(uint64_t) > m->ws.lseq.bytes) return RNN_EDEVICE;
     } else {
         const size_t flag_words = (size_t)LP * m->D * T * plan.ncb * plan.nrb;
         const size_t state_end = (size_t)(l0 + LP) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
-        if (flag_words * sizeof(uint64_t) > m->flags.bytes || state_end > m->hseq.bytes) return RNN_EDEVICE;
+        if (flag_words * sizeof(uint64_t) > m->ws.flags.bytes || state_end > m->ws.hseq.bytes) return RNN_EDEVICE;
     }
     a.status = (unsigned*)m->status.p;
-    a.ticks = m->want_ticks ? (unsigned long long*)m->ticks.p + (size_t)l0 * m->D * T : nullptr;
+    a.ticks = m->want_ticks ? (unsigned long long*)m->ws.ticks.p + (size_t)l0 * m->D * T : nullptr;
     a.spin_limit = m->spin_limit;
-    a.lseq = (uint64_t*)m->lseq.p;
+    a.lseq = (uint64_t*)m->ws.lseq.p;
     a.epoch = m->epoch;
     const int ps = prof_begin(m, RNN_KERNEL_RECURRENT, st);
     if (tagged) HIP_TRY(launch_wavefront_ll(a, st));
@@ -475,37 +521,37 @@ int prepare_workspace_pass(rnn_model* m, const Plan& plan, int T, int B) {
     const bool wavefront = plan.kind == RNN_PLAN_WAVEFRONT;
     const bool tagged = wavefront && plan.CT == 1 && plan.NCH == 1;
     bool any_projection = !wavefront;
-    if ((int)m->ybuf.size() < m->L - 1) m->ybuf.resize(m->L - 1);
+    if ((int)m->ws.ybuf.size() < m->L - 1) m->ws.ybuf.resize(m->L - 1);
     int rc = RNN_OK;
     for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
         const bool inside = wavefront && input_product_inside(m, plan, l, T);
         if (!inside && (!wavefront || first_of_launch(m, plan, l))) any_projection = true;
         // a layer keeps an output of its own unless its consumer reads its state sequence instead (the
         // inside-product kernel of large batches; the tag-in-data kernel's consumers read plain outputs)
-        if (l + 1 < m->L && (!inside || tagged)) rc = grow(m, m->ybuf[l], rows * m->D * m->H * m->esize);
+        if (l + 1 < m->L && (!inside || tagged)) rc = grow(m, m->ws.ybuf[l], rows * m->D * m->H * m->esize);
     }
-    if (rc == RNN_OK && any_projection) rc = grow(m, m->gx, rows * m->D * m->H * SLOTS * sizeof(float));
+    if (rc == RNN_OK && any_projection) rc = grow(m, m->ws.gx, rows * m->D * m->H * SLOTS * sizeof(float));
     if (rc == RNN_OK && wavefront && !tagged) {
-        rc = grow(m, m->hseq, (size_t)m->L * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize);
+        rc = grow(m, m->ws.hseq, (size_t)m->L * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize);
         // one flag word per (layer, direction, step, chain, row block); a launch of LP layers uses the
         // first LP * D * T * ncb * nrb words
         if (rc == RNN_OK)
-            rc = grow(m, m->flags, (size_t)m->L * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
-        if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->xblk, (size_t)T * blocked_rows(B) * m->H * m->esize);
+            rc = grow(m, m->ws.flags, (size_t)m->L * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
+        if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->ws.xblk, (size_t)T * blocked_rows(B) * m->H * m->esize);
     }
     if (rc == RNN_OK && tagged)
-        rc = grow(m, m->lseq, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H) * sizeof(uint64_t), true);
+        rc = grow(m, m->ws.lseq, wavefront_ll_words(m->dtype, plan.LP * m->D, T, B, m->H) * sizeof(uint64_t), true);
     if (rc == RNN_OK && !wavefront) {
-        rc = grow(m, m->h_f32, state * sizeof(float));
-        if (rc == RNN_OK) rc = grow(m, m->c_f32, state * sizeof(float));
-        if (rc == RNN_OK) rc = grow(m, m->h_st, state * m->esize);
-        if (rc == RNN_OK) rc = grow(m, m->gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
+        rc = grow(m, m->ws.h_f32, state * sizeof(float));
+        if (rc == RNN_OK) rc = grow(m, m->ws.c_f32, state * sizeof(float));
+        if (rc == RNN_OK) rc = grow(m, m->ws.h_st, state * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->ws.gh, (size_t)m->D * B * m->H * SLOTS * sizeof(float));
         if (rc == RNN_OK && m->gru_reset_before) {
-            rc = grow(m, m->rh_st, (size_t)B * m->H * m->esize);
-            if (rc == RNN_OK) rc = grow(m, m->gh2, (size_t)B * m->H * SLOTS * sizeof(float));
+            rc = grow(m, m->ws.rh_st, (size_t)B * m->H * m->esize);
+            if (rc == RNN_OK) rc = grow(m, m->ws.gh2, (size_t)B * m->H * SLOTS * sizeof(float));
         }
     }
-    if (rc == RNN_OK) rc = grow(m, m->ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
+    if (rc == RNN_OK) rc = grow(m, m->ws.ticks, (size_t)m->L * m->D * T * sizeof(unsigned long long));
     return rc;
 }
 
@@ -526,20 +572,20 @@ int prepare_workspace(rnn_model* m, const Plan& plan, int T, int B) {
             if (rc == RNN_OK) rc = prepare_workspace_pass(m, last, T, tail);
         }
         const size_t rows = (size_t)T * plan.chunk;
-        if (rc == RNN_OK) rc = grow(m, m->x_ck, rows * m->I * m->esize);
-        if (rc == RNN_OK) rc = grow(m, m->y_ck, rows * m->D * m->H * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->ws.x_ck, rows * m->I * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->ws.y_ck, rows * m->D * m->H * m->esize);
         for (int i = 0; i < 4 && rc == RNN_OK; ++i)
-            rc = grow(m, m->st_ck[i], (size_t)m->L * m->D * plan.chunk * m->H * sizeof(float));
+            rc = grow(m, m->ws.st_ck[i], (size_t)m->L * m->D * plan.chunk * m->H * sizeof(float));
     }
     if (rc == RNN_OK && m->H != m->Hu) {
-        rc = grow(m, m->y_pad, (size_t)T * B * m->D * m->H * m->esize);
+        rc = grow(m, m->ws.y_pad, (size_t)T * B * m->D * m->H * m->esize);
         for (int i = 0; i < 4 && rc == RNN_OK; ++i)
-            rc = grow(m, m->st_pad[i], (size_t)m->L * m->D * B * m->H * sizeof(float));
+            rc = grow(m, m->ws.st_pad[i], (size_t)m->L * m->D * B * m->H * sizeof(float));
     }
     if (rc == RNN_OK && m->batch_first) {
         const size_t rows = (size_t)T * B;
-        rc = grow(m, m->x_tm, rows * m->I * m->esize);
-        if (rc == RNN_OK) rc = grow(m, m->y_tm, rows * m->D * m->Hu * m->esize);
+        rc = grow(m, m->ws.x_tm, rows * m->I * m->esize);
+        if (rc == RNN_OK) rc = grow(m, m->ws.y_tm, rows * m->D * m->Hu * m->esize);
     }
     return rc;
 }
@@ -582,7 +628,7 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
     for (int l0 = 0, LP = 0; l0 < m->L; l0 += LP) {
         int first;
         launch_of(m, plan, l0, first, LP);
-        const void* in = (l0 == 0) ? x : m->ybuf[l0 - 1].p;
+        const void* in = (l0 == 0) ? x : m->ws.ybuf[l0 - 1].p;
         if (plan.CT == 1 && plan.NCH == 1 && input_product_inside(m, plan, l0, T)) {
             // tag-in-data kernel: the x waves of the launch's first layer read the plain input
             const int rc = launch_recurrent(m, plan, l0, LP, T, B, nullptr, y, lengths, h0, c0, hT, cT, st, in);
@@ -591,18 +637,18 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
         }
         if (input_product_inside(m, plan, l0, T)) {
             // the first layer reads the caller's x, re-laid out; a layer above reads the state sequence below it
-            if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->xblk.p, T, B, (int)blocked_rows(B), m->H, st));
+            if (l0 == 0) HIP_TRY(launch_to_blocked(m->dtype, x, m->ws.xblk.p, T, B, (int)blocked_rows(B), m->H, st));
             const int rc = launch_recurrent(m, plan, l0, LP, T, B, nullptr, y, lengths, h0, c0, hT, cT, st,
-                                            l0 == 0 ? m->xblk.p : nullptr, l0 > 0);
+                                            l0 == 0 ? m->ws.xblk.p : nullptr, l0 > 0);
             if (rc != RNN_OK) return rc;
             continue;
         }
         const int K = m->layer_input(l0);
         const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
-        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->gx.p, m->D * N4,
+        HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l0].p, K, (float*)m->ws.gx.p, m->D * N4,
                                T * B, m->D * N4, K, st));
         prof_end(m, ps, st);
-        const int rc = launch_recurrent(m, plan, l0, LP, T, B, (const float*)m->gx.p, y, lengths, h0,
+        const int rc = launch_recurrent(m, plan, l0, LP, T, B, (const float*)m->ws.gx.p, y, lengths, h0,
                                         c0, hT, cT, st);
         if (rc != RNN_OK) return rc;
     }
@@ -630,22 +676,22 @@ int forward_in_passes(rnn_model* m, const Plan& plan, const void* x, const int32
             const int rc = resolve_plan(m, T, bc, pass, false);
             if (rc != RNN_OK) return rc;
         }
-        HIP_TRY(launch_copy_2d((const char*)x + b0 * xrow, B * xrow, m->x_ck.p, bc * xrow, T, bc * xrow, st));
+        HIP_TRY(launch_copy_2d((const char*)x + b0 * xrow, B * xrow, m->ws.x_ck.p, bc * xrow, T, bc * xrow, st));
         float* h0p = nullptr; float* c0p = nullptr;
         if (h0) {
-            h0p = (float*)m->st_ck[0].p;
+            h0p = (float*)m->ws.st_ck[0].p;
             HIP_TRY(launch_copy_2d((const char*)h0 + b0 * srow, B * srow, h0p, bc * srow, groups, bc * srow, st));
         }
         if (c0) {
-            c0p = (float*)m->st_ck[1].p;
+            c0p = (float*)m->ws.st_ck[1].p;
             HIP_TRY(launch_copy_2d((const char*)c0 + b0 * srow, B * srow, c0p, bc * srow, groups, bc * srow, st));
         }
-        float* hTp = hT ? (float*)m->st_ck[2].p : nullptr;
-        float* cTp = cT ? (float*)m->st_ck[3].p : nullptr;
-        const int rc = forward_one_pass(m, pass, m->x_ck.p, lengths ? lengths + b0 : nullptr, h0p, c0p, m->y_ck.p, hTp,
+        float* hTp = hT ? (float*)m->ws.st_ck[2].p : nullptr;
+        float* cTp = cT ? (float*)m->ws.st_ck[3].p : nullptr;
+        const int rc = forward_one_pass(m, pass, m->ws.x_ck.p, lengths ? lengths + b0 : nullptr, h0p, c0p, m->ws.y_ck.p, hTp,
                                         cTp, T, bc, st);
         if (rc != RNN_OK) return rc;
-        HIP_TRY(launch_copy_2d(m->y_ck.p, bc * yrow, (char*)y + b0 * yrow, B * yrow, T, bc * yrow, st));
+        HIP_TRY(launch_copy_2d(m->ws.y_ck.p, bc * yrow, (char*)y + b0 * yrow, B * yrow, T, bc * yrow, st));
         if (hT) HIP_TRY(launch_copy_2d(hTp, bc * srow, (char*)hT + b0 * srow, B * srow, groups, bc * srow, st));
         if (cT) HIP_TRY(launch_copy_2d(cTp, bc * srow, (char*)cT + b0 * srow, B * srow, groups, bc * srow, st));
     }
@@ -692,6 +738,9 @@ int rnn_model_create_ordered(rnn_model** out, int cell, int num_layers, int inpu
     }
     m->num_cus = prop.multiProcessorCount;
     m->lds_limit = prop.sharedMemPerBlock;
+    m->scratch = static_scratch_of(m->device);   // the model's device is current here
+    m->ws.ybuf.resize(num_layers > 1 ? num_layers - 1 : 0);
+    m->ws_static.ybuf.resize(num_layers > 1 ? num_layers - 1 : 0);
 
     const int H = m->H, D = m->D;
     m->wih.resize(m->L);
@@ -878,11 +927,9 @@ int rnn_model_reserve(rnn_model* m, int T, int B) {
     return prepare_workspace(m, plan, T, B);
 }
 
-int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
-                const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
-    if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
-    if (((uintptr_t)x | (uintptr_t)y) & 15) return RNN_EINVAL;
-    if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
+// rnn_forward and rnn_forward_static: the second with the workspace carved from the device's static array.
+static int forward_entry(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
+                         const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     HIP_TRY(hipStreamIsCapturing(st, &capture));
@@ -897,16 +944,16 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
         // The launches recorded now carry the tags chosen now, and every replay runs them again with
         // the same tags: what the previous replay (or any other forward) left in the flag words and
         // the tagged state words must not be taken for this run's, so a replay starts by clearing them.
-        HIP_TRY(launch_fill_zero(m->flags.p, m->flags.bytes, st));
-        HIP_TRY(launch_fill_zero(m->lseq.p, m->lseq.bytes, st));
+        HIP_TRY(launch_fill_zero(m->ws.flags.p, m->ws.flags.bytes, st));
+        HIP_TRY(launch_fill_zero(m->ws.lseq.p, m->ws.lseq.bytes, st));
     }
     if (m->cell == CELL_GRU) { c0 = nullptr; cT = nullptr; }
     void* y_caller = nullptr;
     if (m->batch_first) {   // the plans work on time-major copies
-        HIP_TRY(launch_swap_outer(x, m->x_tm.p, B, T, (size_t)m->I * m->esize, st));
-        x = m->x_tm.p;
+        HIP_TRY(launch_swap_outer(x, m->ws.x_tm.p, B, T, (size_t)m->I * m->esize, st));
+        x = m->ws.x_tm.p;
         y_caller = y;
-        y = m->y_tm.p;
+        y = m->ws.y_tm.p;
     }
     const bool padded = m->H != m->Hu;
     void* y_plain = y;             // time-major output at the caller's width
@@ -915,19 +962,19 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     const size_t srow_u = (size_t)m->Hu * sizeof(float), srow = (size_t)m->H * sizeof(float);
     const int state_rows = m->L * m->D * B;
     if (padded) {                  // the plans work at the padded width: states in, y and states out
-        y = m->y_pad.p;
+        y = m->ws.y_pad.p;
         if (h0) {
-            HIP_TRY(launch_fill_zero(m->st_pad[0].p, (size_t)state_rows * srow, st));
-            HIP_TRY(launch_copy_2d(h0, srow_u, m->st_pad[0].p, srow, state_rows, srow_u, st));
-            h0 = (const float*)m->st_pad[0].p;
+            HIP_TRY(launch_fill_zero(m->ws.st_pad[0].p, (size_t)state_rows * srow, st));
+            HIP_TRY(launch_copy_2d(h0, srow_u, m->ws.st_pad[0].p, srow, state_rows, srow_u, st));
+            h0 = (const float*)m->ws.st_pad[0].p;
         }
         if (c0) {
-            HIP_TRY(launch_fill_zero(m->st_pad[1].p, (size_t)state_rows * srow, st));
-            HIP_TRY(launch_copy_2d(c0, srow_u, m->st_pad[1].p, srow, state_rows, srow_u, st));
-            c0 = (const float*)m->st_pad[1].p;
+            HIP_TRY(launch_fill_zero(m->ws.st_pad[1].p, (size_t)state_rows * srow, st));
+            HIP_TRY(launch_copy_2d(c0, srow_u, m->ws.st_pad[1].p, srow, state_rows, srow_u, st));
+            c0 = (const float*)m->ws.st_pad[1].p;
         }
-        if (hT) hT = (float*)m->st_pad[2].p;
-        if (cT) cT = (float*)m->st_pad[3].p;
+        if (hT) hT = (float*)m->ws.st_pad[2].p;
+        if (cT) cT = (float*)m->ws.st_pad[3].p;
     }
     rc = plan.chunk > 0 ? forward_in_passes(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st)
                         : forward_one_pass(m, plan, x, lengths, h0, c0, y, hT, cT, T, B, st);
@@ -944,6 +991,40 @@ int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float
     if (m->batch_first)
         HIP_TRY(launch_swap_outer(y_plain, y_caller, T, B, (size_t)m->D * m->Hu * m->esize, st));
     return RNN_OK;
+}
+
+int rnn_forward(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
+                const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
+    if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
+    if (((uintptr_t)x | (uintptr_t)y) & 15) return RNN_EINVAL;
+    if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
+    return forward_entry(m, x, lengths, h0, c0, y, hT, cT, T, B, stream);
+}
+
+int rnn_forward_static(rnn_model* m, const void* x, const int32_t* lengths, const float* h0,
+                       const float* c0, void* y, float* hT, float* cT, int T, int B, void* stream) {
+    if (!m || !x || !y || T < 1 || B < 1) return RNN_EINVAL;
+    if (((uintptr_t)x | (uintptr_t)y) & 15) return RNN_EINVAL;
+    if ((size_t)T * B > ((size_t)1 << 30)) return RNN_EUNSUPPORTED;
+    if (!m->scratch) return RNN_EDEVICE;    // the device's static array could not be looked up at create
+    // For the length of this call the model's workspace is a set of empty buffers that grow() fills with
+    // pieces of the static array; the model's own workspace is put back untouched afterwards.
+    std::swap(m->ws, m->ws_static);
+    for (auto& b : m->ws.ybuf) b = DevBuf();
+    {
+        std::vector<DevBuf> keep;
+        keep.swap(m->ws.ybuf);              // no reallocation: the vector keeps its L-1 entries
+        m->ws = rnn_model::Workspace();
+        m->ws.ybuf.swap(keep);
+    }
+    m->arena.base = m->scratch;
+    m->arena.used = 0;
+    m->arena.stream = (hipStream_t)stream;
+    m->arena.on = true;
+    const int rc = forward_entry(m, x, lengths, h0, c0, y, hT, cT, T, B, stream);
+    m->arena.on = false;
+    std::swap(m->ws, m->ws_static);
+    return rc;
 }
 
 int rnn_input_projection(rnn_model* m, int layer, const void* in, float* gx, int rows,
@@ -985,8 +1066,8 @@ int rnn_model_profile_read(rnn_model* m, int kind, double* total_ms, long long* 
 
 int rnn_model_read_step_ticks(rnn_model* m, uint64_t* ticks, size_t count) {
     if (!m || !ticks) return RNN_EINVAL;
-    if (!m->ticks.p || count * sizeof(uint64_t) > m->ticks.bytes) return RNN_EINVAL;
-    HIP_TRY(hipMemcpy(ticks, m->ticks.p, count * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    if (!m->ws.ticks.p || count * sizeof(uint64_t) > m->ws.ticks.bytes) return RNN_EINVAL;
+    HIP_TRY(hipMemcpy(ticks, m->ws.ticks.p, count * sizeof(uint64_t), hipMemcpyDeviceToHost));
     return RNN_OK;
 }
 
@@ -1062,6 +1143,7 @@ const char* rnn_status_string(int status) {
         case RNN_EUNSUPPORTED: return "unsupported shape or plan";
         case RNN_ENOMEM: return "out of memory";
         case RNN_EDEVICE: return "device error";
+        case RNN_ESCRATCH: return "shape needs more workspace than the static scratch array holds";
         default: return "unknown status";
     }
 }

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "librnn_mi355x.so")
 
 RNN_LSTM, RNN_GRU = 0, 1
 RNN_F32, RNN_BF16 = 0, 1
-RNN_OK, RNN_EINVAL, RNN_EUNSUPPORTED, RNN_ENOMEM, RNN_EDEVICE = 0, 1, 2, 3, 4
+RNN_OK, RNN_EINVAL, RNN_EUNSUPPORTED, RNN_ENOMEM, RNN_EDEVICE, RNN_ESCRATCH = 0, 1, 2, 3, 4, 5
+RNN_STATIC_SCRATCH_MIB = 64
 RNN_PLAN_AUTO, RNN_PLAN_CELLWISE, RNN_PLAN_WAVEFRONT = 0, 1, 2
 RNN_ORDER_IFGO_RZN, RNN_ORDER_ONNX = 0, 1
 RNN_KERNEL_PROJECTION, RNN_KERNEL_RECURRENT = 0, 1
@@ -29,7 +30,7 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
            "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
-           "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first")
+           "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static")
 
 _lib = None
 
@@ -64,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_reserve.argtypes = [vp, ci, ci]
     lib.rnn_forward.restype = ci
     lib.rnn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp]
+    lib.rnn_forward_static.restype = ci
+    lib.rnn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp]
     lib.rnn_input_projection.restype = ci
     lib.rnn_input_projection.argtypes = [vp, ci, vp, vp, ci, vp]
     lib.rnn_model_check.restype = ci
@@ -182,6 +185,13 @@ def rnn_forward(model: int, x, lengths, h0, c0, y, hT, cT, T: int, B: int, strea
     s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
     return load_library().rnn_forward(model, _ptr(x), _ptr(lengths), _ptr(h0), _ptr(c0), _ptr(y),
                                       _ptr(hT), _ptr(cT), T, B, s)
+
+
+def rnn_forward_static(model: int, x, lengths, h0, c0, y, hT, cT, T: int, B: int, stream=None) -> int:
+    """rnn_forward on the static scratch array of the device: allocates nothing (include/rnn.h)."""
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    return load_library().rnn_forward_static(model, _ptr(x), _ptr(lengths), _ptr(h0), _ptr(c0), _ptr(y),
+                                             _ptr(hT), _ptr(cT), T, B, s)
 
 
 def rnn_input_projection(model: int, layer: int, inp, gx, rows: int, stream=None) -> int:
