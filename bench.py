@@ -21,11 +21,44 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
-PEAK_F32_TFLOPS = 157.3        # MI355X fp32 vector
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA (published)
+PEAK_F32_TFLOPS = 157.3        # MI355X fp32 vector (published)
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E (published)
 LDS_BYTES_PER_CLK_CU = 128.0   # LDS read bandwidth used for the per-step bound
-CLOCK_GHZ = 2.4
+CLOCK_GHZ = 2.4                # nominal engine clock; the device's own figure is printed beside it
+MFMA_BF16_FLOP_PER_CLK_SIMD = 1024
 TICK_HZ = 100e6                # device wall clock used by the step ticks
+
+
+def roofline_constants():
+    """The constants every roofline figure of this report uses, beside what the device itself reports."""
+    import torch
+    prop = torch.cuda.get_device_properties(0)
+    cus = prop.multi_processor_count
+    clock_ghz = getattr(prop, "clock_rate", 0) / 1e6 if getattr(prop, "clock_rate", 0) else None
+    derived = cus * 4 * MFMA_BF16_FLOP_PER_CLK_SIMD * (clock_ghz or CLOCK_GHZ) / 1e3
+    return {"device": prop.name, "compute_units": cus, "device_clock_ghz": clock_ghz,
+            "lds_bytes_per_workgroup": getattr(prop, "shared_memory_per_block", None),
+            "peak_bf16_tflops_used": PEAK_BF16_TFLOPS, "peak_f32_tflops_used": PEAK_F32_TFLOPS,
+            "peak_hbm_gbps_used": PEAK_HBM_GBPS,
+            "peak_bf16_tflops_from_device": round(derived, 1),   # CUs x 4 SIMDs x 1024 flop/clk x device clock
+            "lds_bytes_per_clk_cu_used": LDS_BYTES_PER_CLK_CU, "clock_ghz_used": CLOCK_GHZ}
+
+
+def host_description():
+    model = ""
+    try:
+        for ln in open("/proc/cpuinfo"):
+            if ln.startswith("model name"):
+                model = ln.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return {"cpu_model": model, "nproc": os.cpu_count() or 1, "usable_cores": usable}
 
 
 def log(msg: str) -> None:
@@ -51,9 +84,15 @@ def W_paper_grid():
     return W.paper_grid()
 
 
-def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool = False, plan=None, setup=None):
+def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool = False, plan=None, setup=None,
+                  reference=None, kernel_events: bool = True):
     """name: one of the named workloads, or a workloads.Config.  plan: an rnn_plan (default: automatic).
-    setup(model, io, wl): called before the workspace is sized, to set options of the model."""
+    setup(model, io, wl): called before the workspace is sized, to set options of the model.
+    reference: (rows, (y, hT, cT)) from the CPU oracle for some sequences of this workload: the device result of
+    the last warm-up call is compared with it before anything is timed.
+    kernel_events: bracket every kernel of the timed forwards with HIP events on the launch stream (the per-kernel
+    averages of the report); without them the timed loop is the bare calls."""
+    import numpy as np
     import torch
     from paper_2307_11339_amd import harness, rnn, workloads as W
 
@@ -68,13 +107,27 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
     assert rnn.rnn_model_reserve(model.handle, cfg.T, cfg.B) == rnn.RNN_OK
     log("[bench] %s: inputs generated and uploaded in %.1f s" % (name, time.time() - t0))
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
+    for _ in range(max(warmup, 1 if reference is not None else 0)):
         harness.forward(model, io, stream)
     torch.cuda.synchronize()
     assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
 
-    # timed region: exactly `steps` forwards, kernel events on the launch stream
-    rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_KERNELS)
+    parity = None
+    if reference is not None:   # same inputs, same launch configuration as the timed calls, before they run
+        rows, (ry, rh, rc) = reference
+        y, hT, cT, ybits = harness.results(io)
+        err = max(float(np.abs(y[:, rows] - ry).max()), float(np.abs(hT[:, rows] - rh).max()),
+                  float(np.abs(cT[:, rows] - rc).max()) if rc is not None else 0.0)
+        lengths = wl.lengths if wl.lengths is not None else np.full(cfg.B, cfg.T)
+        padded_ok = all(bool(np.all(ybits[int(lengths[b]):, b] == 0)) for b in range(cfg.B))
+        tol = 2e-2 if cfg.dtype == 1 else 1e-4
+        parity = {"max_abs_err": err, "tolerance": tol, "ok": bool(err <= tol and padded_ok),
+                  "padded_positions_all_zero_bits": padded_ok, "sequences_compared": [int(r) for r in rows],
+                  "against": "CPU oracle (fp64), y / hT / cT of those sequences, all layers and steps"}
+        log("[bench] %s: parity vs oracle on %d sequences: max-abs %.3e (tolerance %.0e)" % (name, len(rows), err, tol))
+
+    # timed region: exactly `steps` forwards; kernel events on the launch stream
+    rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_KERNELS if kernel_events else 0)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(steps):
@@ -96,19 +149,22 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
         # per layer: 1 = the input product is a projection launch, 0 = it runs inside the recurrent kernel
         "projection_launched": [rnn.rnn_model_input_product_placement(model.handle, cfg.T, cfg.B, l)[1]
                                 for l in range(cfg.L)],
+        "parity": parity,
     }
-    if per_call > 0:  # per-call latency distribution, each call waited for
-        lat = []
-        for _ in range(per_call):
-            a = time.perf_counter()
+    if per_call > 0:
+        # per-call latency: every call bracketed by two events on the launch stream, calls back to back,
+        # no kernel events inside, one wait at the end
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(per_call)]
+        for a, b in ev:
+            a.record(stream)
             harness.forward(model, io, stream)
-            torch.cuda.synchronize()
-            lat.append((time.perf_counter() - a) * 1e3)
-        lat.sort()
+            b.record(stream)
+        torch.cuda.synchronize()
+        lat = sorted(a.elapsed_time(b) for a, b in ev)
         out["p50_ms"] = statistics.median(lat)
         out["p90_ms"] = lat[int(0.9 * (len(lat) - 1))]
+        out["calls_timed"] = per_call
     if ticks:
-        import numpy as np
         rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_STEP_TICKS)
         harness.forward(model, io, stream)
         torch.cuda.synchronize()
@@ -256,23 +312,44 @@ def time_projection_gemm(name: str, reps: int = 10):
 
 
 def cpu_baseline(name: str, n_seq: int):
-    """The oracle as it stands, timed on the host cores for a bounded sample of the workload."""
+    """The oracle as it stands, timed on the host cores for a bounded sample of the workload.  Returns the report
+    entry and (rows, (y, hT, cT)), the oracle's results for those sequences, for the parity check of the same run."""
     import numpy as np
     from oracle import rnn_oracle
     from paper_2307_11339_amd import workloads as W
 
     cfg = W.CONFIGS[name]
     wl = W.make_workload(cfg)
-    rows = np.linspace(0, cfg.B - 1, num=min(n_seq, cfg.B)).astype(int)
+    # one sequence in each block of B / n_seq consecutive sequences (for C5: one per 32-sequence chain of the launch)
+    rows = np.unique(np.round(np.linspace(0, cfg.B - 1, num=min(n_seq, cfg.B))).astype(int))
     sub = wl.take_batch(rows)
-    threads = min(16, os.cpu_count() or 1)
+    host = host_description()
+    threads = max(1, min(16, host["usable_cores"]))
     rnn_oracle.build()
     t0 = time.perf_counter()
-    rnn_oracle.forward_workload(sub, nthreads=threads)
+    ref = rnn_oracle.forward_workload(sub, nthreads=threads)
     dt = time.perf_counter() - t0
-    return {"value": len(rows) / dt, "unit": "sequences/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of the %d sequences of %s through all %d layers and %d steps, fp64, %.1f s"
-                      % (len(rows), cfg.B, name, cfg.L, cfg.T, dt)}
+    # the same code on one thread, on one sequence cut to a few steps when the whole one would take too long
+    steps1 = cfg.T
+    per_step_flops = sum(2.0 * cfg.G * cfg.H * (cfg.layer_input(l) + cfg.H) * cfg.D for l in range(cfg.L))
+    while steps1 > 8 and steps1 * per_step_flops > 12e9:     # about 10 s of scalar fp64
+        steps1 //= 2
+    one = wl.take_batch(rows[:1])
+    one.x = np.ascontiguousarray(one.x[:steps1])
+    one.cfg = one.cfg.scaled(T=steps1)
+    if one.lengths is not None:
+        one.lengths = np.minimum(one.lengths, steps1).astype(np.int32)
+    t1 = time.perf_counter()
+    rnn_oracle.forward_workload(one, nthreads=1)
+    dt1 = time.perf_counter() - t1
+    entry = {"value": len(rows) / dt, "unit": "sequences/s", "cores": threads, "kind": "oracle",
+             "sample": "%d of the %d sequences of %s through all %d layers and %d steps, fp64, %.1f s"
+                       % (len(rows), cfg.B, name, cfg.L, cfg.T, dt),
+             "single_thread": {"value": (steps1 / cfg.T) / dt1 if dt1 > 0 else None, "unit": "sequences/s", "cores": 1,
+                               "sample": "1 sequence, all %d layers, %d of its %d steps, %.1f s (scaled to whole sequences)"
+                                         % (cfg.L, steps1, cfg.T, dt1)},
+             "host": host}
+    return entry, (rows, ref)
 
 
 def recorded_traffic(workload: str, kernel_class: str):
@@ -327,7 +404,12 @@ def main() -> int:
         print(json.dumps({"copy_calibration_bytes": n, "copies": 5}))
         return 0
 
-    cfg, main_res = time_workload(args.workload, args.steps, args.warmup)
+    # The oracle goes first: its results for a sample of the sequences are both the CPU baseline (timed) and the
+    # reference the device result is compared with before anything is timed.
+    cpu_entry, reference = (None, None) if args.no_cpu else cpu_baseline(args.workload, n_seq=8)
+    cfg, main_res = time_workload(args.workload, args.steps, args.warmup, reference=reference)
+    if main_res["parity"] is not None and not main_res["parity"]["ok"]:
+        log("[bench] PARITY FAILED: %r" % (main_res["parity"],))
     proj_flops, rec_flops = algorithmic_flops(cfg)
     # dominant kernel = the class with the larger share of the step
     proj_total = main_res["projection"]["avg_ms"] * main_res["projection"]["launches_per_step"]
@@ -347,9 +429,25 @@ def main() -> int:
     rec_tf = tflops(sum(rec_flops) + proj_in, main_res["recurrent"])
     dominant = "recurrent" if rec_total >= proj_total else "projection"
     ach = rec_tf if dominant == "recurrent" else proj_tf
+    traffic = recorded_traffic(cfg.name, dominant)
     roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(ach / peak, 4), "traffic": recorded_traffic(cfg.name, dominant), "kernel": dominant,
+                "frac": round(ach / peak, 4), "traffic": traffic, "kernel": dominant,
                 "avg_ms": round(main_res[dominant]["avg_ms"], 4)}
+    # streamed activations of the dominant kernel: HBM bytes per launch (counters, when on record for this kernel
+    # source) and algorithmic bytes per launch (x or state in, state out, output, weights once), over its duration
+    if dominant == "recurrent" and main_res["recurrent"]["avg_ms"] > 0:
+        n_launch = max(main_res["recurrent"]["launches_per_step"], 1.0)
+        es = 2 if bf16 else 4
+        rows = cfg.T * cfg.B
+        # per layer: its input read, its state sequence written and read back by the next step's products
+        alg = (sum(rows * cfg.layer_input(l) * es + 2 * rows * cfg.D * cfg.H * es for l in range(cfg.L)) +
+               rows * cfg.D * cfg.H * es +
+               sum(cfg.D * cfg.G * cfg.H * (cfg.layer_input(l) + cfg.H) * es for l in range(cfg.L))) / n_launch
+        sec = main_res["recurrent"]["avg_ms"] * 1e-3
+        roofline["hbm"] = {"algorithmic_bytes_per_launch": int(alg), "algorithmic_gbps": round(alg / sec / 1e9, 1),
+                           "measured_gbps": round(traffic / sec / 1e9, 1) if traffic else None,
+                           "peak_gbps": PEAK_HBM_GBPS,
+                           "frac_of_peak": round((traffic or alg) / sec / 1e9 / PEAK_HBM_GBPS, 4)}
 
     line = {
         "metric": "RNN forward sequences/sec",
@@ -378,6 +476,8 @@ def main() -> int:
         },
         "device_bytes": main_res["device_bytes"],
         "input_product_in_recurrent_kernel": [l for l, sep in enumerate(placed) if sep != 1],
+        "parity": main_res["parity"],
+        "roofline_constants": roofline_constants(),
     }
 
     if not args.no_extra:
@@ -385,9 +485,9 @@ def main() -> int:
         for name in ("C1", "C2", "C3", "C4"):
             if name == args.workload:
                 continue
-            c, r = time_workload(name, steps=50, warmup=5, per_call=50, ticks=True)
+            c, r = time_workload(name, steps=100, warmup=10, per_call=100, ticks=True)
             e = {"seq_per_s": round(r["seq_per_s"], 1), "ms_per_call": round(r["ms_per_step"], 4),
-                 "p50_ms": round(r["p50_ms"], 4), "p90_ms": round(r["p90_ms"], 4),
+                 "p50_ms": round(r["p50_ms"], 4), "p90_ms": round(r["p90_ms"], 4), "calls_timed": r["calls_timed"],
                  "recurrent_avg_ms": round(r["recurrent"]["avg_ms"], 4),
                  "projection_avg_ms": round(r["projection"]["avg_ms"], 4)}
             if "step_us_p50" in r:
@@ -407,7 +507,7 @@ def main() -> int:
         b1 = {}
         for name in ("C2", "C4", "C5"):
             c1 = W_config(name).scaled(name=name + "/batch1", B=1)
-            _, r = time_workload(c1, steps=20, warmup=3, per_call=30)
+            _, r = time_workload(c1, steps=20, warmup=10, per_call=100)
             b1[name] = {"p50_ms": round(r["p50_ms"], 4), "p90_ms": round(r["p90_ms"], 4),
                         "ms_per_call": round(r["ms_per_step"], 4)}
         line["batch1_latency"] = b1
@@ -416,7 +516,7 @@ def main() -> int:
         # the paper's own model grid (Table 6): <layers, batch, io size, seq len>, fp32 LSTM
         grid = {}
         for c in W_paper_grid():
-            _, r = time_workload(c, steps=30, warmup=3, per_call=30)
+            _, r = time_workload(c, steps=30, warmup=10, per_call=100)
             # latency and device memory (weights + workspace), the two quantities of the paper's Table 6
             grid[c.name] = {"p50_ms": round(r["p50_ms"], 4), "ms_per_call": round(r["ms_per_step"], 4),
                             "device_mb": round(r["device_bytes"] / 1e6, 3)}
@@ -428,8 +528,8 @@ def main() -> int:
         line["graph_replay"] = time_graph_replay()
         line["other_widths"] = time_other_widths()
 
-    if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(args.workload, n_seq=8)
+    if cpu_entry is not None:
+        line["cpu_baseline"] = cpu_entry
 
     print(json.dumps(line))
     sys.stdout.flush()

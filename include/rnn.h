@@ -3,9 +3,9 @@
  *
  * The operation.  A stacked recurrent network is unrolled over layers and time steps into a
  * grid of cell operators A_t^l; cell (l, t) may run as soon as cell (l, t-1) and cell (l-1, t)
- * have finished, so cells on one anti-diagonal are independent (paper: Section 1, "parallelism
- * after unfolding along the number of layers and the sequence length"; Section 2.2, figure of
- * the folded and unfolded RNN).  Where the paper runs independent cells on CPU cores next to a
+ * have finished, so cells on one anti-diagonal are independent (paper: Section 1, where the
+ * unrolled network is said to be parallel across layers and across time steps; Section 2.2,
+ * figure of the folded and unfolded RNN).  Where the paper runs independent cells on CPU cores next to a
  * GPU that executes cells one by one, this library runs the whole grid inside one persistent
  * GPU kernel whose workgroups are split into one group per (layer, direction).
  *
@@ -24,6 +24,16 @@
  *     passed by pointer are left untouched;
  *   - a model belongs to the HIP device that was current when it was created, and at most one
  *     rnn_forward may be in flight per model (its workspace and step flags are per model);
+ *   - what may run beside a forward pass.  The persistent kernels (RNN_PLAN_WAVEFRONT) size their grid for a GPU
+ *     that is otherwise idle: every workgroup of a launch has to be resident at the same time, because workgroups
+ *     wait for one another's steps.  Other kernels on other streams of the same GPU (another model's forward pass,
+ *     the caller's own kernels, another process) can take compute units away and leave part of a launch
+ *     unscheduled until they finish; the launch then makes no progress meanwhile.  It cannot hang for good: every
+ *     wait inside the kernels is bounded (rnn_model_set_spin_limit), a launch whose waits run out drains, its
+ *     outputs are undefined and rnn_model_check reports RNN_EDEVICE.  So: run forward passes of different models
+ *     one after another (one stream, or ordered streams) when latency matters, and call rnn_model_check where a
+ *     stall must be noticed.  Copies (hipMemcpyAsync) and kernels of the cellwise plan beside a forward pass are
+ *     harmless;
  *   - the one-time set-up of a kernel variant (its LDS size, how many workgroups fit the GPU) is kept per
  *     process: calls into the library are made from one thread at a time, and the GPUs of a process are
  *     of one kind.
@@ -150,6 +160,12 @@ int rnn_model_set_peepholes(rnn_model* model, const float* const* peepholes, int
  * time-major, as described at rnn_forward.  rnn_input_projection is not affected. */
 int rnn_model_set_batch_first(rnn_model* model, int on);
 
+/* Debug validation of the inputs of rnn_forward / rnn_forward_static.  on = 1: every call first copies `lengths`
+ * to the host (waiting for `stream`) and returns RNN_EINVAL, with nothing enqueued, unless 1 <= lengths[b] <= T
+ * for every sequence; such a call cannot be recorded into a HIP graph (RNN_EUNSUPPORTED while the stream is
+ * capturing).  on = 0 (the default): no check on the host, out-of-range values are clamped on the device. */
+int rnn_model_set_validation(rnn_model* model, int on);
+
 /* Size the workspace now for forwards of T steps and B sequences under the current plan, so that
  * later rnn_forward calls of that shape allocate nothing.  Only what the plan chosen for (T, B)
  * touches is allocated (the paper's memory model, Section 3, Equation 4, counts exactly such
@@ -163,7 +179,9 @@ int rnn_model_reserve(rnn_model* model, int T, int B);
  * All tensors are contiguous, time-major DEVICE pointers owned by the caller:
  *   x        [T, B, I]      dtype     input
  *   lengths  [B]            int32     valid steps per sequence, 1 <= lengths[b] <= T; NULL = all T.
- *                                      Values outside the range are clamped to [0, T] on the device.
+ *                                      Values outside the range are clamped to [0, T] on the device (a sequence
+ *                                      of length 0 keeps its initial state and gets +0.0 everywhere); with
+ *                                      rnn_model_set_validation(model, 1) they are RNN_EINVAL instead.
  *   h0, c0   [L*D, B, H]    fp32      initial state, row l*D+d; NULL = zeros; c0 unused for GRU
  *   y        [T, B, D*H]    dtype     output of the last layer; positions t >= lengths[b] receive
  *                                      +0.0 (all-zero bits)
@@ -229,7 +247,7 @@ enum rnn_profile_flags { RNN_PROFILE_KERNELS = 1, RNN_PROFILE_STEP_TICKS = 2 };
 
 /* Measurement aids for the two kernels that dominate the forward pass (projection over all
  * time steps; persistent recurrent kernel), the quantities the paper's profiler collects per
- * operator (Section 4.1, "profile the model to get the operator execution time").
+ * operator (Section 4.1: the model is profiled first, to obtain every operator's run time).
  *   flags & RNN_PROFILE_KERNELS     later forwards bracket every projection and every persistent
  *                                   launch with HIP events on the caller's stream;
  *   flags & RNN_PROFILE_STEP_TICKS  the persistent kernel stores the device wall clock (100 MHz)
@@ -262,6 +280,13 @@ int rnn_model_check(rnn_model* model);
  * of several layers give up, because an upper layer waits at the start of a launch for the layers below
  * it to get going; tests of the give-up path use that. */
 int rnn_model_set_spin_limit(rnn_model* model, unsigned polls);
+
+/* Test aid.  Every persistent launch stamps its step flags and tagged state words with a 32-bit tag, one more
+ * than the launch before; after 2^32 launches of a model the tag wraps, and the launch that wraps first clears
+ * those buffers (tag 0 means "never written").  This call sets the tag of the most recent launch to `tag`, so a
+ * test reaches the wrap with the next launches instead of after 2^32; it waits for the device and clears the
+ * flag and tagged-word buffers of the model's own workspace, so no earlier launch's tags can be met again. */
+int rnn_model_set_launch_tag(rnn_model* model, uint32_t tag);
 
 /* Where the input product W_ih x_t of `layer` is computed for a forward pass of T steps and B
  * sequences under the current plan: *separate_launch = 1 when it is a projection launch of its own

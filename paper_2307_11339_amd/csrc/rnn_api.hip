@@ -83,6 +83,7 @@ struct rnn_model {
     float clip = 0.0f;          // clipping threshold of the gate arguments (cellwise plan only), 0 = none
     std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM, cellwise plan only)
     bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
+    bool validate = false;      // check `lengths` on the host before every forward
     // cell variants that only the cellwise plan implements
     bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
     // Everything a forward pass keeps in device memory besides the weights.
@@ -919,6 +920,12 @@ int rnn_model_set_batch_first(rnn_model* m, int on) {
     return RNN_OK;
 }
 
+int rnn_model_set_validation(rnn_model* m, int on) {
+    if (!m || (on != 0 && on != 1)) return RNN_EINVAL;
+    m->validate = on != 0;
+    return RNN_OK;
+}
+
 int rnn_model_reserve(rnn_model* m, int T, int B) {
     if (!m || T < 1 || B < 1) return RNN_EINVAL;
     Plan plan;
@@ -935,6 +942,14 @@ static int forward_entry(rnn_model* m, const void* x, const int32_t* lengths, co
     HIP_TRY(hipStreamIsCapturing(st, &capture));
     m->capturing = capture != hipStreamCaptureStatusNone;
     struct Done { rnn_model* m; ~Done() { m->capturing = false; } } done{m};
+    if (m->validate && lengths) {
+        if (m->capturing) return RNN_EUNSUPPORTED;
+        std::vector<int32_t> host((size_t)B);
+        HIP_TRY(hipMemcpyAsync(host.data(), lengths, (size_t)B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        for (int b = 0; b < B; ++b)
+            if (host[b] < 1 || host[b] > T) return RNN_EINVAL;
+    }
     Plan plan;
     int rc = resolve_plan(m, T, B, plan);
     if (rc != RNN_OK) return rc;
@@ -1084,6 +1099,16 @@ int rnn_model_check(rnn_model* m) {
 int rnn_model_set_spin_limit(rnn_model* m, unsigned polls) {
     if (!m) return RNN_EINVAL;
     m->spin_limit = polls == 0 ? DEFAULT_SPIN_LIMIT : polls;
+    return RNN_OK;
+}
+
+int rnn_model_set_launch_tag(rnn_model* m, uint32_t tag) {
+    if (!m) return RNN_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    if (m->ws.lseq.p) HIP_TRY(hipMemset(m->ws.lseq.p, 0, m->ws.lseq.bytes));
+    if (m->ws.flags.p) HIP_TRY(hipMemset(m->ws.flags.p, 0, m->ws.flags.bytes));
+    HIP_TRY(hipDeviceSynchronize());
+    m->epoch = tag;
     return RNN_OK;
 }
 

@@ -19,9 +19,9 @@
 //     fragments were requested during the previous chain step) while the flags it will need
 //     become visible, then the recurrent part;
 //   - one wave writes a chain step to memory, from LDS, in whole cache lines, and is the only
-//     one that needs a store acknowledged; it checks for the acknowledgement with a counted wait
-//     (loads requested behind the stores stay in flight) early in the next chain step and stores
-//     the flag word there;
+//     one that needs a store acknowledged; it waits for the acknowledgement early in the next
+//     chain step (the stores are then its only memory operations in flight: the state fragments
+//     of the next chain step were requested before the gates) and stores the flag word there;
 //   - a launch may hold several such layers side by side (template flag MULTI): a layer above the
 //     first of the launch takes the state sequence of the group below as its x, as it is produced,
 //     behind that group's flag vectors.
@@ -208,17 +208,12 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     // reserved until the load has returned: the empty asm that "uses" it sits behind a wait that
     // has covered the load anyway, so that it never causes a wait of its own.
     uint32_t pf = 0;
-    auto store_pending_flag = [&](int loads_behind) {
+    auto store_pending_flag = [&]() {
         if (pend_flag != nullptr) {
-            if (loads_behind == 0) {
-                __builtin_amdgcn_s_waitcnt(0x0F70);
-            } else {
-                // (counts every memory operation of the wave: a variant of this kernel must not spill
-                // registers to memory, which the build checks)
-                constexpr int NLD = KB * CT;
-                static_assert(NCH == 1 || NLD < 64, "vmcnt has six bits");   // (the counted wait is used with several chains only)
-                __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
-            }
+            // every memory operation of this wave has completed, the stores of the chain step among them
+            // (no counting: whatever else the wave has in flight, a spilled register included, is waited
+            // for as well and was issued long before the stores)
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             asm volatile("" ::: "memory");
             asm volatile("" ::"v"(pf));
             if (lane == 0) {
@@ -260,7 +255,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                     if (kb < KBL) acc[rt][ct] = TR::mfma(abuf[kb & 1][rt], xbuf[kb][ct], acc[rt][ct]);
                     else TR::mfma_acc_a(wxr[rt][kb - KBL], xbuf[kb][ct], acc[rt][ct]);   // the recurrent part follows: no wait here
                 }
-            if (NCH > 1 && kb == KB / 8 && w == 0) store_pending_flag(1);
+            if (NCH > 1 && kb == KB / 8 && w == 0) store_pending_flag();
             // (a layer above the first of the launch) the flag word of the group below for the x fragments
             // that the recurrent part is about to request
             if (MULTI && kb == KB / 2 && xflag != nullptr) seenx = ld_dev_u64(xflag);
@@ -354,6 +349,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 if (sn > 0 && sn < T && !__all((uint32_t)(seen >> 32) == epoch)) poll_h(cn, sn);
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // loads of the state stay below the flag check
                 if (w == 0 && !xfused) pf = touch_x((c + 2) % NCH, s + (c + 2) / NCH);   // (never lines that are still being written)
+                // The state of the next chain step (its flags have just been seen) is requested now: its
+                // registers are free since the last matrix instruction, and the fragments travel while the
+                // partial sums are exchanged and the gates run.
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) load_h(cn, sn, kb);
+                __builtin_amdgcn_sched_barrier(0);
             } else {
                 // One chain: the state is requested as late as possible, after the input part.
                 uint64_t unused_x = 0;
@@ -443,14 +445,8 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             }
             asm volatile("" ::: "memory");
             if (NCH > 1) {
-                // The state of the next chain step (its flags have been seen) is requested behind the
-                // stores.  Memory operations complete in order, so once only these KB * CT loads are
-                // outstanding every store has been acknowledged; wave 0 checks that early in the input
-                // part of the next chain step, where it hardly has to wait any more, and stores the
-                // flag word there.
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb) load_h(cn, sn, kb);
+                // Wave 0 waits for the acknowledgement of these stores early in the input part of the
+                // next chain step, where it hardly has to wait any more, and stores the flag word there.
                 pend_flag = my_flags + (size_t)s * flag_step + (size_t)c * p.nrb + rb;
                 pend_step = s;
                 pend_chain = c;
@@ -466,7 +462,7 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
             if (NCH == 1) asm volatile("" ::"v"(pf));
         }
     }
-    if (NCH > 1 && w == 0) store_pending_flag(0);
+    if (NCH > 1 && w == 0) store_pending_flag();
 
 #pragma unroll
     for (int c = 0; c < NCH; ++c)

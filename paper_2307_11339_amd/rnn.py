@@ -30,7 +30,8 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_status_string", "rnn_model_set_profiling", "rnn_model_profile_read",
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
            "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
-           "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static")
+           "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static",
+           "rnn_model_set_validation", "rnn_model_set_launch_tag")
 
 _lib = None
 
@@ -75,6 +76,10 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_set_clip.argtypes = [vp, ctypes.c_float]
     lib.rnn_model_set_peepholes.restype = ci
     lib.rnn_model_set_peepholes.argtypes = [vp, ctypes.POINTER(vp), ci]
+    lib.rnn_model_set_validation.restype = ci
+    lib.rnn_model_set_validation.argtypes = [vp, ci]
+    lib.rnn_model_set_launch_tag.restype = ci
+    lib.rnn_model_set_launch_tag.argtypes = [vp, ctypes.c_uint32]
     lib.rnn_model_set_batch_first.restype = ci
     lib.rnn_model_set_batch_first.argtypes = [vp, ci]
     lib.rnn_model_set_spin_limit.restype = ci
@@ -173,6 +178,14 @@ def rnn_model_set_peepholes(model: int, peepholes: Optional[Sequence], on_device
 
 def rnn_model_set_batch_first(model: int, on: int) -> int:
     return load_library().rnn_model_set_batch_first(model, on)
+
+
+def rnn_model_set_validation(model: int, on: int) -> int:
+    return load_library().rnn_model_set_validation(model, on)
+
+
+def rnn_model_set_launch_tag(model: int, tag: int) -> int:
+    return load_library().rnn_model_set_launch_tag(model, tag)
 
 
 def rnn_model_reserve(model: int, T: int, B: int) -> int:

@@ -314,6 +314,68 @@ def test_error_codes(gpu):
     model.close()
 
 
+def test_length_validation(gpu):
+    """Out-of-range lengths: clamped on the device by default, RNN_EINVAL under rnn_model_set_validation."""
+    import torch
+    harness, rnn, W = gpu
+    wl = _small_workload(W, SMALL[0])
+    model = harness.DeviceModel(wl)
+    io = harness.DeviceIO(wl)
+    c = wl.cfg
+    good = io.lengths.clone()
+    st = torch.cuda.current_stream()
+
+    def call(lengths):
+        return rnn.rnn_forward(model.handle, io.x, lengths, io.h0, io.c0, io.y, io.hT, io.cT, c.T, c.B, st)
+
+    assert call(good) == rnn.RNN_OK
+    torch.cuda.synchronize()
+    ref = io.y.clone()
+    assert rnn.rnn_model_set_validation(model.handle, 2) == rnn.RNN_EINVAL
+    assert rnn.rnn_model_set_validation(model.handle, 1) == rnn.RNN_OK
+    assert call(good) == rnn.RNN_OK
+    for bad_value in (0, -3, c.T + 1):
+        bad = good.clone()
+        bad[1] = bad_value
+        io.y.fill_(7.0)
+        assert call(bad) == rnn.RNN_EINVAL
+        torch.cuda.synchronize()
+        assert float(io.y.float().min()) == 7.0          # nothing was enqueued
+    assert call(None) == rnn.RNN_OK                       # no lengths: nothing to check
+    assert rnn.rnn_model_set_validation(model.handle, 0) == rnn.RNN_OK
+    bad = good.clone()
+    bad[1] = c.T + 5                                      # clamped to T on the device
+    assert call(bad) == rnn.RNN_OK
+    assert call(good) == rnn.RNN_OK
+    torch.cuda.synchronize()
+    assert torch.equal(io.y, ref)
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    model.close()
+
+
+@pytest.mark.parametrize("name", ["lstm_bf16_8layer_h256", "lstm_bf16_inside_sq", "lstm_bf16_b299"])
+def test_launch_tag_wraps(gpu, name):
+    """The 32-bit launch tag wraps after 2^32 launches: the launch that wraps clears the flag words and the
+    tagged words and starts again from tag 1.  Forced here by setting the tag just below the wrap: the
+    forwards across it give, bit for bit, what the first forward gave."""
+    import torch
+    harness, rnn, W = gpu
+    wl = _small_workload(W, next(s for s in SMALL if s[0] == name))
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    ref = (io.y.clone(), io.hT.clone(), io.cT.clone())
+    assert rnn.rnn_model_set_launch_tag(model.handle, 0xFFFFFFFF - 2) == rnn.RNN_OK
+    for k in range(8):      # tags ...FFFE, ...FFFF, then the wrap, then 1, 2, ... (several launches per forward)
+        io.y.fill_(7.0)
+        harness.forward(model, io)
+        torch.cuda.synchronize()
+        assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK, k
+        assert torch.equal(io.y, ref[0]) and torch.equal(io.hT, ref[1]) and torch.equal(io.cT, ref[2]), k
+    model.close()
+
+
 @pytest.mark.parametrize("cell", [0, 1], ids=["lstm", "gru"])
 def test_onnx_gate_order(gpu, oracle, cell):
     """Weights whose gate row blocks come in the order of the ONNX operators (LSTM i,o,f,c; GRU z,r,h)
@@ -739,6 +801,32 @@ def test_C5_sampled_sequences(gpu, oracle):
     the eight 32-sequence chains of the launch, plus the last lane of the first 16-sequence tile, the
     first lane of the second and the last lane of the last."""
     _run_named(gpu, oracle, "C5", 0, sample=[0, 15, 16, 36, 72, 109, 145, 182, 218, 255])
+
+
+def test_long_sequence_on_the_interleaved_chain_kernel(gpu, oracle):
+    """1000 steps on the kernel that issues its matrix instructions by hand from the accumulation registers
+    (two interleaved chains per workgroup, input product inside): a slip in the spacing of those instructions or
+    in the step protocol that shows only now and then has 2000 chain steps per workgroup to show in (the variant
+    of the throughput workload: 1024 units, part of W_ih in LDS), against
+    the oracle on sampled sequences (first and last lane of a tile, both chains of a workgroup)."""
+    import torch
+    harness, rnn, W = gpu
+    cfg = W.Config("long_T_interleaved", W.LSTM, L=1, D=1, I=1024, H=1024, T=1000, B=128, dtype=W.BF16,
+                   seed=W.BASE_SEED + 41, len_min=800)
+    prop = torch.cuda.get_device_properties(0)
+    rc, plan, sep = rnn.rnn_plan_query(cfg.cell, cfg.L, cfg.I, cfg.H, cfg.D, cfg.dtype, rnn.RNN_PLAN_AUTO, cfg.T, cfg.B,
+                                       prop.multi_processor_count, 160 * 1024)
+    assert rc == rnn.RNN_OK and plan["chains"] == 2 and sep == [0], (plan, sep)
+    wl = W.make_workload(cfg, zero_pad_x=False)
+    model = harness.DeviceModel(wl)
+    io = harness.DeviceIO(wl)
+    harness.forward(model, io)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    rows = np.array([0, 15, 47, 64, 127])   # chains of 32 sequences: 0, 0, 1, 2, 3
+    ref = oracle.forward_workload(wl.take_batch(rows), nthreads=16)
+    _check(harness, wl, io, ref, rows=rows)
+    model.close()
 
 
 @pytest.mark.parametrize("name", ["C2", "C4", "C5"])
