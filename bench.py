@@ -183,8 +183,8 @@ def time_workload(name, steps: int, warmup: int, per_call: int = 0, ticks: bool 
 def time_cell_variants():
     """The cell variants and layouts beyond the plain time-major cell: what each costs.  Batch-first I/O on the
     bidirectional workload (every plan works on a re-laid-out copy: one more pass over x and y); peephole weights
-    and a clipping threshold on the paper's own 12-layer model under the cellwise plan (the only plan that has
-    them), beside the plain cell under the same plan and under the automatic one."""
+    and a clipping threshold on the paper's own 12-layer model and on C3, under the cellwise plan and inside the
+    persistent kernels, beside the plain cell."""
     import numpy as np
     import torch
     from paper_2307_11339_amd import rnn, workloads as W
@@ -208,12 +208,19 @@ def time_cell_variants():
         assert rnn.rnn_model_set_clip(model.handle, 3.0) == rnn.RNN_OK
 
     base = W.paper_grid()[0]
-    _, r = time_workload(base, steps=5, warmup=1)
+    _, r = time_workload(base, steps=50, warmup=5)
     out["paper_base_ms"] = round(r["ms_per_step"], 4)
     _, r = time_workload(base, steps=5, warmup=1, plan=rnn.RNN_PLAN_CELLWISE)
     out["paper_base_cellwise_ms"] = round(r["ms_per_step"], 4)
-    _, r = time_workload(base, steps=5, warmup=1, setup=options)
+    _, r = time_workload(base, steps=5, warmup=1, plan=rnn.RNN_PLAN_CELLWISE, setup=options)
     out["paper_base_cellwise_peepholes_clip_ms"] = round(r["ms_per_step"], 4)
+    # the same terms inside the persistent kernels (a unit's peephole weights and the threshold sit in registers)
+    _, r = time_workload(base, steps=50, warmup=5, setup=options)
+    out["paper_base_peepholes_clip_ms"] = round(r["ms_per_step"], 4)
+    _, r = time_workload("C3", steps=50, warmup=5)
+    out["C3_ms"] = round(r["ms_per_step"], 4)
+    _, r = time_workload("C3", steps=50, warmup=5, setup=options)
+    out["C3_peepholes_clip_ms"] = round(r["ms_per_step"], 4)
     return out
 
 

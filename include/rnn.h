@@ -137,9 +137,10 @@ int rnn_model_set_plan(rnn_model* model, int plan);
 int rnn_model_set_gru_reset_before(rnn_model* model, int on);
 
 /* The two optional terms that the ONNX LSTM / GRU operators (the format of the models the paper's
- * system ingests, Section 1 and Section 4.1) add to the plain cell.  Both run under the cellwise
- * plan only: RNN_EUNSUPPORTED while RNN_PLAN_WAVEFRONT is selected, and selecting that plan while
- * either is set is refused.
+ * system ingests, Section 1 and Section 4.1) add to the plain cell.  Both are part of the gate
+ * arithmetic of every plan (the persistent kernels keep a unit's three peephole weights and the
+ * threshold in registers beside its bias).  Either call takes effect with the next forward; no forward
+ * of the model may be in flight.
  *
  * Clipping threshold: clip > 0 limits the argument of every gate activation (i, f, g, o including
  * their peephole terms; r, z and the whole argument of n) to [-clip, +clip]; the cell state inside

@@ -39,26 +39,6 @@ __global__ void state_export_kernel(const float* h_f32, const float* c_f32, floa
 // clip = 0: no clipping
 __device__ inline float limit(float v, float clip) { return clip > 0.0f ? fminf(fmaxf(v, -clip), clip) : v; }
 
-// The cell with the optional terms of the ONNX operators: peephole weights (LSTM: i and f see c_{t-1},
-// o sees the new c_t) and a clipping threshold on the argument of every gate activation (not on the
-// cell state inside o * tanh(c)).  pw = {p_i, p_f, p_o} of this unit.
-template <int CELL>
-__device__ inline float cell_update_ext(const float a[SLOTS], float h_prev, float& c, const float pw[3], float clip) {
-    if (CELL == CELL_LSTM) {
-        const float ig = sigmoid_f(limit(a[0] + pw[0] * c, clip));
-        const float fg = sigmoid_f(limit(a[1] + pw[1] * c, clip));
-        const float gg = tanh_f(limit(a[2], clip));
-        c = fg * c + ig * gg;
-        const float og = sigmoid_f(limit(a[3] + pw[2] * c, clip));
-        return og * tanh_f(c);
-    } else {
-        const float r = sigmoid_f(limit(a[0], clip));
-        const float z = sigmoid_f(limit(a[1], clip));
-        const float n = tanh_f(limit(a[2] + r * a[3], clip));
-        return (1.0f - z) * n + z * h_prev;
-    }
-}
-
 template <int CELL, int DT>
 __global__ void cell_step_kernel(CellStepArgs a) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;  // (b, u)
@@ -88,11 +68,8 @@ __global__ void cell_step_kernel(CellStepArgs a) {
         const float n = tanh_f(limit(pre[2] + nh, a.clip));
         h = (1.0f - z) * n + z * a.h_f32[i];
     } else if (a.peep != nullptr || a.clip > 0.0f) {
-        float pw[3] = {0.0f, 0.0f, 0.0f};
-        if (CELL == CELL_LSTM && a.peep != nullptr) {
-            pw[0] = a.peep[u]; pw[1] = a.peep[a.H + u]; pw[2] = a.peep[2 * a.H + u];
-        }
-        h = cell_update_ext<CELL>(pre, a.h_f32[i], c, pw, a.clip);
+        const CellExt e = load_cell_ext(CELL == CELL_LSTM ? a.peep : nullptr, a.H, u, a.clip);
+        h = cell_update_ext<CELL>(pre, a.h_f32[i], c, e);
     } else {
         h = cell_update<CELL>(pre, a.h_f32[i], c);
     }

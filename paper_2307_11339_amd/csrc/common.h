@@ -61,4 +61,42 @@ __device__ inline float cell_update(const float a[SLOTS], float h_prev, float& c
     }
 }
 
+// The optional terms of the ONNX LSTM / GRU operators for one hidden unit: peephole weights (LSTM: i and f
+// see c_{t-1}, o sees the new c_t) and the bound on the argument of every gate activation (never on the cell
+// state inside o * tanh(c)).  The plain cell is {0, 0, 0, +infinity}: a + 0 * c == a and a value limited to
+// [-inf, +inf] is itself, so one code path serves both and gives the plain cell's bits when the terms are off.
+struct CellExt {
+    float p_i, p_f, p_o;   // peephole weights of this unit (0 for a GRU)
+    float lim;             // clipping threshold, +infinity for none
+};
+
+__device__ inline float limit_to(float v, float lim) { return fminf(fmaxf(v, -lim), lim); }
+
+template <int CELL>
+__device__ inline float cell_update_ext(const float a[SLOTS], float h_prev, float& c, const CellExt& e) {
+    if (CELL == CELL_LSTM) {
+        const float ig = sigmoid_f(limit_to(a[0] + e.p_i * c, e.lim));
+        const float fg = sigmoid_f(limit_to(a[1] + e.p_f * c, e.lim));
+        const float gg = tanh_f(limit_to(a[2], e.lim));
+        c = fg * c + ig * gg;
+        const float og = sigmoid_f(limit_to(a[3] + e.p_o * c, e.lim));
+        return og * tanh_f(c);
+    } else {
+        const float r = sigmoid_f(limit_to(a[0], e.lim));
+        const float z = sigmoid_f(limit_to(a[1], e.lim));
+        const float n = tanh_f(limit_to(a[2] + r * a[3], e.lim));
+        return (1.0f - z) * n + z * h_prev;
+    }
+}
+
+// CellExt of hidden unit `unit`: peep = NULL or [3, H] (p_i, p_f, p_o), clip = 0 for none.
+__device__ inline CellExt load_cell_ext(const float* peep, int H, int unit, float clip) {
+    CellExt e;
+    e.p_i = peep ? peep[unit] : 0.0f;
+    e.p_f = peep ? peep[H + unit] : 0.0f;
+    e.p_o = peep ? peep[2 * H + unit] : 0.0f;
+    e.lim = clip > 0.0f ? clip : __builtin_inff();
+    return e;
+}
+
 }  // namespace rnn

@@ -73,6 +73,10 @@ struct WavefrontArgs {
     const void* whh[WF_MAX_LAYERS * 2];   // packed W_hh per (local layer, direction): [4H, H]
     const void* wih[WF_MAX_LAYERS * 2];   // packed W_ih (layers l0+1.. only, D = 1): [4H, H]
     const float* bias[WF_MAX_LAYERS * 2]; // [H, 4]
+    const float* peep[WF_MAX_LAYERS * 2]; // NULL, or (LSTM) [3, H] peephole weights p_i, p_f, p_o per (local layer, direction)
+    float clip;                           // clipping threshold of the gate arguments, 0 = none
+    int ext;                              // 1 when clip > 0 or a peep[] entry is set: the launch runs the kernel
+                                          // variants whose gate phase carries those terms
     const float* gx;             // projection of layer l0: [T*B, D, H, 4] (unused when xin is given)
     const void* xin;             // NULL, or the finished input of layer l0, which then multiplies it
                                  // with its resident W_ih inside the kernel instead of reading gx.

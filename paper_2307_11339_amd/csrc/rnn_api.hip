@@ -80,12 +80,12 @@ struct rnn_model {
 
     DevBuf status;          // one word, raised by a kernel whose wait gave up (rnn_model_check)
     bool gru_reset_before = false;
-    float clip = 0.0f;          // clipping threshold of the gate arguments (cellwise plan only), 0 = none
-    std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM, cellwise plan only)
+    float clip = 0.0f;          // clipping threshold of the gate arguments, 0 = none
+    std::vector<DevBuf> peep;   // empty, or per (layer, direction) [3, H] fp32 peephole weights (LSTM)
     bool batch_first = false;   // x is [B, T, I] and y [B, T, D*H]
     bool validate = false;      // check `lengths` on the host before every forward
-    // cell variants that only the cellwise plan implements
-    bool cellwise_only() const { return gru_reset_before || clip > 0.0f || !peep.empty(); }
+    // the cell variant that only the cellwise plan implements (two dependent recurrent products per cell)
+    bool cellwise_only() const { return gru_reset_before; }
     // Everything a forward pass keeps in device memory besides the weights.
     struct Workspace {
         DevBuf gx, hseq, flags, h_f32, c_f32, h_st, gh, ticks;
@@ -449,12 +449,15 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
             a.whh[ll * m->D + d] = m->whh[l * m->D + d].p;
             a.wih[ll * m->D + d] = m->wih[l].p;  // fused layers have D = 1
             a.bias[ll * m->D + d] = (const float*)m->bias[l * m->D + d].p;
+            a.peep[ll * m->D + d] = m->peep.empty() ? nullptr : (const float*)m->peep[l * m->D + d].p;
         }
         char* base = (char*)((l == m->L - 1) ? y : m->ws.ybuf[l].p);
         a.out[ll] = base;
         // a layer whose consumer reads the state sequence instead keeps no separate output
         if (!tagged && (xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
     }
+    a.clip = m->clip;
+    a.ext = (m->clip > 0.0f || !m->peep.empty()) ? 1 : 0;
     a.gx = gx;
     a.xin = xin;
     a.xin_width2 = (tagged && xin) ? 2 * m->layer_input(l0) / m->H : 0;
@@ -877,7 +880,6 @@ int rnn_model_set_gru_reset_before(rnn_model* m, int on) {
 
 int rnn_model_set_clip(rnn_model* m, float clip) {
     if (!m || !(clip >= 0.0f) || !isfinite(clip)) return RNN_EINVAL;
-    if (clip > 0.0f && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     m->clip = clip;
     return RNN_OK;
 }
@@ -890,7 +892,7 @@ int rnn_model_set_peepholes(rnn_model* m, const float* const* peepholes, int on_
         m->peep.clear();
         return RNN_OK;
     }
-    if (m->cell != CELL_LSTM || m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
+    if (m->cell != CELL_LSTM) return RNN_EUNSUPPORTED;
     const size_t bytes = (size_t)3 * m->H * sizeof(float);
     std::vector<DevBuf> fresh((size_t)m->L * m->D);
     int rc = RNN_OK;

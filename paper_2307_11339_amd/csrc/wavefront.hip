@@ -43,6 +43,14 @@
 // waiting, so the grid always drains.
 #include "wf_traits.h"
 
+// Every variant exists twice: with the plain cell, and (RNN_CELL_EXT = 1, the translation unit
+// wavefront_b.hip) with the optional peephole and clipping terms in the gate phase, so that a model
+// without those terms runs exactly the plain cell's instructions.
+#ifndef RNN_CELL_EXT
+#define RNN_CELL_EXT 0
+#endif
+
+
 namespace rnn {
 
 namespace {
@@ -63,7 +71,7 @@ constexpr int variant_occupancy(int /*CT*/) { return 1; }
 // also covers the loads in flight, which bounds what can be hidden.  Four chains of 16
 // sequences were measured slower than two of 32: the fixed cost of a chain step, two barriers,
 // a store acknowledgement and a flag poll, is paid twice as often.)
-template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH>
+template <class TR, int CELL, int RT, int CT, int KB, bool FUSED, int NCH, bool EXT>
 __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(WavefrontArgs p) {
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
@@ -122,6 +130,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
     float c_reg[NCH][NOWN], h_reg[NCH][NOWN];
     int len_reg[NCH][NOWN], col_reg[NCH][NOWN];
     f32x4 bias_reg[NOWN];
+    CellExt ext_reg[EXT ? NOWN : 1];                // peephole weights and clipping bound of the unit
     int unit_reg[NOWN];
     const size_t state_row = (size_t)(l * p.D + d) * B;
 #pragma unroll
@@ -132,6 +141,7 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
         unit_reg[o] = unit;
         bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+        if constexpr (EXT) ext_reg[o] = load_cell_ext(CELL == CELL_LSTM ? p.peep[g] : nullptr, H, min(unit, H - 1), p.clip);
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int col = ((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
@@ -285,7 +295,9 @@ __global__ __launch_bounds__(256, variant_occupancy(CT)) void wavefront_kernel(W
                     const bool active = valid && t < len_reg[c][o];
                     float c_new = c_reg[c][o];
                     const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
-                    const float hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
+                    float hn;
+                    if constexpr (EXT) hn = cell_update_ext<CELL>(pre, h_reg[c][o], c_new, ext_reg[o]);
+                    else hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
                     float kept = h_reg[c][o];
                     if (active) {
                         c_reg[c][o] = c_new;
@@ -352,7 +364,7 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     if (a.Bp < a.B || a.Bp % 4 != 0) return hipErrorInvalidValue;
     const int grid = a.LP * a.D * a.nrb * (a.ncb / NCH);
     const size_t smem = (size_t)4 * RT * CT * 64 * sizeof(f32x4);
-    auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH>;
+    auto kern = wavefront_kernel<TR, CELL, RT, CT, KB, FUSED, NCH, RNN_CELL_EXT != 0>;
     if (smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -402,7 +414,24 @@ template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
 template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
+hipError_t launch_here(const WavefrontArgs& a, hipStream_t stream) {
+    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
+    const int KB = a.H / (4 * kw);
+#define X(TR, rt, ct, kb, nch)                                                          \
+    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
+        return launch_cell_fused<TR, rt, ct, kb, nch>(a, stream);
+    RNN_WF_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
+
+#if RNN_CELL_EXT
+hipError_t launch_wavefront_ext(const WavefrontArgs& a, hipStream_t stream) { return launch_here(a, stream); }
+#else
+hipError_t launch_wavefront_ext(const WavefrontArgs& a, hipStream_t stream);   // wavefront_b.hip
 
 bool wavefront_variant_exists(int dtype, int RT, int CT, int NCH, int H, bool fused) {
     if (fused && variant_occupancy(CT) > 1) return false;  // no room for W_ih at two workgroups per CU
@@ -419,15 +448,7 @@ bool wavefront_variant_exists(int dtype, int RT, int CT, int NCH, int H, bool fu
 int wavefront_variant_occupancy(int CT) { return variant_occupancy(CT); }
 
 hipError_t launch_wavefront(const WavefrontArgs& a, hipStream_t stream) {
-    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
-    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
-    const int KB = a.H / (4 * kw);
-#define X(TR, rt, ct, kb, nch)                                                          \
-    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
-        return launch_cell_fused<TR, rt, ct, kb, nch>(a, stream);
-    RNN_WF_VARIANTS(X)
-#undef X
-    return hipErrorInvalidValue;
+    return a.ext ? launch_wavefront_ext(a, stream) : launch_here(a, stream);
 }
 
 hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int D, int T, int B, int Bp,
@@ -440,5 +461,7 @@ hipError_t launch_wavefront_init(int dtype, const float* h0, int l0, int LP, int
         wavefront_init_kernel<DT_F32><<<blocks, 256, 0, stream>>>(h0, l0, LP, D, T, B, Bp, H, hseq);
     return hipGetLastError();
 }
+
+#endif  // !RNN_CELL_EXT
 
 }  // namespace rnn

@@ -29,6 +29,12 @@
 #ifndef RNN_LL_PART
 #define RNN_LL_PART 0
 #endif
+// Every variant exists twice: with the plain cell, and (RNN_CELL_EXT = 1, the translation units
+// wavefront_ll_d/e/f.hip) with the optional peephole and clipping terms in the gate phase, so that a model
+// without those terms runs exactly the plain cell's instructions.
+#ifndef RNN_CELL_EXT
+#define RNN_CELL_EXT 0
+#endif
 
 namespace rnn {
 namespace {
@@ -299,7 +305,7 @@ __device__ inline void ll_consume(const typename TR::frag (&wreg)[RT][KB], const
 // layer: 2 = as wide as the layer (also when that layer reads a projection), 1 = half as wide, 4 = twice as wide
 // (a bidirectional layer above the first, which reads [forward, backward] of the layer below).
 // XWO = XW + 8 * (mode of the h waves' state fetch, see ll_wait).
-template <class TR, int CELL, int RT, int KB, int XWO>
+template <class TR, int CELL, int RT, int KB, int XWO, bool EXT>
 __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(WavefrontArgs p) {
     constexpr int XW = XWO & 7;
     constexpr int WAIT_MODE = (XWO >> 3) & 3;        // how the h waves fetch the state, see ll_wait
@@ -480,6 +486,7 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
 
     float c_reg[NOWN], h_reg[NOWN];
     f32x4 bias_reg[NOWN];
+    CellExt ext_reg[EXT ? NOWN : 1];                 // peephole weights and clipping bound of the unit
     int unit_reg[NOWN];
     const int col = cb * 16 + (lane & 15);
     const bool valid = col < B;
@@ -494,6 +501,7 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
         c_reg[o] = 0.0f;
         h_reg[o] = 0.0f;
         bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (EXT) ext_reg[o] = load_cell_ext(CELL == CELL_LSTM ? p.peep[g] : nullptr, H, min(unit, H - 1), p.clip);
         if (rt < RT && valid) {
             const size_t si = (state_row + col) * H + unit;
             if (p.h0) h_reg[o] = p.h0[si];
@@ -563,7 +571,9 @@ __global__ __launch_bounds__((XWO & 7) ? 512 : 256) void wavefront_ll_kernel(Wav
                 const bool active = valid && t < len;
                 float c_new = c_reg[o];
                 const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
-                const float hn = cell_update<CELL>(pre, h_reg[o], c_new);
+                float hn;
+                if constexpr (EXT) hn = cell_update_ext<CELL>(pre, h_reg[o], c_new, ext_reg[o]);
+                else hn = cell_update<CELL>(pre, h_reg[o], c_new);
                 if (active) {
                     float kept;
                     (void)TR::store_val(hn, kept);
@@ -625,7 +635,7 @@ hipError_t launch_ll_variant(const WavefrontArgs& a, hipStream_t stream) {
     constexpr int QW = KB * TR::WORDS_PER_KW;
     const size_t smem = (size_t)(XW ? 3 : 1) * 4 * RT * 64 * sizeof(f32x4) +
                         (size_t)(XW ? 8 : 4) * 16 * (QW + 4) * sizeof(uint32_t);
-    auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, XWO>;
+    auto kern = wavefront_ll_kernel<TR, CELL, RT, KB, XWO, RNN_CELL_EXT != 0>;
     static bool configured = false;
     if (!configured && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -737,13 +747,17 @@ hipError_t launch_here(const WavefrontArgs& a, hipStream_t stream, int KB) {
 
 }  // namespace
 
-#if RNN_LL_PART == 1
-hipError_t launch_wavefront_ll_part1(const WavefrontArgs& a, hipStream_t stream, int KB) { return launch_here(a, stream, KB); }
-#elif RNN_LL_PART == 2
-hipError_t launch_wavefront_ll_part2(const WavefrontArgs& a, hipStream_t stream, int KB) { return launch_here(a, stream, KB); }
-#else
-hipError_t launch_wavefront_ll_part1(const WavefrontArgs& a, hipStream_t stream, int KB);
-hipError_t launch_wavefront_ll_part2(const WavefrontArgs& a, hipStream_t stream, int KB);
+// every translation unit exports its variants under a name of its own: part 0..2, plain or extended cell
+#define RNN_LL_FN2(part, ext) launch_wavefront_ll_part##part##_ext##ext
+#define RNN_LL_FN(part, ext) RNN_LL_FN2(part, ext)
+hipError_t RNN_LL_FN(RNN_LL_PART, RNN_CELL_EXT)(const WavefrontArgs& a, hipStream_t stream, int KB) { return launch_here(a, stream, KB); }
+
+#if RNN_LL_PART == 0 && RNN_CELL_EXT == 0
+hipError_t launch_wavefront_ll_part1_ext0(const WavefrontArgs& a, hipStream_t stream, int KB);
+hipError_t launch_wavefront_ll_part2_ext0(const WavefrontArgs& a, hipStream_t stream, int KB);
+hipError_t launch_wavefront_ll_part0_ext1(const WavefrontArgs& a, hipStream_t stream, int KB);
+hipError_t launch_wavefront_ll_part1_ext1(const WavefrontArgs& a, hipStream_t stream, int KB);
+hipError_t launch_wavefront_ll_part2_ext1(const WavefrontArgs& a, hipStream_t stream, int KB);
 
 bool wavefront_ll_variant_exists(int dtype, int RT, int H) {
     const int kw = dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
@@ -761,15 +775,18 @@ hipError_t launch_wavefront_ll(const WavefrontArgs& a, hipStream_t stream) {
     if (a.H % (4 * kw) != 0 || a.CT != 1) return hipErrorInvalidValue;
     const int KB = a.H / (4 * kw);
 #define X(TR, rt, kb) \
-    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_here(a, stream, KB);
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) \
+        return a.ext ? launch_wavefront_ll_part0_ext1(a, stream, KB) : launch_wavefront_ll_part0_ext0(a, stream, KB);
     RNN_LL_VARIANTS_0(X)
 #undef X
 #define X(TR, rt, kb) \
-    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_wavefront_ll_part1(a, stream, KB);
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) \
+        return a.ext ? launch_wavefront_ll_part1_ext1(a, stream, KB) : launch_wavefront_ll_part1_ext0(a, stream, KB);
     RNN_LL_VARIANTS_1(X)
 #undef X
 #define X(TR, rt, kb) \
-    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) return launch_wavefront_ll_part2(a, stream, KB);
+    if (LLDtOf<TR>::value == a.dtype && a.RT == rt && KB == kb) \
+        return a.ext ? launch_wavefront_ll_part2_ext1(a, stream, KB) : launch_wavefront_ll_part2_ext0(a, stream, KB);
     RNN_LL_VARIANTS_2(X)
 #undef X
     return hipErrorInvalidValue;
@@ -790,6 +807,6 @@ size_t wavefront_ll_words(int dtype, int groups, int T, int B, int H) {
     return (size_t)groups * (size_t)(T + 1) * B * (dtype == DT_BF16 ? H / 2 : H);
 }
 
-#endif  // RNN_LL_PART == 0
+#endif  // RNN_LL_PART == 0 && RNN_CELL_EXT == 0
 
 }  // namespace rnn

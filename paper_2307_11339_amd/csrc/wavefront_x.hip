@@ -27,6 +27,14 @@
 //     behind that group's flag vectors.
 #include "wf_traits.h"
 
+// Every variant exists twice: with the plain cell, and (RNN_CELL_EXT = 1, the translation unit
+// wavefront_x_b.hip) with the optional peephole and clipping terms in the gate phase, so that a model
+// without those terms runs exactly the plain cell's instructions.
+#ifndef RNN_CELL_EXT
+#define RNN_CELL_EXT 0
+#endif
+
+
 namespace rnn {
 
 namespace {
@@ -51,8 +59,12 @@ constexpr int wx_register_blocks() {
 // MULTI: the launch runs p.LP layers side by side, one group of workgroups each; a layer above the first
 // of the launch reads the state sequence of the group below as its x, behind that group's flags, so the
 // groups settle on successive anti-diagonals of the layer x time grid (paper Section 2.2).
-template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool MULTI>
+template <class TR, int CELL, int RT, int CT, int KB, int NCH, bool MULTI, bool EXT>
 __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
+    // peephole weights of an extended LSTM cell: in LDS for the interleaved-chain shapes (no register to
+    // spare beside the resident weights), in registers otherwise (no LDS to spare beside the W_ih slice)
+    constexpr bool PEEP_LDS = EXT && CELL == CELL_LSTM && NCH == 2;
+    constexpr bool PEEP_REG = EXT && CELL == CELL_LSTM && NCH != 2;
     static_assert(!MULTI || NCH > 1, "layers side by side need interleaved chains");
     typedef typename TR::elem elem;
     typedef typename TR::frag frag;
@@ -64,6 +76,10 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     f32x4* red = reinterpret_cast<f32x4*>(smem_raw);  // [4 waves][NTILE][64 lanes]
     frag* wxl = reinterpret_cast<frag*>(smem_raw + (size_t)4 * NTILE * 64 * sizeof(f32x4));  // [4][RT][KBL][64]
+    // (PEEP_LDS) peephole weights of the workgroup's units [3][RT * 4] (zeros without them): read with the
+    // partial sums in the gate phase, so that they cost no registers across the matrix parts
+    float* peep_lds = reinterpret_cast<float*>(smem_raw + (size_t)4 * NTILE * 64 * sizeof(f32x4) +
+                                               (size_t)4 * RT * KBL * 64 * sizeof(frag));
 
     __builtin_amdgcn_s_setprio(3);
     const int tid = threadIdx.x;
@@ -109,9 +125,10 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 
     // ---- per-lane state of the (unit, sequence) pairs this lane finishes ---------------------
     float c_reg[NCH][NOWN], h_reg[NCH][NOWN];
-    int len_reg[NCH][NOWN], col_reg[NCH][NOWN];
+    int len_reg[NCH][NOWN];                         // valid steps of the pair's sequence; 0 for a column beyond the batch
     f32x4 bias_reg[NOWN];
     int unit_reg[NOWN];
+    float peep_reg[PEEP_REG ? NOWN : 1][3];
     const size_t state_row = (size_t)l * B;
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) {
@@ -121,10 +138,13 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
         unit_reg[o] = unit;
         bias_reg[o] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (j < NTILE) bias_reg[o] = *reinterpret_cast<const f32x4*>(p.bias[g] + (size_t)unit * SLOTS);
+        if constexpr (PEEP_REG) {
+            const CellExt e = load_cell_ext(p.peep[g], H, min(unit, H - 1), p.clip);
+            peep_reg[o][0] = e.p_i; peep_reg[o][1] = e.p_f; peep_reg[o][2] = e.p_o;
+        }
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int col = ((cbg * NCH + c) * CT + (ct + rot_c) % CT) * 16 + (lane & 15);
-            col_reg[c][o] = col;
             c_reg[c][o] = 0.0f;
             h_reg[c][o] = 0.0f;
             len_reg[c][o] = 0;
@@ -135,6 +155,15 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 len_reg[c][o] = p.lengths ? min(max(p.lengths[col], 0), T) : T;
             }
         }
+    }
+
+    const float clip_lim = p.clip > 0.0f ? p.clip : __builtin_inff();   // uniform
+    if constexpr (PEEP_LDS) {
+        if (tid < 3 * RT * 4) {
+            const int k = tid / (RT * 4), u = tid - k * (RT * 4);
+            peep_lds[tid] = p.peep[g] ? p.peep[g][(size_t)k * H + rb * RT * 4 + u] : 0.0f;
+        }
+        // (the first barrier of the first chain step orders these writes before the first read)
     }
 
     // B operand columns of this lane (clamped so that loads stay in bounds; columns >= B are
@@ -384,6 +413,24 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     part[o][q] = red[(q * NTILE + min(w + 4 * o, NTILE - 1)) * 64 + lane];
+            CellExt ext[NOWN];
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o) ext[o] = CellExt{0.0f, 0.0f, 0.0f, clip_lim};
+            if constexpr (PEEP_LDS) {
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    const int ul = min(unit_reg[o] - rb * RT * 4, RT * 4 - 1);     // unit inside the workgroup's slice
+                    ext[o].p_i = peep_lds[ul];
+                    ext[o].p_f = peep_lds[RT * 4 + ul];
+                    ext[o].p_o = peep_lds[2 * RT * 4 + ul];
+                }
+            }
+            if constexpr (PEEP_REG) {
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    ext[o].p_i = peep_reg[o][0]; ext[o].p_f = peep_reg[o][1]; ext[o].p_o = peep_reg[o][2];
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
@@ -396,13 +443,14 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
                 }
                 const int j = w + 4 * o;
                 if (j < NTILE) {  // uniform per wave
-                    const bool valid = col_reg[c][o] < B;
                     f32x4 a = (part[o][0] + part[o][1]) + (part[o][2] + part[o][3]);
                     a += bias_reg[o];
-                    const bool active = valid && t < len_reg[c][o];
+                    const bool active = t < len_reg[c][o];
                     float c_new = c_reg[c][o];
                     const float pre[SLOTS] = {a[0], a[1], a[2], a[3]};
-                    const float hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
+                    float hn;
+                    if constexpr (EXT) hn = cell_update_ext<CELL>(pre, h_reg[c][o], c_new, ext[o]);
+                    else hn = cell_update<CELL>(pre, h_reg[c][o], c_new);
                     float kept = h_reg[c][o];
                     if (active) {
                         c_reg[c][o] = c_new;
@@ -469,8 +517,9 @@ __global__ __launch_bounds__(256, 1) void wavefront_x_kernel(WavefrontArgs p) {
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int j = w + 4 * o;
-            if (j < NTILE && col_reg[c][o] < B) {
-                const size_t si = (state_row + col_reg[c][o]) * H + unit_reg[o];
+            const int col = ((cbg * NCH + c) * CT + (j % CT + rot_c) % CT) * 16 + (lane & 15);
+            if (j < NTILE && col < B) {
+                const size_t si = (state_row + col) * H + unit_reg[o];
                 if (p.hT) p.hT[si] = h_reg[c][o];
                 if (p.cT && CELL == CELL_LSTM) p.cT[si] = c_reg[c][o];
             }
@@ -503,7 +552,8 @@ __global__ __launch_bounds__(256) void to_blocked_kernel(const uint4* __restrict
 template <class TR, int RT, int CT, int KB, int NCH>
 constexpr size_t lds_bytes() {
     return (size_t)4 * RT * CT * 64 * sizeof(f32x4) +
-           (size_t)4 * RT * (KB - wx_register_blocks<TR, RT, KB, NCH>()) * 64 * sizeof(typename TR::frag);
+           (size_t)4 * RT * (KB - wx_register_blocks<TR, RT, KB, NCH>()) * 64 * sizeof(typename TR::frag) +
+           ((RNN_CELL_EXT && NCH == 2) ? (size_t)3 * RT * 4 * sizeof(float) : 0);   // partial sums, W_ih blocks, (extended cell, two chains) peephole weights
 }
 
 int device_lds_limit() {
@@ -528,7 +578,7 @@ hipError_t launch_variant(const WavefrontArgs& a, hipStream_t stream) {
     const int grid = a.LP * a.nrb * (a.ncb / NCH);
     constexpr size_t smem = lds_bytes<TR, RT, CT, KB, NCH>();
     if (smem > (size_t)device_lds_limit()) return hipErrorInvalidValue;
-    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, MULTI>;
+    auto kern = wavefront_x_kernel<TR, CELL, RT, CT, KB, NCH, MULTI, RNN_CELL_EXT != 0>;
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -583,7 +633,25 @@ template <class TR> struct DtOf;
 template <> struct DtOf<TraitsBf16> { static constexpr int value = DT_BF16; };
 template <> struct DtOf<TraitsF32> { static constexpr int value = DT_F32; };
 
+hipError_t launch_here(const WavefrontArgs& a, hipStream_t stream) {
+    if (a.LP < 1 || a.D != 1 || a.xin == nullptr) return hipErrorInvalidValue;
+    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
+    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
+    const int KB = a.H / (4 * kw);
+#define X(TR, rt, ct, kb, nch)                                                          \
+    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
+        return launch_cell<TR, rt, ct, kb, nch>(a, stream);
+    RNN_WFX_VARIANTS(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
 }  // namespace
+
+#if RNN_CELL_EXT
+hipError_t launch_wavefront_x_ext(const WavefrontArgs& a, hipStream_t stream) { return launch_here(a, stream); }
+#else
+hipError_t launch_wavefront_x_ext(const WavefrontArgs& a, hipStream_t stream);   // wavefront_x_b.hip
 
 bool wavefront_x_variant_exists(int dtype, int RT, int CT, int NCH, int H, size_t lds_limit, bool several_layers) {
     if (several_layers && NCH < 2) return false;
@@ -612,16 +680,9 @@ hipError_t launch_to_blocked(int dtype, const void* src, void* dst, int T, int B
 }
 
 hipError_t launch_wavefront_x(const WavefrontArgs& a, hipStream_t stream) {
-    if (a.LP < 1 || a.D != 1 || a.xin == nullptr) return hipErrorInvalidValue;
-    const int kw = a.dtype == DT_BF16 ? TraitsBf16::KW : TraitsF32::KW;
-    if (a.H % (4 * kw) != 0) return hipErrorInvalidValue;
-    const int KB = a.H / (4 * kw);
-#define X(TR, rt, ct, kb, nch)                                                          \
-    if (DtOf<TR>::value == a.dtype && a.RT == rt && a.CT == ct && KB == kb && a.NCH == nch)  \
-        return launch_cell<TR, rt, ct, kb, nch>(a, stream);
-    RNN_WFX_VARIANTS(X)
-#undef X
-    return hipErrorInvalidValue;
+    return a.ext ? launch_wavefront_x_ext(a, stream) : launch_here(a, stream);
 }
+
+#endif  // !RNN_CELL_EXT
 
 }  // namespace rnn

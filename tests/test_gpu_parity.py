@@ -409,28 +409,39 @@ def test_onnx_gate_order(gpu, oracle, cell):
     ref_model.close()
 
 
-@pytest.mark.parametrize("spec,clip,peep", [
-    (("lstm_opts_bf16", 0, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, True),
+OPT_SPECS = [
+    (("lstm_opts_bf16", 0, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, True),           # tag-in-data kernel, both directions
     (("lstm_opts_f32", 0, 3, 1, 20, 64, 12, 5, 0, True, True), 0.4, True),
     (("lstm_peep_only", 0, 2, 1, 64, 128, 8, 6, 1, True, True), 0.0, True),
     (("lstm_clip_only", 0, 2, 1, 64, 128, 8, 6, 1, True, True), 0.3, False),
     (("gru_clip_bf16", 1, 2, 2, 40, 128, 9, 21, 1, True, True), 0.5, False),
     (("gru_clip_f32", 1, 2, 1, 12, 32, 8, 18, 0, True, True), 0.25, False),
     (("lstm_opts_padded_h72", 0, 2, 2, 24, 72, 6, 5, 1, True, True), 0.6, True),      # 72 -> 128 units: padded peephole weights
-], ids=lambda v: v[0] if isinstance(v, tuple) else None)
-def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
-    """The optional terms of the ONNX operators (cellwise plan): peephole weights and the clipping
-    threshold of the gate arguments, against the oracle with the same terms; setting them is refused
-    where they do not exist, and taking them away restores the plain cell bit for bit."""
+    (("lstm_opts_4layer_sq_h1024_b1", 0, 4, 1, 1024, 1024, 7, 1, 1, False, True), 0.15, True),   # the batch-1 latency shape
+    (("lstm_opts_inside_sq", 0, 2, 1, 512, 512, 11, 300, 1, True, True), 0.5, True),  # inside-product kernel, two chains
+    (("lstm_opts_b300", 0, 1, 1, 64, 512, 6, 300, 1, True, True), 0.5, True),         # flag-vector kernel
+    (("gru_clip_b256_bidir", 1, 1, 2, 64, 128, 5, 256, 1, True, True), 0.4, False),   # flag-vector kernel, both directions
+    (("lstm_opts_sidebyside_l3", 0, 3, 1, 512, 512, 5, 64, 1, True, True), 0.6, True),  # layers side by side
+]
+
+
+@pytest.mark.parametrize("plan", ["cellwise", "wavefront"])
+@pytest.mark.parametrize("spec,clip,peep", OPT_SPECS, ids=lambda v: v[0] if isinstance(v, tuple) else None)
+def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep, plan):
+    """The optional terms of the ONNX operators, under the cellwise plan and inside the persistent kernels:
+    peephole weights and the clipping threshold of the gate arguments, against the oracle with the same terms;
+    setting them is refused where they do not exist, and taking them away restores the plain cell bit for bit."""
     import torch
     harness, rnn, W = gpu
     wl = _small_workload(W, spec)
     c = wl.cfg
+    if plan == "cellwise" and c.B * c.T > 2000:
+        pytest.skip("large batch: the persistent kernels are the point of this shape")
     rng = np.random.default_rng(c.seed + 99)
     ps = [rng.uniform(-4, 4, (3, c.H)).astype(np.float32) for _ in range(c.L * c.D)] if peep else None
-    if ps is not None:
+    if ps is not None and len(ps) > 1:
         ps[-1] = None                          # a missing entry = zeros
-    model = harness.DeviceModel(wl)
+    model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_CELLWISE if plan == "cellwise" else rnn.RNN_PLAN_WAVEFRONT)
     io_plain, io = harness.DeviceIO(wl), harness.DeviceIO(wl)
     harness.forward(model, io_plain)
     torch.cuda.synchronize()
@@ -438,11 +449,18 @@ def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
         assert rnn.rnn_model_set_clip(model.handle, clip) == rnn.RNN_OK
     if ps is not None:
         assert rnn.rnn_model_set_peepholes(model.handle, ps, 0) == rnn.RNN_OK
-    assert rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_EUNSUPPORTED
     harness.forward(model, io)
-    ref = oracle.forward_workload(wl, nthreads=8, peepholes=ps, clip=clip)
-    _check(harness, wl, io, ref)
-    plain = oracle.forward_workload(wl, nthreads=8)
+    torch.cuda.synchronize()
+    assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+    rows = None
+    sub = wl
+    if c.B > 64:                               # large batches: the oracle recomputes sampled sequences
+        rows = np.unique(np.concatenate([np.arange(0, c.B, max(c.B // 20, 1)), [15, 16, 31, 32, c.B - 1]]))
+        sub = wl.take_batch(rows)
+    sub_ps = ps
+    ref = oracle.forward_workload(sub, nthreads=8, peepholes=sub_ps, clip=clip)
+    _check(harness, wl, io, ref, rows=rows)
+    plain = oracle.forward_workload(sub, nthreads=8)
     moved = float(np.max(np.abs(ref[0] - plain[0])))
     assert moved > 3 * TOL[c.dtype]          # the terms were active: a kernel that ignored them would fail above
     if ps is not None:   # the same from device memory
@@ -464,10 +482,6 @@ def test_peepholes_and_clipping(gpu, oracle, spec, clip, peep):
     assert rnn.rnn_model_set_clip(model.handle, float("nan")) == rnn.RNN_EINVAL
     if c.cell == 1:
         assert rnn.rnn_model_set_peepholes(model.handle, [None] * (c.L * c.D), 0) == rnn.RNN_EUNSUPPORTED
-    if rnn.rnn_model_set_plan(model.handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_OK:
-        assert rnn.rnn_model_set_clip(model.handle, 0.5) == rnn.RNN_EUNSUPPORTED
-        if c.cell == 0:
-            assert rnn.rnn_model_set_peepholes(model.handle, [None] * (c.L * c.D), 0) == rnn.RNN_EUNSUPPORTED
     model.close()
 
 
