@@ -278,6 +278,28 @@ int launch_count(const rnn_model* m, const Plan& plan) {
     return count;
 }
 
+// Index of the launch that holds layer l (launches are numbered in stream order).
+int launch_index(const Plan& plan, int l) {
+    if (plan.first_alone) return l == 0 ? 0 : 1 + (l - 1) / plan.LP;
+    return l / plan.LP;
+}
+
+// Only what is live is kept (the paper's memory model, Section 3, Equation 4, charges an operator's output
+// while a successor still needs it): the output of layer l is read by layer l + 1 alone, and a state
+// sequence by its own launch and by the launch after it.
+//
+// Entry of ws.ybuf that holds the output of layer l < L - 1, or -1 when that layer keeps none (its consumer
+// reads its state sequence, or sits in the same launch of the tag-in-data kernel and reads the tagged words).
+int ybuf_slot(const rnn_model* m, const Plan& plan, int l, int T);
+// Layer regions of the state-sequence buffer: two launches' worth, used alternately.
+int state_regions(const rnn_model* m, const Plan& plan) { return std::min(m->L, 2 * plan.LP); }
+int state_region_index(const rnn_model* m, const Plan& plan, int l) {
+    int l0, n;
+    launch_of(m, plan, l, l0, n);
+    if (state_regions(m, plan) == m->L) return l;   // every layer has its own
+    return (launch_index(plan, l) % 2) * plan.LP + (l - l0);
+}
+
 // Gate row of the caller's [G*H, K] matrix that feeds slot s of unit u; -1 = no row (zeros).
 // order: rnn_gate_order of the caller's row blocks.
 int source_row(int cell, bool recurrent, int H, int u, int s, int order) {
@@ -338,8 +360,8 @@ int forward_cellwise(rnn_model* m, const void* x, const int32_t* lengths, const 
                               m->ws.h_st.p, state, st));
     const int N4 = SLOTS * m->H;
     for (int l = 0; l < m->L; ++l) {
-        const void* in = (l == 0) ? x : m->ws.ybuf[l - 1].p;
-        void* out = (l == m->L - 1) ? y : m->ws.ybuf[l].p;
+        const void* in = (l == 0) ? x : m->ws.ybuf[(l - 1) % 2].p;      // two buffers, used alternately
+        void* out = (l == m->L - 1) ? y : m->ws.ybuf[l % 2].p;
         const int K = m->layer_input(l);
         const int ps = prof_begin(m, RNN_KERNEL_PROJECTION, st);
         HIP_TRY(launch_gemm_nt(m->dtype, in, K, m->wih[l].p, K, (float*)m->ws.gx.p, m->D * N4,
@@ -413,8 +435,9 @@ inline size_t blocked_rows(int B) { return ((size_t)B + 3) & ~(size_t)3; }
 // State sequences of the layers from l0 on (flag-vector kernels): every (layer, direction) owns
 // T + 1 slots of blocked_rows(B) * H elements, so a layer can read the finished sequence of the
 // layer below.
-void* state_region(rnn_model* m, int l0, int T, int B) {
-    return (char*)m->ws.hseq.p + (size_t)l0 * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
+void* state_region(rnn_model* m, const Plan& plan, int l, int T, int B) {
+    return (char*)m->ws.hseq.p +
+           (size_t)state_region_index(m, plan, l) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
 }
 
 // One persistent launch: layers [l0, l0 + LP) over all T steps.
@@ -435,7 +458,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
                                          (uint64_t*)m->ws.lseq.p, m->epoch, st));
     } else {
         HIP_TRY(launch_wavefront_init(m->dtype, h0, l0, LP, m->D, T, B, (int)blocked_rows(B), m->H,
-                                      state_region(m, l0, T, B), st));
+                                      state_region(m, plan, l0, T, B), st));
     }
     WavefrontArgs a;
     memset(&a, 0, sizeof(a));
@@ -451,8 +474,8 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
             a.bias[ll * m->D + d] = (const float*)m->bias[l * m->D + d].p;
             a.peep[ll * m->D + d] = m->peep.empty() ? nullptr : (const float*)m->peep[l * m->D + d].p;
         }
-        char* base = (char*)((l == m->L - 1) ? y : m->ws.ybuf[l].p);
-        a.out[ll] = base;
+        const int slot = (l == m->L - 1) ? -1 : ybuf_slot(m, plan, l, T);
+        a.out[ll] = (l == m->L - 1) ? y : (slot >= 0 ? m->ws.ybuf[slot].p : nullptr);
         // a layer whose consumer reads the state sequence instead keeps no separate output
         if (!tagged && (xin || x_from_state) && l != m->L - 1) a.out[ll] = nullptr;
     }
@@ -462,8 +485,8 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
     a.xin = xin;
     a.xin_width2 = (tagged && xin) ? 2 * m->layer_input(l0) / m->H : 0;
     if (x_from_state)  // x_t of layer l0 = state of layer l0 - 1 after step t = slot t + 1 of its sequence
-        a.xin = (const char*)state_region(m, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
-    a.hseq = state_region(m, l0, T, B);
+        a.xin = (const char*)state_region(m, plan, l0 - 1, T, B) + blocked_rows(B) * m->H * m->esize;
+    a.hseq = state_region(m, plan, l0, T, B);
     a.h0 = h0; a.c0 = c0; a.hT = hT; a.cT = cT; a.lengths = lengths;
     a.flagv = (uint64_t*)m->ws.flags.p;
     // the launch must stay inside the buffers the workspace holds (a kernel never checks)
@@ -471,7 +494,7 @@ int launch_recurrent(rnn_model* m, const Plan& plan, int l0, int LP, int T, int 
         if (wavefront_ll_words(m->dtype, LP * m->D, T, B, m->H) * sizeof(uint64_t) > m->ws.lseq.bytes) return RNN_EDEVICE;
     } else {
         const size_t flag_words = (size_t)LP * m->D * T * plan.ncb * plan.nrb;
-        const size_t state_end = (size_t)(l0 + LP) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
+        const size_t state_end = (size_t)(state_region_index(m, plan, l0) + LP) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize;
         if (flag_words * sizeof(uint64_t) > m->ws.flags.bytes || state_end > m->ws.hseq.bytes) return RNN_EDEVICE;
     }
     a.status = (unsigned*)m->status.p;
@@ -516,6 +539,22 @@ bool input_product_inside(const rnn_model* m, const Plan& plan, int l, int T) {
     return wavefront_x_variant_exists(m->dtype, plan.RT, plan.CT, plan.NCH, m->H, m->lds_limit, true);
 }
 
+int ybuf_slot(const rnn_model* m, const Plan& plan, int l, int T) {
+    if (plan.kind != RNN_PLAN_WAVEFRONT) return l % 2;          // cellwise: two buffers, used alternately
+    const bool tagged = plan.CT == 1 && plan.NCH == 1;
+    int l0, n;
+    launch_of(m, plan, l, l0, n);
+    if (tagged) {
+        // only the last layer of a launch writes an output (the layers inside a launch exchange tagged
+        // words); the launch after it reads it: two buffers, used alternately
+        return l == l0 + n - 1 ? launch_index(plan, l) % 2 : -1;
+    }
+    // flag-vector kernels: a layer that computes its input product inside keeps no output of its own unless it
+    // is the last (the layer above it does the same and reads this layer's state sequence, slot t + 1); any
+    // other layer keeps one (a fused layer of the same launch reads it while it is produced)
+    return input_product_inside(m, plan, l, T) ? -1 : l;
+}
+
 // Size the workspace for one forward pass of T steps and B sequences under `plan`: only what that
 // plan touches is allocated (the paper's memory model, Section 3, Equation 4, charges a model with
 // its weights, outputs and temporaries; this is the temporaries part).
@@ -530,17 +569,16 @@ int prepare_workspace_pass(rnn_model* m, const Plan& plan, int T, int B) {
     for (int l = 0; l < m->L && rc == RNN_OK; ++l) {
         const bool inside = wavefront && input_product_inside(m, plan, l, T);
         if (!inside && (!wavefront || first_of_launch(m, plan, l))) any_projection = true;
-        // a layer keeps an output of its own unless its consumer reads its state sequence instead (the
-        // inside-product kernel of large batches; the tag-in-data kernel's consumers read plain outputs)
-        if (l + 1 < m->L && (!inside || tagged)) rc = grow(m, m->ws.ybuf[l], rows * m->D * m->H * m->esize);
+        const int slot = l + 1 < m->L ? ybuf_slot(m, plan, l, T) : -1;
+        if (slot >= 0) rc = grow(m, m->ws.ybuf[slot], rows * m->D * m->H * m->esize);
     }
     if (rc == RNN_OK && any_projection) rc = grow(m, m->ws.gx, rows * m->D * m->H * SLOTS * sizeof(float));
     if (rc == RNN_OK && wavefront && !tagged) {
-        rc = grow(m, m->ws.hseq, (size_t)m->L * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize);
-        // one flag word per (layer, direction, step, chain, row block); a launch of LP layers uses the
-        // first LP * D * T * ncb * nrb words
+        rc = grow(m, m->ws.hseq, (size_t)state_regions(m, plan) * m->D * (T + 1) * blocked_rows(B) * m->H * m->esize);
+        // one flag word per (layer of a launch, direction, step, chain, row block); every launch stamps
+        // them with its own tag, so all launches share the words of one
         if (rc == RNN_OK)
-            rc = grow(m, m->ws.flags, (size_t)m->L * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
+            rc = grow(m, m->ws.flags, (size_t)std::min(m->L, plan.LP) * m->D * T * plan.ncb * plan.nrb * sizeof(uint64_t), true);
         if (rc == RNN_OK && input_product_inside(m, plan, 0, T)) rc = grow(m, m->ws.xblk, (size_t)T * blocked_rows(B) * m->H * m->esize);
     }
     if (rc == RNN_OK && tagged)
@@ -632,7 +670,8 @@ int forward_wavefront(rnn_model* m, const Plan& plan, const void* x, const int32
     for (int l0 = 0, LP = 0; l0 < m->L; l0 += LP) {
         int first;
         launch_of(m, plan, l0, first, LP);
-        const void* in = (l0 == 0) ? x : m->ws.ybuf[l0 - 1].p;
+        const int in_slot = l0 == 0 ? -1 : ybuf_slot(m, plan, l0 - 1, T);
+        const void* in = (l0 == 0) ? x : (in_slot >= 0 ? m->ws.ybuf[in_slot].p : nullptr);
         if (plan.CT == 1 && plan.NCH == 1 && input_product_inside(m, plan, l0, T)) {
             // tag-in-data kernel: the x waves of the launch's first layer read the plain input
             const int rc = launch_recurrent(m, plan, l0, LP, T, B, nullptr, y, lengths, h0, c0, hT, cT, st, in);

@@ -676,6 +676,40 @@ def test_workspace_follows_the_plan(gpu):
     model.close()
 
 
+@pytest.mark.parametrize("kind", ["inside_product", "tagged", "cellwise"])
+def test_workspace_keeps_only_live_layers(gpu, oracle, kind):
+    """A deeper model needs no more workspace than a shallow one: the state sequences of two launches and two
+    inter-layer output buffers are used alternately (only the layer being written and the one being read are
+    live), whatever the number of layers.  Checked on the byte count and, for the deep model, against the oracle
+    (re-used regions hold another layer's data when a launch starts)."""
+    import torch
+    harness, rnn, W = gpu
+    shape = {"inside_product": dict(I=512, H=512, T=9, B=300), "tagged": dict(I=256, H=256, T=12, B=3),
+             "cellwise": dict(I=64, H=128, T=6, B=5)}[kind]
+    plan = rnn.RNN_PLAN_CELLWISE if kind == "cellwise" else rnn.RNN_PLAN_WAVEFRONT
+    deep_layers = 40 if kind == "tagged" else 7        # tagged: 16 layers per launch, so 3 launches
+    shallow_layers = 32 if kind == "tagged" else 2     # two launches already use both halves
+    work = {}
+    for L in (shallow_layers, deep_layers):
+        cfg = W.Config("ws_%s_%d" % (kind, L), W.LSTM, L=L, D=1, dtype=W.BF16, seed=W.BASE_SEED + 60 + L, len_min=2, **shape)
+        wl = W.make_workload(cfg, zero_pad_x=False)
+        model = harness.DeviceModel(wl, plan=plan)
+        weights = rnn.rnn_model_device_bytes(model.handle)
+        assert rnn.rnn_model_reserve(model.handle, cfg.T, cfg.B) == rnn.RNN_OK
+        work[L] = rnn.rnn_model_device_bytes(model.handle) - weights
+        if L == deep_layers:
+            io = harness.DeviceIO(wl)
+            harness.forward(model, io)
+            torch.cuda.synchronize()
+            assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+            rows = np.unique(np.linspace(0, cfg.B - 1, 6).astype(int))
+            _check(harness, wl, io, oracle.forward_workload(wl.take_batch(rows), nthreads=16), rows=rows)
+        model.close()
+    # what still grows with the depth: step clocks (8 bytes per layer and step) and the fp32 state of the cellwise plan
+    slack = (deep_layers - shallow_layers) * (8 * shape["T"] + 3 * shape["B"] * shape["H"] * 4) + 4096
+    assert work[deep_layers] <= work[shallow_layers] + slack, work
+
+
 @pytest.mark.parametrize("name", ["gru_bf16_inside_t2", "lstm_f32_inside_b501", "lstm_bf16_b299", "lstm_bf16_inside_sq",
                                   "lstm_f32_fusedflag_h32", "gru_f32_fusedflag_h64", "gru_f32_bidir",
                                   "lstm_bf16_sidebyside_l4", "gru_bf16_sidebyside_l2"])
