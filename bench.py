@@ -284,7 +284,7 @@ def time_other_widths():
     return out
 
 
-def time_projection_gemm(name: str, reps: int = 10):
+def time_projection_gemm(name: str, reps: int = 30, warm: int = 30):
     """The batched input projection X W_ih^T of one layer of the workload over all time steps, as a launch of its
     own (rnn_input_projection).  No named workload needs it any more (their input products run inside the
     recurrent kernels), so it is measured here on its own: it serves every layer whose input is not H/2, H or 2H
@@ -300,7 +300,7 @@ def time_projection_gemm(name: str, reps: int = 10):
     a = torch.randn(rows, K, device="cuda", dtype=torch.float32).to(tdt)
     gx = torch.empty(rows, N, device="cuda", dtype=torch.float32)
     st = torch.cuda.current_stream()
-    for _ in range(3):
+    for _ in range(warm):      # a few launches are not enough: the first tens of milliseconds run measurably slower
         rnn.rnn_input_projection(model.handle, 0, a, gx, rows, st)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(st)

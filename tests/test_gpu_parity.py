@@ -294,6 +294,36 @@ def test_input_projection(gpu, oracle):
         model.close()
 
 
+def test_input_projection_at_full_size(gpu, oracle):
+    """The projection of one layer of the headline workload over all its time steps (131072 x 1024 times
+    1024 x 4096): the shape the large-tile kernel with the XCD-blocked tile order is made for.  The oracle computes
+    sampled rows, among them the first and last row of a tile, of an XCD band and of the matrix."""
+    import torch
+    harness, rnn, W = gpu
+    base = W.CONFIGS["C5"]
+    rows, I, H = base.T * base.B, base.I, base.H
+    cfg = W.Config("proj_full", base.cell, L=1, D=1, I=I, H=H, T=1, B=1, dtype=base.dtype, seed=W.BASE_SEED + 56)
+    wl = W.make_workload(cfg)
+    model = harness.DeviceModel(wl)
+    g = torch.Generator(device="cpu").manual_seed(W.BASE_SEED + 57)
+    a = torch.randn(rows, I, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    x = a.cuda()
+    gx = torch.full((rows, 1, H, 4), 9.0, device="cuda")
+    assert rnn.rnn_input_projection(model.handle, 0, x, gx, rows, torch.cuda.current_stream()) == 0
+    torch.cuda.synchronize()
+    pick = [0, 1, 31, 32, 255, 256, 2047, 2048, 16383, 16384, 16385, 65535, 65536, 70001, 114687, 114688,
+            rows - 257, rows - 256, rows - 2, rows - 1]
+    got = gx[pick, 0].cpu().numpy().astype(np.float64)                     # [n, H, 4]
+    P = oracle.projection(a[pick].to(torch.float64).numpy(), wl.weight(0, 0, 0)).reshape(len(pick), 4, H)
+    exp = np.transpose(P, (0, 2, 1))
+    err = np.max(np.abs(got - exp))
+    _say("    projection %d x %d x %d: %d sampled rows, error %.3e" % (rows, I, 4 * H, len(pick), err))
+    assert err <= 3e-4     # exact products, fp32 accumulation over 1024 terms of size <= ~0.2
+    # every row was written: no element still holds the fill value
+    assert int((gx == 9.0).sum().item()) == 0
+    model.close()
+
+
 def test_error_codes(gpu):
     import torch
     harness, rnn, W = gpu
