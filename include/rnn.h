@@ -325,6 +325,20 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
                    int dtype, int requested_plan, int T, int B, int compute_units, size_t lds_bytes,
                    int* plan, int* separate_projection);
 
+/*
+ * Measurement aid, no part of the forward pass: the rate at which `compute_units` workgroups (one per compute
+ * unit, one wave per SIMD, 16 independent accumulators per wave) issue dense 32 x 32 x 16 bf16 matrix instructions
+ * and nothing else, for `iterations` rounds of 64 instructions per wave, after one untimed pass of the same length.
+ * The published matrix peak of the chip assumes its highest clock; under a chip-wide matrix load the clock is lower,
+ * and this figure is the ceiling the contraction kernels (Section 2.2: the two products of every cell) can be
+ * compared with.  Results (HOST pointers): shader clocks per instruction on one wave, the shader clock in GHz during
+ * the loop (shader clocks over the 100 MHz constant counter), and the whole launch's rate in TFLOP/s from stream
+ * events.  Allocates 256 bytes of device memory for the call, synchronises `stream`; RNN_EUNSUPPORTED while the
+ * stream is being captured, RNN_EINVAL outside 1..4096 compute units, 1..2^20 iterations or on a NULL pointer.
+ */
+int rnn_probe_matrix_rate(int compute_units, int iterations, double* clocks_per_instruction,
+                          double* shader_ghz, double* tflops, void* stream);
+
 /* Static, NUL-terminated description of an rnn_status value. */
 const char* rnn_status_string(int status);
 

@@ -324,6 +324,21 @@ def test_input_projection_at_full_size(gpu, oracle):
     model.close()
 
 
+def test_matrix_rate_probe(gpu):
+    """The measurement aid reports a plausible rate: a 32 x 32 x 16 bf16 matrix instruction takes 8 passes of 4
+    clocks on its SIMD, and a wave that issues nothing else keeps the pipe full."""
+    import torch
+    harness, rnn, W = gpu
+    rc, clk, ghz, tf = rnn.rnn_probe_matrix_rate(8, 2000, torch.cuda.current_stream())
+    assert rc == rnn.RNN_OK
+    _say("    8 compute units: %.2f clocks per instruction, %.3f GHz, %.1f TFLOP/s" % (clk, ghz, tf))
+    assert 31.5 <= clk <= 36.0
+    assert 0.5 <= ghz <= 3.0
+    assert abs(tf - 8 * 4 * 32768 / clk * ghz * 1e9 / 1e12) <= 0.15 * tf     # events and stamps agree
+    assert rnn.rnn_probe_matrix_rate(0, 10, None)[0] == rnn.RNN_EINVAL
+    assert rnn.rnn_probe_matrix_rate(8, 0, None)[0] == rnn.RNN_EINVAL
+
+
 def test_error_codes(gpu):
     import torch
     harness, rnn, W = gpu
