@@ -30,6 +30,19 @@ around it):
                   edges); it is placed on the processor with the smallest EFT, ties to the lowest
                   index.  Latency = the largest finish time.
 
+  place_resident  the same list scheduling under a residency rule, the form of the paper's memory
+                  constraint (Section 3, Equation 4: what a device holds is bounded) that the
+                  persistent kernels impose: every vertex has a kind (the weights it needs: its layer
+                  and direction), a processor (a group of compute units) holds the weights of ONE kind
+                  for the length of a launch and a kind lives on ONE processor.  Reading used here:
+                  the vertices are taken in the given order in passes (a pass is a launch); in a pass
+                  a vertex is placed when all its predecessors are placed and its kind's processor,
+                  or else a processor that holds nothing yet, exists: on its kind's processor if the
+                  kind has one, otherwise on the empty processor with the smallest EFT (ties to the
+                  lowest index), which then holds that kind; a vertex that cannot be placed waits
+                  for the next pass, which starts, with all processors empty, when the last vertex
+                  of this pass has finished (launches on one stream run one after the other).
+
 Every function is a direct transcription of these definitions with Python lists and loops.
 """
 from __future__ import annotations
@@ -155,3 +168,55 @@ def simulate(n: int, pred: Sequence[Sequence[int]], order: Sequence[int], P: int
         if aft[v] > latency:
             latency = aft[v]
     return proc, aft, latency
+
+
+def place_resident(n: int, pred: Sequence[Sequence[int]], order: Sequence[int], P: int,
+                   exec_time: Sequence[float], comm: Sequence[Sequence[float]], kind: Sequence[int]):
+    """Returns (proc[v], pass_of[v], aft[v], latency, number of passes)."""
+    proc = [-1] * n
+    pass_of = [-1] * n
+    aft = [0.0] * n
+    waiting = list(order)
+    if sorted(waiting) != list(range(n)):
+        raise ValueError("the order is not a permutation of the vertices")
+    start = 0.0
+    r = 0
+    while waiting:
+        avail = [start] * P
+        holds = [None] * P            # kind held by each processor in this pass
+        left = []
+        end = start
+        for v in waiting:
+            if any(pass_of[m] < 0 for m in pred[v]):
+                left.append(v)
+                continue
+            if kind[v] in holds:
+                allowed = [holds.index(kind[v])]
+            else:
+                allowed = [j for j in range(P) if holds[j] is None]
+            if not allowed:
+                left.append(v)
+                continue
+            best_j, best_eft = -1, 0.0
+            for j in allowed:
+                est = avail[j]
+                for i, m in enumerate(pred[v]):
+                    ready = aft[m] + (comm[v][i] if proc[m] != j else 0.0)
+                    if ready > est:
+                        est = ready
+                eft = est + exec_time[v]
+                if best_j < 0 or eft < best_eft:
+                    best_j, best_eft = j, eft
+            proc[v] = best_j
+            pass_of[v] = r
+            aft[v] = best_eft
+            avail[best_j] = best_eft
+            holds[best_j] = kind[v]
+            if best_eft > end:
+                end = best_eft
+        if len(left) == len(waiting):
+            raise ValueError("the order is not topological")
+        waiting = left
+        start = end
+        r += 1
+    return proc, pass_of, aft, max(aft) if n else 0.0, r

@@ -152,3 +152,119 @@ def test_greedy_choice_against_brute_force_on_tiny_graphs():
                 cands.append((t0 + ex[v], j))
             assert (aft[v], proc[v]) == min(cands)
             free[proc[v]] = aft[v]
+
+
+# ---- placement under the residency rule (a processor holds one kind per pass, a kind one processor) ----
+
+def _kinds_of_grid(L, T, D):
+    return [v // T for v in range(L * D * T)]          # vertex (l*D + d)*T + s -> kind l*D + d
+
+
+@pytest.mark.parametrize("L,T,D,LP", [(1, 7, 1, 1), (4, 6, 1, 4), (8, 5, 1, 4), (8, 9, 1, 3), (12, 16, 1, 12),
+                                      (3, 6, 2, 1), (2, 5, 2, 2), (8, 40, 1, 1)])
+def test_resident_placement_closed_forms_on_the_grid(L, T, D, LP):
+    """Unit cells, free communication, P = LP * D processors: a pass holds LP layers and layer l runs in pass l // LP.
+    One direction: on processor l % LP, inside a pass every cell finishes at its depth, and the passes add up to the
+    sum over passes of (layers in the pass + T - 1).  Two directions: a layer needs the layer below at the same
+    TIME, which the backward direction reaches in its last step, so layers follow one another (finish of step s of
+    layer l: l * T + s + 1, latency L * T) whatever the pass holds, and the two directions of a layer sit on two
+    different processors (which of them gets which is a matter of the order among vertices that are ready together)."""
+    n, pred = S.grid_dag(L, T, D)
+    comm = _zeros_like(pred)
+    order = S.topological_order(n, pred, comm, [1.0] * n)
+    proc, pass_of, aft, lat, passes = S.place_resident(n, pred, order, LP * D, [1.0] * n, comm, _kinds_of_grid(L, T, D))
+    assert passes == -(-L // LP)
+    t0 = 0
+    starts = []
+    for r in range(passes):
+        starts.append(t0)
+        t0 += min(LP, L - r * LP) + T - 1
+    assert lat == (t0 if D == 1 else L * T)
+    for l in range(L):
+        for d in range(D):
+            for s in range(T):
+                v = S.vertex_id(L, T, D, l, d, s)
+                assert pass_of[v] == l // LP
+                assert proc[v] == proc[S.vertex_id(L, T, D, l, d, 0)]
+                if D == 1:
+                    assert proc[v] == l % LP
+                    assert aft[v] == starts[l // LP] + (l % LP) + s + 1
+                else:
+                    assert aft[v] == l * T + s + 1
+    for r in range(passes):
+        kinds = sorted({v // T for v in range(n) if pass_of[v] == r})
+        procs = [proc[k * T] for k in kinds]
+        assert sorted(procs) == list(range(len(kinds)))          # one processor each, the lowest ones
+
+
+def test_resident_placement_one_kind_is_serial():
+    """All vertices of one kind: everything runs on processor 0 in one pass, one after the other in the given
+    order, whatever P is."""
+    rng = random.Random(5)
+    n = 25
+    pred = [sorted(rng.sample(range(v), rng.randint(0, min(v, 3)))) for v in range(n)]
+    comm = [[rng.choice([0.0, 1.5]) for _ in p] for p in pred]
+    ex = [rng.choice([0.5, 1.0, 2.0]) for _ in range(n)]
+    order = S.topological_order(n, pred, comm, ex)
+    proc, pass_of, aft, lat, passes = S.place_resident(n, pred, order, 3, ex, comm, [7] * n)
+    assert passes == 1 and set(proc) == {0} and set(pass_of) == {0}
+    t = 0.0
+    for v in order:
+        t += ex[v]
+        assert aft[v] == pytest.approx(t)
+    assert lat == pytest.approx(sum(ex))
+
+
+def test_resident_placement_worked_example():
+    """Four vertices, two kinds, ONE processor: a -> b, a -> c, (b, c) -> d with kinds a, c: 0 and b, d: 1, unit
+    times, order a b c d.  Pass 0 places a (the processor now holds kind 0), skips b (kind 1), places c, skips d
+    (b is not placed): it ends at 2.  Pass 1 places b in [2, 3] and d in [3, 4].  With two processors there is one
+    pass: a on 0 in [0, 1]; b on 1 (empty) from 1 + 0.5 (communication across processors) to 2.5; c on 0 in [1, 2];
+    d on processor 1 (its kind lives there): ready when b is done (2.5) and c has arrived (2 + 0.5) -> [2.5, 3.5]."""
+    pred = [[], [0], [0], [1, 2]]
+    comm = [[], [0.5], [0.5], [0.5, 0.5]]
+    kind = [0, 1, 0, 1]
+    proc, pass_of, aft, lat, passes = S.place_resident(4, pred, [0, 1, 2, 3], 1, [1.0] * 4, comm, kind)
+    assert (passes, pass_of, proc) == (2, [0, 1, 0, 1], [0, 0, 0, 0])
+    assert aft == [1.0, 3.0, 2.0, 4.0] and lat == 4.0
+    proc, pass_of, aft, lat, passes = S.place_resident(4, pred, [0, 1, 2, 3], 2, [1.0] * 4, comm, kind)
+    assert (passes, pass_of, proc) == (1, [0, 0, 0, 0], [0, 1, 0, 1])
+    assert aft == [1.0, 2.5, 2.0, 3.5] and lat == 3.5
+
+
+def test_resident_placement_invariants_on_random_graphs():
+    """Every vertex is placed once; it starts after its predecessors (plus communication across processors) and not
+    before its pass; a processor runs one vertex at a time and one kind per pass; a kind uses one processor per
+    pass; a pass starts when the one before it has ended; a predecessor never sits in a later pass."""
+    rng = random.Random(23)
+    for trial in range(60):
+        n = rng.randint(1, 40)
+        pred = [sorted(rng.sample(range(v), rng.randint(0, min(v, 3)))) for v in range(n)]
+        comm = [[rng.choice([0.0, 0.5, 2.0]) for _ in p] for p in pred]
+        ex = [rng.choice([0.5, 1.0, 2.5]) for _ in range(n)]
+        kind = [rng.randint(0, 5) for _ in range(n)]
+        order = S.topological_order(n, pred, comm, ex)
+        P = rng.randint(1, 4)
+        proc, pass_of, aft, lat, passes = S.place_resident(n, pred, order, P, ex, comm, kind)
+        assert all(0 <= proc[v] < P and 0 <= pass_of[v] < passes for v in range(n))
+        start = [aft[v] - ex[v] for v in range(n)]
+        ends = [max([aft[v] for v in range(n) if pass_of[v] == r]) for r in range(passes)]
+        begins = [0.0] + ends[:-1]
+        for v in range(n):
+            assert start[v] >= begins[pass_of[v]] - 1e-12
+            for i, m in enumerate(pred[v]):
+                assert pass_of[m] <= pass_of[v]
+                assert start[v] >= aft[m] + (comm[v][i] if proc[m] != proc[v] else 0.0) - 1e-12
+        for r in range(passes):
+            assert min(start[v] for v in range(n) if pass_of[v] == r) >= begins[r] - 1e-12
+            for j in range(P):
+                mine = [v for v in range(n) if pass_of[v] == r and proc[v] == j]
+                assert len({kind[v] for v in mine}) <= 1
+                iv = sorted((start[v], aft[v]) for v in mine)
+                assert all(iv[i][1] <= iv[i + 1][0] + 1e-12 for i in range(len(iv) - 1))
+            for k in set(kind):
+                assert len({proc[v] for v in range(n) if pass_of[v] == r and kind[v] == k}) <= 1
+        assert lat == max(aft)
+        # with as many processors as kinds nothing ever waits for a second pass
+        _, _, _, _, one = S.place_resident(n, pred, order, 6, ex, comm, kind)
+        assert one == 1
