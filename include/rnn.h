@@ -325,6 +325,17 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
                    int dtype, int requested_plan, int T, int B, int compute_units, size_t lds_bytes,
                    int* plan, int* separate_projection);
 
+/* Which launch of a forward pass holds which layer (launches numbered in stream order), and which group of
+ * workgroups of that launch runs which (layer, direction), for the plan rnn_plan_query reports for the same
+ * arguments.  The split is the scheduler's: the cell grid (Section 2.2) sorted by the topological sorting of Section
+ * 4.1 and placed by the list scheduling of Section 3 on as many processors as a launch has room for groups, each
+ * processor holding the weights of one (layer, direction) per pass (rnn_schedule_place_resident); a pass is a
+ * launch.  Under the cellwise plan every layer is a launch of its own.  Pure host code; HOST pointers:
+ * layer_launch[num_layers], layer_group[num_layers * num_directions] (may be NULL).  Errors as rnn_plan_query. */
+int rnn_plan_launches(int cell, int num_layers, int input_size, int hidden_size, int num_directions,
+                      int dtype, int requested_plan, int T, int B, int compute_units, size_t lds_bytes,
+                      int* layer_launch, int* layer_group);
+
 /*
  * Measurement aid, no part of the forward pass: the rate at which `compute_units` workgroups (one per compute
  * unit, one wave per SIMD, 16 independent accumulators per wave) issue dense 32 x 32 x 16 bf16 matrix instructions

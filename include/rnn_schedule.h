@@ -57,6 +57,24 @@ int rnn_schedule_simulate(int n, const int* pred_offset, const int* pred_index, 
                           const double* exec_time, const double* comm, int* proc, double* aft,
                           double* latency);
 
+/* The same list scheduling under a residency rule, the form in which the persistent kernels meet the memory
+ * constraint of Section 3 (Equation 4: what a device holds is bounded): every vertex has a kind (the weights it
+ * needs: its layer and direction), a processor (a group of compute units) holds the weights of ONE kind for the
+ * length of a launch, and a kind lives on ONE processor.  Reading implemented: the vertices are taken in `order`
+ * in passes (a pass is a launch).  In a pass a vertex is placed when all its predecessors are placed and its kind's
+ * processor, or else a processor that holds nothing yet, exists: on its kind's processor if the kind has one,
+ * otherwise on the empty processor with the smallest EFT (ties to the lowest index), which then holds that kind.
+ * A vertex that cannot be placed waits for the next pass, which starts, with all processors empty, when the last
+ * vertex of this pass has finished (launches on one stream run one after the other).  Start times follow the rules
+ * of rnn_schedule_simulate.  rnn_forward derives from the result which layers share a launch and which group of
+ * workgroups runs which (layer, direction).
+ *   kind      per vertex, any int
+ *   proc, pass, aft (each may be NULL)  receive processor, pass and finish time of every vertex
+ *   latency   receives the largest finish time; n_passes the number of passes */
+int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_index, const int* order, int P,
+                                const double* exec_time, const double* comm, const int* kind, int* proc,
+                                int* pass, double* aft, double* latency, int* n_passes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,6 +1,7 @@
 // Host side of the library: the C ABI of include/rnn.h, weight repacking, workspace and the
 // choice of execution plan.  All arithmetic of the forward pass runs in the HIP kernels.
 #include "../../include/rnn.h"
+#include "../../include/rnn_schedule.h"
 
 #include <math.h>
 #include <stdlib.h>
@@ -31,6 +32,17 @@ struct Plan {
     // > 0: the batch is larger than one pass of this plan can hold; it runs in passes of `chunk` sequences
     // (sequences are independent) through copies in the workspace, the last pass with a plan of its own
     int chunk = 0;
+    // Which layers share a launch, as the scheduler placed the cell graph (derive_launches): per layer the launch
+    // that holds it, per launch its first layer and its number of layers.  Empty (the cellwise plan): one layer
+    // per launch.
+    std::vector<int> layer_launch, launch_layer0, launch_layers;
+};
+
+// The launches of one (steps, layers per launch, first layer alone) combination, kept with the model.
+struct LaunchTable {
+    int steps = 0, LP = 0;
+    bool first_alone = false;
+    std::vector<int> layer_launch, launch_layer0, launch_layers;
 };
 
 }  // namespace
@@ -115,6 +127,9 @@ struct rnn_model {
     size_t prof_used = 0;
 
     int layer_input(int l) const { return l == 0 ? I : D * H; }
+
+    // launch tables already derived for this model (the scheduler runs once per combination, not per forward pass)
+    mutable std::vector<LaunchTable> launch_tables;
 };
 
 namespace {
@@ -236,8 +251,89 @@ bool choose_wavefront(const rnn_model* m, int T, int B, Plan& plan) {
     return false;
 }
 
+// Which layers share a launch, and which group of workgroups of a launch runs which (layer, direction): taken from
+// the scheduler, not from arithmetic on layer numbers.  The cell graph of the layers that run in the persistent
+// kernels (Section 2.2; all of them, or those above a first layer that runs alone behind its projection) is built
+// (rnn_schedule_grid), sorted (rnn_schedule_order: the topological sorting of Section 4.1) and placed
+// (rnn_schedule_place_resident: the list scheduling of Section 3 with one kind of weights per processor and pass)
+// on P = LP * D processors, one per group of workgroups that a launch of this plan has room for.  A pass of the
+// placement is a launch; the processor of a (layer, direction) in its pass is its group.  Cell times: the products
+// of a cell, 2 * gates * H * (input width + H) flops, relative to a layer above the first; an edge costs a quarter of
+// such a cell across groups (a state vector through the L2).  The grid is uniform along time, so the first 256
+// steps decide.  The kernels number the groups of a launch by ascending (layer, direction) and take the launch's
+// first layer and layer count; processors are identical, so the groups of a pass are renumbered that way, and what
+// the kernels cannot run (a layer split over passes, directions of one layer in different passes, layers of a
+// pass that are not consecutive) is reported as an error instead of being run differently.
+int derive_launches(const rnn_model* m, Plan& plan, int T) {
+    const int steps = T < 256 ? T : 256;
+    for (const LaunchTable& t : m->launch_tables)
+        if (t.steps == steps && t.LP == plan.LP && t.first_alone == plan.first_alone) {
+            plan.layer_launch = t.layer_launch; plan.launch_layer0 = t.launch_layer0; plan.launch_layers = t.launch_layers;
+            return RNN_OK;
+        }
+    LaunchTable tab;
+    tab.steps = steps; tab.LP = plan.LP; tab.first_alone = plan.first_alone;
+    tab.layer_launch.assign(m->L, -1);
+    const int lbase = plan.first_alone ? 1 : 0;         // layers below lbase run in launches of their own
+    for (int l = 0; l < lbase; ++l) {
+        tab.layer_launch[l] = l;
+        tab.launch_layer0.push_back(l);
+        tab.launch_layers.push_back(1);
+    }
+    const int Ls = m->L - lbase, D = m->D;
+    if (Ls > 0) {
+        int n = 0, ne = 0;
+        int rc = rnn_schedule_grid_size(Ls, steps, D, &n, &ne);
+        if (rc != RNN_OK) return rc;
+        std::vector<int> off(n + 1), idx(ne > 0 ? ne : 1), order(n), kind(n), proc(n), pass(n);
+        std::vector<double> exec(n), comm(ne > 0 ? ne : 1, 0.25);
+        rc = rnn_schedule_grid(Ls, steps, D, off.data(), idx.data());
+        if (rc != RNN_OK) return rc;
+        const double unit = (double)(m->layer_input(m->L - 1) + m->H);
+        for (int v = 0; v < n; ++v) {
+            kind[v] = v / steps;                        // vertex (l * D + d) * steps + s
+            exec[v] = (double)(m->layer_input(lbase + kind[v] / D) + m->H) / unit;
+        }
+        rc = rnn_schedule_order(n, off.data(), idx.data(), comm.data(), exec.data(), order.data());
+        if (rc != RNN_OK) return rc;
+        double latency = 0.0;
+        int passes = 0;
+        rc = rnn_schedule_place_resident(n, off.data(), idx.data(), order.data(), plan.LP * D, exec.data(), comm.data(),
+                                         kind.data(), proc.data(), pass.data(), nullptr, &latency, &passes);
+        if (rc != RNN_OK) return rc;
+        std::vector<int> first(passes, -1), last(passes, -1);
+        for (int k = 0; k < Ls * D; ++k) {
+            const int l = lbase + k / D, r = pass[k * steps];
+            for (int s = 1; s < steps; ++s)
+                if (pass[k * steps + s] != r || proc[k * steps + s] != proc[k * steps]) return RNN_EDEVICE;
+            if (k % D && r != pass[(k - 1) * steps]) return RNN_EDEVICE;     // the directions of a layer share a launch
+            if (first[r] < 0) first[r] = l;
+            if (l < first[r] || (last[r] >= 0 && l > last[r] + 1)) return RNN_EDEVICE;   // ascending and consecutive
+            last[r] = l;
+            tab.layer_launch[l] = lbase + r;
+        }
+        for (int r = 0; r < passes; ++r) {
+            if (first[r] < 0 || (r > 0 && first[r] != last[r - 1] + 1)) return RNN_EDEVICE;
+            tab.launch_layer0.push_back(first[r]);
+            tab.launch_layers.push_back(last[r] - first[r] + 1);
+        }
+    }
+    plan.layer_launch = tab.layer_launch; plan.launch_layer0 = tab.launch_layer0; plan.launch_layers = tab.launch_layers;
+    if (m->launch_tables.size() >= 64) m->launch_tables.clear();
+    m->launch_tables.push_back(std::move(tab));
+    return RNN_OK;
+}
+
+int resolve_plan_shape(const rnn_model* m, int T, int B, Plan& plan, bool may_chunk);
+
 // may_chunk: a batch that no persistent launch can hold may be split into passes
 int resolve_plan(const rnn_model* m, int T, int B, Plan& plan, bool may_chunk = true) {
+    const int rc = resolve_plan_shape(m, T, B, plan, may_chunk);
+    if (rc != RNN_OK || plan.kind != RNN_PLAN_WAVEFRONT) return rc;
+    return derive_launches(m, plan, T);
+}
+
+int resolve_plan_shape(const rnn_model* m, int T, int B, Plan& plan, bool may_chunk) {
     if (m->cellwise_only() && m->requested_plan == RNN_PLAN_WAVEFRONT) return RNN_EUNSUPPORTED;
     if (m->requested_plan == RNN_PLAN_CELLWISE || m->cellwise_only()) {
         plan = Plan();
@@ -257,15 +353,12 @@ int resolve_plan(const rnn_model* m, int T, int B, Plan& plan, bool may_chunk = 
     return RNN_OK;
 }
 
-// First layer and number of layers of the launch that holds layer l.
+// First layer and number of layers of the launch that holds layer l (from the scheduler's table).
 void launch_of(const rnn_model* m, const Plan& plan, int l, int& l0, int& n) {
-    if (plan.first_alone) {
-        if (l == 0) { l0 = 0; n = 1; return; }
-        l0 = 1 + ((l - 1) / plan.LP) * plan.LP;
-    } else {
-        l0 = (l / plan.LP) * plan.LP;
-    }
-    n = (l0 + plan.LP <= m->L) ? plan.LP : (m->L - l0);
+    if (plan.layer_launch.empty()) { l0 = l; n = 1; return; }
+    const int r = plan.layer_launch[l];
+    l0 = plan.launch_layer0[r];
+    n = plan.launch_layers[r];
 }
 bool first_of_launch(const rnn_model* m, const Plan& plan, int l) {
     int l0, n;
@@ -273,16 +366,11 @@ bool first_of_launch(const rnn_model* m, const Plan& plan, int l) {
     return l == l0;
 }
 int launch_count(const rnn_model* m, const Plan& plan) {
-    int count = 0;
-    for (int l = 0; l < m->L; ++l) count += first_of_launch(m, plan, l) ? 1 : 0;
-    return count;
+    return plan.layer_launch.empty() ? m->L : (int)plan.launch_layer0.size();
 }
 
 // Index of the launch that holds layer l (launches are numbered in stream order).
-int launch_index(const Plan& plan, int l) {
-    if (plan.first_alone) return l == 0 ? 0 : 1 + (l - 1) / plan.LP;
-    return l / plan.LP;
-}
+int launch_index(const Plan& plan, int l) { return plan.layer_launch.empty() ? l : plan.layer_launch[l]; }
 
 // Only what is live is kept (the paper's memory model, Section 3, Equation 4, charges an operator's output
 // while a successor still needs it): the output of layer l is read by layer l + 1 alone, and a state
@@ -1194,6 +1282,34 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
     if (separate_projection)
         for (int l = 0; l < num_layers; ++l)
             separate_projection[l] = !wavefront ? 1 : input_product_inside(&m, plan, l, T) ? 0 : first_of_launch(&m, plan, l) ? 1 : 0;
+    return RNN_OK;
+}
+
+int rnn_plan_launches(int cell, int num_layers, int input_size, int hidden_size, int num_directions, int dtype,
+                      int requested_plan, int T, int B, int compute_units, size_t lds_bytes, int* layer_launch,
+                      int* layer_group) {
+    if (!layer_launch || T < 1 || B < 1 || compute_units < 1) return RNN_EINVAL;
+    if (requested_plan != RNN_PLAN_AUTO && requested_plan != RNN_PLAN_CELLWISE && requested_plan != RNN_PLAN_WAVEFRONT)
+        return RNN_EINVAL;
+    int rc = check_model_shape(cell, num_layers, input_size, hidden_size, num_directions, dtype);
+    if (rc != RNN_OK) return rc;
+    rnn_model m;   // shape and device figures only: no buffer is touched
+    m.cell = cell; m.L = num_layers; m.I = input_size; m.Hu = hidden_size; m.H = padded_width(dtype, hidden_size);
+    m.D = num_directions; m.dtype = dtype;
+    m.esize = (dtype == RNN_BF16) ? 2 : 4;
+    m.num_cus = compute_units;
+    m.lds_limit = lds_bytes;
+    m.requested_plan = requested_plan;
+    Plan plan;
+    rc = resolve_plan(&m, T, B, plan);
+    if (rc != RNN_OK) return rc;
+    for (int l = 0; l < num_layers; ++l) {
+        int l0, n;
+        launch_of(&m, plan, l, l0, n);
+        layer_launch[l] = launch_index(plan, l);
+        if (layer_group)
+            for (int d = 0; d < num_directions; ++d) layer_group[l * num_directions + d] = (l - l0) * num_directions + d;
+    }
     return RNN_OK;
 }
 

@@ -161,4 +161,77 @@ int rnn_schedule_simulate(int n, const int* pred_offset, const int* pred_index, 
     return RNN_ENOMEM;
 }
 
+int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_index, const int* order, int P,
+                                const double* exec_time, const double* comm, const int* kind, int* proc,
+                                int* pass, double* aft, double* latency, int* n_passes) try {
+    if (!graph_ok(n, pred_offset, pred_index) || !order || P < 1 || !exec_time || !kind || !latency || !n_passes)
+        return RNN_EINVAL;
+    if (pred_offset[n] > 0 && !comm) return RNN_EINVAL;
+    std::vector<int> where(n, -1), round(n, -1), waiting(order, order + n), left;
+    {
+        std::vector<char> seen(n, 0);
+        for (int v : waiting) {
+            if (v < 0 || v >= n || seen[v]) return RNN_EINVAL;
+            seen[v] = 1;
+        }
+    }
+    std::vector<double> finish(n, 0.0), free_at(P);
+    std::vector<int> holds(P);
+    std::vector<char> empty(P);
+    double begin = 0.0;
+    int r = 0;
+    while (!waiting.empty()) {
+        for (int j = 0; j < P; ++j) { free_at[j] = begin; empty[j] = 1; }
+        left.clear();
+        double end = begin;
+        for (int v : waiting) {
+            bool ready = true;
+            for (int e = pred_offset[v]; e < pred_offset[v + 1] && ready; ++e) ready = round[pred_index[e]] >= 0;
+            int home = -1;                         // the processor that holds this kind in this pass
+            for (int j = 0; j < P && home < 0; ++j)
+                if (!empty[j] && holds[j] == kind[v]) home = j;
+            int best = -1;
+            double best_eft = 0.0;
+            for (int j = 0; ready && j < P; ++j) {
+                if (home >= 0 ? j != home : !empty[j]) continue;
+                double est = free_at[j];
+                for (int e = pred_offset[v]; e < pred_offset[v + 1]; ++e) {
+                    const int m = pred_index[e];
+                    const double at = finish[m] + (where[m] != j ? comm[e] : 0.0);
+                    if (at > est) est = at;
+                }
+                const double eft = est + exec_time[v];
+                if (best < 0 || eft < best_eft) { best = j; best_eft = eft; }
+            }
+            if (best < 0) {
+                left.push_back(v);
+                continue;
+            }
+            where[v] = best;
+            round[v] = r;
+            finish[v] = best_eft;
+            free_at[best] = best_eft;
+            holds[best] = kind[v];
+            empty[best] = 0;
+            if (best_eft > end) end = best_eft;
+        }
+        if (left.size() == waiting.size()) return RNN_EINVAL;   // the order is not topological
+        waiting.swap(left);
+        begin = end;
+        ++r;
+    }
+    double worst = 0.0;
+    for (int v = 0; v < n; ++v) {
+        if (finish[v] > worst) worst = finish[v];
+        if (proc) proc[v] = where[v];
+        if (pass) pass[v] = round[v];
+        if (aft) aft[v] = finish[v];
+    }
+    *latency = worst;
+    *n_passes = r;
+    return RNN_OK;
+} catch (const std::bad_alloc&) {
+    return RNN_ENOMEM;
+}
+
 }  // extern "C"

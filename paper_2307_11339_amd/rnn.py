@@ -31,7 +31,7 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
            "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
            "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static",
-           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate")
+           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate", "rnn_plan_launches")
 
 _lib = None
 
@@ -90,6 +90,9 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_device_bytes.argtypes = [vp]
     lib.rnn_model_input_product_placement.restype = ci
     lib.rnn_model_input_product_placement.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci)]
+    lib.rnn_plan_launches.restype = ci
+    lib.rnn_plan_launches.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.c_size_t, ctypes.POINTER(ci),
+                                      ctypes.POINTER(ci)]
     lib.rnn_plan_query.restype = ci
     lib.rnn_plan_query.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, ci, ci, ctypes.c_size_t, ctypes.POINTER(ci),
                                    ctypes.POINTER(ci)]
@@ -252,6 +255,16 @@ def rnn_plan_query(cell: int, num_layers: int, input_size: int, hidden_size: int
     rc = load_library().rnn_plan_query(cell, num_layers, input_size, hidden_size, num_directions, dtype,
                                        requested_plan, T, B, compute_units, lds_bytes, plan, sep)
     return rc, dict(zip(PLAN_FIELDS, list(plan))), list(sep)[:max(num_layers, 0)]
+
+
+def rnn_plan_launches(cell: int, num_layers: int, input_size: int, hidden_size: int, num_directions: int, dtype: int,
+                      requested_plan: int, T: int, B: int, compute_units: int, lds_bytes: int):
+    """Host only (no GPU needed).  Returns (status, launch of every layer, group of every (layer, direction))."""
+    lay = (ctypes.c_int * max(num_layers, 1))()
+    grp = (ctypes.c_int * max(num_layers * num_directions, 1))()
+    rc = load_library().rnn_plan_launches(cell, num_layers, input_size, hidden_size, num_directions, dtype,
+                                          requested_plan, T, B, compute_units, lds_bytes, lay, grp)
+    return rc, list(lay)[:max(num_layers, 0)], list(grp)[:max(num_layers * num_directions, 0)]
 
 
 def rnn_model_set_profiling(model: int, flags: int) -> int:

@@ -7,7 +7,8 @@ import numpy as np
 
 from . import rnn
 
-EXPORTS = ("rnn_schedule_grid_size", "rnn_schedule_grid", "rnn_schedule_order", "rnn_schedule_simulate")
+EXPORTS = ("rnn_schedule_grid_size", "rnn_schedule_grid", "rnn_schedule_order", "rnn_schedule_simulate",
+           "rnn_schedule_place_resident")
 
 _declared = False
 
@@ -25,6 +26,9 @@ def _lib():
         lib.rnn_schedule_order.argtypes = [ci, vp, vp, vp, vp, vp]
         lib.rnn_schedule_simulate.restype = ci
         lib.rnn_schedule_simulate.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+        lib.rnn_schedule_place_resident.restype = ci
+        lib.rnn_schedule_place_resident.argtypes = [ci, vp, vp, vp, ci, vp, vp, vp, vp, vp, vp,
+                                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
         _declared = True
     return lib
 
@@ -72,3 +76,23 @@ def rnn_schedule_simulate(pred_offset, pred_index, order, P: int, exec_time, com
     rc = _lib().rnn_schedule_simulate(n, _p(off), _p(idx) if idx.size else None, _p(od), P, _p(ex),
                                       _p(cm) if cm.size else None, _p(proc), _p(aft), ctypes.byref(lat))
     return rc, proc, aft, lat.value
+
+
+def rnn_schedule_place_resident(pred_offset, pred_index, order, P: int, exec_time, comm, kind):
+    """Returns (status, proc int32 [n], pass int32 [n], aft float64 [n], latency, number of passes)."""
+    off = np.ascontiguousarray(pred_offset, dtype=np.int32)
+    idx = np.ascontiguousarray(pred_index, dtype=np.int32)
+    od = np.ascontiguousarray(order, dtype=np.int32)
+    ex = np.ascontiguousarray(exec_time, dtype=np.float64)
+    cm = np.ascontiguousarray(comm, dtype=np.float64)
+    kd = np.ascontiguousarray(kind, dtype=np.int32)
+    n = off.size - 1
+    proc = np.full(n, -1, dtype=np.int32)
+    rnd = np.full(n, -1, dtype=np.int32)
+    aft = np.zeros(n, dtype=np.float64)
+    lat = ctypes.c_double(0.0)
+    npass = ctypes.c_int(0)
+    rc = _lib().rnn_schedule_place_resident(n, _p(off), _p(idx) if idx.size else None, _p(od), P, _p(ex),
+                                            _p(cm) if cm.size else None, _p(kd), _p(proc), _p(rnd), _p(aft),
+                                            ctypes.byref(lat), ctypes.byref(npass))
+    return rc, proc, rnd, aft, lat.value, npass.value

@@ -193,3 +193,64 @@ def test_errors():
     assert q(cus=0) == rnn.RNN_EINVAL
     assert q(plan=9) == rnn.RNN_EINVAL
     assert q(H=30) == rnn.RNN_EUNSUPPORTED           # fp32 widths are multiples of 4
+
+
+def _launches(c, plan=rnn.RNN_PLAN_AUTO, cus=CUS, lds=LDS, T=None, B=None):
+    return rnn.rnn_plan_launches(c.cell, c.L, c.I, c.H, c.D, c.dtype, plan, T or c.T, B or c.B, cus, lds)
+
+
+def _by_layer_numbers(L, D, LP, first_alone):
+    """The split written out on layer numbers: launches of LP consecutive layers, after a first layer that runs alone
+    when it needs a projection the others do not; groups of a launch in ascending (layer, direction)."""
+    launch, group = [], []
+    for l in range(L):
+        if first_alone:
+            r, l0 = (0, 0) if l == 0 else (1 + (l - 1) // LP, 1 + ((l - 1) // LP) * LP)
+        else:
+            r, l0 = l // LP, (l // LP) * LP
+        launch.append(r)
+        group += [(l - l0) * D + d for d in range(D)]
+    return launch, group
+
+
+def test_launch_split_comes_out_of_the_scheduler():
+    """The launches of a forward pass are the passes of the scheduler's placement of the cell grid (topological
+    sorting, then list scheduling with one (layer, direction) per processor and pass, as many processors as a launch
+    has room for groups).  For the named workloads, the 13 models of the paper's grid and shapes whose first layer
+    runs alone or whose layers do not divide evenly, that placement is the split one would write down on layer
+    numbers."""
+    cases = [(name, W.CONFIGS[name], None) for name in ("C1", "C2", "C3", "C4", "C5")]
+    cases += [(c.name, c, None) for c in W.paper_grid()]
+    sq = W.Config("m", W.LSTM, L=4, D=1, I=1024, H=1024, T=128, B=64, dtype=W.BF16, seed=1)
+    cases += [("side_by_side", sq, False), ("first_alone", sq.scaled(I=64), True),
+              ("first_alone_7", sq.scaled(I=64, L=7), True),
+              ("uneven", W.Config("u", W.LSTM, L=7, D=1, I=256, H=256, T=40, B=8, dtype=W.BF16, seed=1), None),
+              ("one_step", W.Config("t1", W.GRU, L=5, D=1, I=128, H=128, T=1, B=3, dtype=W.BF16, seed=1), None),
+              ("two_directions", W.Config("bi", W.LSTM, L=3, D=2, I=96, H=128, T=33, B=16, dtype=W.BF16, seed=1), None)]
+    seen_multi = seen_alone = 0
+    for name, c, alone in cases:
+        rc, plan, sep = _query(c)
+        assert rc == rnn.RNN_OK, name
+        rc, launch, group = _launches(c)
+        assert rc == rnn.RNN_OK, name
+        if plan["kind"] != rnn.RNN_PLAN_WAVEFRONT:
+            assert launch == list(range(c.L)), name
+            continue
+        LP = plan["layers_per_launch"]
+        if alone is None:                       # the first layer runs alone iff that explains the launch count
+            alone = plan["launches"] == 1 + -(-(c.L - 1) // LP) and plan["launches"] != -(-c.L // LP)
+        want_launch, want_group = _by_layer_numbers(c.L, c.D, LP, alone)
+        assert launch == want_launch, (name, launch, want_launch)
+        assert group == want_group, name
+        assert max(launch) + 1 == plan["launches"], name
+        seen_multi += LP > 1 and max(launch) > 0
+        seen_alone += alone
+    assert seen_multi >= 1 and seen_alone >= 2      # the cases do exercise several launches of several layers
+
+
+def test_launch_split_query_errors():
+    c = W.CONFIGS["C2"]
+    assert rnn.rnn_plan_launches(c.cell, c.L, c.I, c.H, c.D, c.dtype, 99, c.T, c.B, CUS, LDS)[0] == rnn.RNN_EINVAL
+    assert rnn.rnn_plan_launches(c.cell, c.L, c.I, c.H, c.D, c.dtype, rnn.RNN_PLAN_AUTO, 0, c.B, CUS, LDS)[0] == rnn.RNN_EINVAL
+    rc, launch, _ = _launches(c, plan=rnn.RNN_PLAN_CELLWISE)
+    assert rc == rnn.RNN_OK and launch == list(range(c.L))

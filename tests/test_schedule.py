@@ -71,6 +71,46 @@ def test_order_and_simulation_on_random_graphs(sched):
             assert proc.tolist() == wp and aft.tolist() == wa and lat == wl
 
 
+def test_resident_placement_on_random_graphs(sched):
+    """The library's placement under the residency rule equals the reference vertex by vertex."""
+    schedule, rnn = sched
+    rng = random.Random(4111)
+    for trial in range(200):
+        n, pred, comm, ex = _random_case(rng, 60)
+        off, idx = _csr(pred)
+        order = S.topological_order(n, pred, comm, ex)
+        kind = [rng.randint(0, 6) for _ in range(n)]
+        for P in (1, 2, 5):
+            wp, wr, wa, wl, wn = S.place_resident(n, pred, order, P, ex, comm, kind)
+            rc, proc, rnd, aft, lat, npass = schedule.rnn_schedule_place_resident(off, idx, order, P, ex, _flat(comm), kind)
+            assert rc == rnn.RNN_OK
+            assert proc.tolist() == wp and rnd.tolist() == wr and aft.tolist() == wa and lat == wl and npass == wn
+    # errors: an order that is not a permutation, one that is not topological, no processors
+    off, idx = _csr([[], [0], [1]])
+    ex, cm, kind = [1.0] * 3, [0.0, 0.0], [0, 1, 2]
+    assert schedule.rnn_schedule_place_resident(off, idx, [0, 1, 1], 2, ex, cm, kind)[0] == rnn.RNN_EINVAL
+    assert schedule.rnn_schedule_place_resident(off, idx, [0, 1, 2], 0, ex, cm, kind)[0] == rnn.RNN_EINVAL
+    rc, proc, rnd, aft, lat, npass = schedule.rnn_schedule_place_resident(off, idx, [2, 1, 0], 3, ex, cm, kind)
+    wp, wr, wa, wl, wn = S.place_resident(3, [[], [0], [1]], [2, 1, 0], 3, ex, [[], [0.0], [0.0]], kind)
+    assert rc == rnn.RNN_OK and rnd.tolist() == wr and npass == wn     # out-of-order vertices simply wait a pass
+
+
+@pytest.mark.parametrize("L,T,D,LP", [(12, 96, 1, 12), (8, 512, 1, 1), (8, 128, 1, 4), (2, 256, 2, 1), (8, 256, 1, 3)])
+def test_resident_placement_on_the_grids_of_the_workloads(sched, L, T, D, LP):
+    schedule, rnn = sched
+    n, pred = S.grid_dag(L, T, D)
+    off, idx = _csr(pred)
+    comm = [[0.25] * len(p) for p in pred]
+    ex = [1.0] * n
+    order = S.topological_order(n, pred, comm, ex)
+    kind = [v // T for v in range(n)]
+    wp, wr, wa, wl, wn = S.place_resident(n, pred, order, LP * D, ex, comm, kind)
+    rc, proc, rnd, aft, lat, npass = schedule.rnn_schedule_place_resident(off, idx, order, LP * D, ex, _flat(comm), kind)
+    assert rc == rnn.RNN_OK
+    assert proc.tolist() == wp and rnd.tolist() == wr and aft.tolist() == wa and lat == wl and npass == wn
+    assert npass == -(-L // LP)
+
+
 @pytest.mark.parametrize("L,T,D,P", [(12, 96, 1, 12), (8, 512, 1, 8), (2, 256, 2, 4), (4, 128, 1, 2)])
 def test_the_grids_of_the_workloads(sched, L, T, D, P):
     """The shapes this repository runs (the paper's Table 6 model, the five named workloads): order and
