@@ -61,6 +61,25 @@ def matrix_rate_under_load(iterations: int = 20000):
     return out
 
 
+def exchange_floor(steps: int = 4000):
+    """One step of the tagged all-gather the small-batch kernels are built on, without their arithmetic
+    (rnn_probe_exchange_step), in the group shapes of the named small-batch workloads: 512 words are the h vector of
+    1024 bf16 units, 256 words of 512 units."""
+    import torch
+    from paper_2307_11339_amd import rnn
+    out = {}
+    for name, (groups, wgs, words) in (("C1_shape_1x32_workgroups_512_words", (1, 32, 512)),
+                                       ("C2_shape_2x32_workgroups_256_words", (2, 32, 256)),
+                                       ("C3_shape_4x64_workgroups_512_words", (4, 64, 512)),
+                                       ("one_group_64_workgroups_512_words", (1, 64, 512)),
+                                       ("one_group_8_workgroups_512_words", (1, 8, 512))):
+        rc, us, clk = rnn.rnn_probe_exchange_step(groups, wgs, words, steps, torch.cuda.current_stream())
+        if rc != 0:
+            raise RuntimeError("rnn_probe_exchange_step: status %d" % rc)
+        out[name] = {"us_per_step": round(us, 3), "shader_clocks_per_step": round(clk, 1)}
+    return out
+
+
 def host_description():
     model = ""
     try:
@@ -399,6 +418,8 @@ def main() -> int:
                     help="time only the stand-alone input projection of one layer of the workload and exit")
     ap.add_argument("--matrix-rate", action="store_true",
                     help="only measure the dense matrix-instruction rate and shader clock under load")
+    ap.add_argument("--exchange-floor", action="store_true",
+                    help="only measure a step of the small-batch kernels' exchange without their arithmetic")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run a plain device copy of MIB mebibytes five times (reference reading "
@@ -417,6 +438,9 @@ def main() -> int:
 
     if args.projection_gemm:
         print(json.dumps({"projection_gemm": time_projection_gemm(args.workload)}))
+        return 0
+    if args.exchange_floor:
+        print(json.dumps({"exchange_floor": exchange_floor()}))
         return 0
     if args.matrix_rate:
         print(json.dumps({"matrix_rate_under_load": matrix_rate_under_load()}))
@@ -553,6 +577,7 @@ def main() -> int:
     if not args.no_extra:
         line["projection_gemm"] = time_projection_gemm(args.workload)
         line["matrix_rate_under_load"] = matrix_rate_under_load()
+        line["exchange_floor"] = exchange_floor()
         sustained = line["matrix_rate_under_load"]["all_compute_units"]["tflops"]
         if bf16 and sustained > 0:
             # the same achieved rates against what the chip sustains on matrix instructions alone (its clock drops

@@ -350,6 +350,22 @@ int rnn_plan_launches(int cell, int num_layers, int input_size, int hidden_size,
 int rnn_probe_matrix_rate(int compute_units, int iterations, double* clocks_per_instruction,
                           double* shader_ghz, double* tflops, void* stream);
 
+/*
+ * Measurement aid, no part of the forward pass: one step of the exchange the small-batch persistent kernels are
+ * built on, without their arithmetic.  `groups` independent groups (the layers of a launch) of `workgroups`
+ * workgroups each; in every step each workgroup of a group publishes its share of the group's `words` tagged 64-bit
+ * words (device-scope stores), then fetches all of them (device-scope loads, a quarter per wave) until every word
+ * carries the step's tag, and joins its waves at a barrier: what a step of the cell grid (Section 2.2: h_t of every
+ * unit is needed by every unit at t + 1) costs before any product or gate is computed.  Results (HOST pointers):
+ * microseconds per step from stream events, shader clocks per step on workgroup 0; the second of two passes is
+ * timed.  Allocates groups * (steps + 1) * words * 8 bytes for the call and synchronises `stream`.  RNN_EINVAL
+ * unless 1 <= groups <= 64, groups * workgroups <= compute units (all must be resident), words a multiple of 8 and
+ * of workgroups, 8 <= words <= 2048, words / workgroups <= 64, 1 <= steps <= 100000; RNN_EUNSUPPORTED while the
+ * stream is being captured; RNN_EDEVICE if a wait gave up (the kernel's waits are bounded).
+ */
+int rnn_probe_exchange_step(int groups, int workgroups, int words, int steps, double* us_per_step,
+                            double* clocks_per_step, void* stream);
+
 /* Static, NUL-terminated description of an rnn_status value. */
 const char* rnn_status_string(int status);
 

@@ -31,7 +31,7 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
            "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
            "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static",
-           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate", "rnn_plan_launches")
+           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate", "rnn_plan_launches", "rnn_probe_exchange_step")
 
 _lib = None
 
@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_set_peepholes.argtypes = [vp, ctypes.POINTER(vp), ci]
     lib.rnn_model_set_validation.restype = ci
     lib.rnn_model_set_validation.argtypes = [vp, ci]
+    lib.rnn_probe_exchange_step.restype = ci
+    lib.rnn_probe_exchange_step.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ctypes.c_double)] * 2 + [vp]
     lib.rnn_probe_matrix_rate.restype = ci
     lib.rnn_probe_matrix_rate.argtypes = [ci, ci] + [ctypes.POINTER(ctypes.c_double)] * 3 + [vp]
     lib.rnn_model_set_launch_tag.restype = ci
@@ -191,6 +193,14 @@ def rnn_model_set_validation(model: int, on: int) -> int:
 
 def rnn_model_set_launch_tag(model: int, tag: int) -> int:
     return load_library().rnn_model_set_launch_tag(model, tag)
+
+
+def rnn_probe_exchange_step(groups: int, workgroups: int, words: int, steps: int, stream=None):
+    """(status, microseconds per step, shader clocks per step); see include/rnn.h."""
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    out = [ctypes.c_double(0.0) for _ in range(2)]
+    rc = load_library().rnn_probe_exchange_step(groups, workgroups, words, steps, *[ctypes.byref(o) for o in out], s)
+    return (rc,) + tuple(o.value for o in out)
 
 
 def rnn_probe_matrix_rate(compute_units: int, iterations: int, stream=None):

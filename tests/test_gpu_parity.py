@@ -339,6 +339,21 @@ def test_matrix_rate_probe(gpu):
     assert rnn.rnn_probe_matrix_rate(8, 0, None)[0] == rnn.RNN_EINVAL
 
 
+def test_exchange_step_probe(gpu):
+    """The measurement aid runs to the end (no wait gives up) and reports a step between the cost of one device-scope
+    round trip and the step of the kernels built on the same exchange."""
+    import torch
+    harness, rnn, W = gpu
+    for groups, wgs, words in ((1, 8, 64), (1, 64, 512), (4, 64, 512), (3, 5, 40)):
+        rc, us, clk = rnn.rnn_probe_exchange_step(groups, wgs, words, 500, torch.cuda.current_stream())
+        _say("    %d x %d workgroups, %d words: %.3f us per step, %.0f clocks" % (groups, wgs, words, us, clk))
+        assert rc == rnn.RNN_OK
+        assert 0.2 <= us <= 5.0
+    bad = ((0, 8, 64, 10), (1, 8, 60, 10), (1, 7, 64, 10), (1, 1, 128, 10), (1, 8, 64, 0), (65, 1, 8, 10), (1, 8, 4096, 10))
+    for g, w, n, st in bad:
+        assert rnn.rnn_probe_exchange_step(g, w, n, st, None)[0] == rnn.RNN_EINVAL
+
+
 def test_error_codes(gpu):
     import torch
     harness, rnn, W = gpu
