@@ -325,6 +325,36 @@ int rnn_plan_query(int cell, int num_layers, int input_size, int hidden_size, in
                    int dtype, int requested_plan, int T, int B, int compute_units, size_t lds_bytes,
                    int* plan, int* separate_projection);
 
+/*
+ * A stacked RNN whose layers have different hidden sizes (Section 2.2: a layer takes the output sequence of the layer
+ * below as its input; nothing else ties their widths).  Consecutive layers of one hidden size form a run; every run
+ * is an rnn_model of its own, padded to a kernel width, planned by the scheduler and launched on its own, and the
+ * runs follow one another on the stream, each reading the output of the one before it from a buffer the stack owns.
+ *   hidden_sizes[num_layers]   H_l >= 1, each as rnn_model_create accepts it
+ *   weights                    as for rnn_model_create: L*D*4 host pointers in order (l, d, {W_ih, W_hh, b_ih, b_hh}),
+ *                              W_ih[l,d] [G*H_l, I_l] with I_0 = input_size and I_l = D*H_{l-1}, W_hh[l,d] [G*H_l, H_l]
+ * Errors as rnn_model_create (the first failing run decides); nothing is left allocated on failure.
+ */
+typedef struct rnn_stack rnn_stack;
+int rnn_stack_create(rnn_stack** out, int cell, int num_layers, int input_size, const int* hidden_sizes,
+                     int num_directions, int dtype, const void* const* weights, int weights_on_device);
+/* Free the stack, its models and buffers.  NULL is accepted; streams that run it must have been synchronised. */
+void rnn_stack_destroy(rnn_stack* stack);
+/* Number of runs, and one run: its first layer, number of layers, hidden size and model (any result pointer may be
+ * NULL).  The model stays owned by the stack; the per-model settings (rnn_model_set_plan, _set_clip, ...) apply to it. */
+int rnn_stack_runs(const rnn_stack* stack);
+int rnn_stack_run(const rnn_stack* stack, int run, int* first_layer, int* num_layers, int* hidden_size,
+                  rnn_model** model);
+/* Device bytes of all runs plus the buffers between them. */
+size_t rnn_stack_device_bytes(const rnn_stack* stack);
+/* rnn_forward through all runs.  x [T, B, I] and y [T, B, D*H_last] as there (DEVICE pointers, dtype).  h0, c0, hT,
+ * cT: NULL, or HOST arrays of one DEVICE pointer per run (entries may be NULL), each [layers of the run * D, B, H of
+ * the run] fp32.  The buffers between runs grow on demand (then the call synchronises the device; RNN_EUNSUPPORTED
+ * instead while `stream` is being captured).  One forward in flight per stack. */
+int rnn_stack_forward(rnn_stack* stack, const void* x, const int32_t* lengths, const float* const* h0,
+                      const float* const* c0, void* y, float* const* hT, float* const* cT, int T, int B,
+                      void* stream);
+
 /* Which launch of a forward pass holds which layer (launches numbered in stream order), and which group of
  * workgroups of that launch runs which (layer, direction), for the plan rnn_plan_query reports for the same
  * arguments.  The split is the scheduler's: the cell grid (Section 2.2) sorted by the topological sorting of Section

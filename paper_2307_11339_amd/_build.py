@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librnn_mi355x.so")
 SOURCES = ["wavefront_ll.hip", "wavefront_ll_b.hip", "wavefront_ll_c.hip", "wavefront_ll_d.hip", "wavefront_ll_e.hip",
            "wavefront_ll_f.hip", "wavefront_x.hip", "wavefront_x_b.hip", "wavefront.hip", "wavefront_b.hip",
-           "rnn_api.hip", "gemm.hip", "cellwise.hip", "schedule.hip", "probe.hip"]   # the slowest first
+           "rnn_api.hip", "gemm.hip", "cellwise.hip", "schedule.hip", "probe.hip", "rnn_stack.hip"]   # the slowest first
 HEADERS = ["common.h", "kernels.h", "wf_traits.h", "wavefront_ll.hip", "wavefront_x.hip", "wavefront.hip",
            os.path.join("..", "..", "include", "rnn.h"),
            os.path.join("..", "..", "include", "rnn_schedule.h")]

@@ -31,7 +31,9 @@ EXPORTS = ("rnn_model_create", "rnn_model_destroy", "rnn_model_set_plan", "rnn_m
            "rnn_model_read_step_ticks", "rnn_model_input_product_placement", "rnn_model_create_ordered",
            "rnn_model_set_gru_reset_before", "rnn_plan_query", "rnn_model_set_spin_limit",
            "rnn_model_set_clip", "rnn_model_set_peepholes", "rnn_model_set_batch_first", "rnn_forward_static",
-           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate", "rnn_plan_launches", "rnn_probe_exchange_step")
+           "rnn_model_set_validation", "rnn_model_set_launch_tag", "rnn_probe_matrix_rate", "rnn_plan_launches", "rnn_probe_exchange_step",
+           "rnn_stack_create", "rnn_stack_destroy", "rnn_stack_runs", "rnn_stack_run", "rnn_stack_device_bytes",
+           "rnn_stack_forward")
 
 _lib = None
 
@@ -78,6 +80,19 @@ def load_library() -> ctypes.CDLL:
     lib.rnn_model_set_peepholes.argtypes = [vp, ctypes.POINTER(vp), ci]
     lib.rnn_model_set_validation.restype = ci
     lib.rnn_model_set_validation.argtypes = [vp, ci]
+    lib.rnn_stack_create.restype = ci
+    lib.rnn_stack_create.argtypes = [ctypes.POINTER(vp), ci, ci, ci, ctypes.POINTER(ci), ci, ci, ctypes.POINTER(vp), ci]
+    lib.rnn_stack_destroy.restype = None
+    lib.rnn_stack_destroy.argtypes = [vp]
+    lib.rnn_stack_runs.restype = ci
+    lib.rnn_stack_runs.argtypes = [vp]
+    lib.rnn_stack_run.restype = ci
+    lib.rnn_stack_run.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(vp)]
+    lib.rnn_stack_device_bytes.restype = ctypes.c_size_t
+    lib.rnn_stack_device_bytes.argtypes = [vp]
+    lib.rnn_stack_forward.restype = ci
+    lib.rnn_stack_forward.argtypes = [vp, vp, vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.POINTER(vp),
+                                      ctypes.POINTER(vp), ci, ci, vp]
     lib.rnn_probe_exchange_step.restype = ci
     lib.rnn_probe_exchange_step.argtypes = [ci, ci, ci, ci] + [ctypes.POINTER(ctypes.c_double)] * 2 + [vp]
     lib.rnn_probe_matrix_rate.restype = ci
@@ -193,6 +208,55 @@ def rnn_model_set_validation(model: int, on: int) -> int:
 
 def rnn_model_set_launch_tag(model: int, tag: int) -> int:
     return load_library().rnn_model_set_launch_tag(model, tag)
+
+
+def rnn_stack_create(cell: int, input_size: int, hidden_sizes: Sequence[int], num_directions: int, dtype: int,
+                     weights: Sequence, weights_on_device: int) -> int:
+    """weights: L*D*4 tensors/arrays/None in order (l, d, {W_ih, W_hh, b_ih, b_hh}).  Returns the handle."""
+    L = len(hidden_sizes)
+    n = L * num_directions * 4
+    assert len(weights) == n
+    arr = (ctypes.c_void_p * n)(*[_ptr(w) for w in weights])
+    hs = (ctypes.c_int * L)(*[int(h) for h in hidden_sizes])
+    out = ctypes.c_void_p()
+    rc = load_library().rnn_stack_create(ctypes.byref(out), cell, L, input_size, hs, num_directions, dtype, arr,
+                                         weights_on_device)
+    if rc != RNN_OK:
+        raise RnnError(rc, "rnn_stack_create")
+    return out.value
+
+
+def rnn_stack_destroy(stack: Optional[int]) -> None:
+    load_library().rnn_stack_destroy(stack)
+
+
+def rnn_stack_runs(stack: int) -> int:
+    return load_library().rnn_stack_runs(stack)
+
+
+def rnn_stack_run(stack: int, run: int):
+    """Returns (status, first layer, layers, hidden size, model handle)."""
+    a, b, c = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    m = ctypes.c_void_p()
+    rc = load_library().rnn_stack_run(stack, run, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(m))
+    return rc, a.value, b.value, c.value, m.value
+
+
+def rnn_stack_device_bytes(stack: int) -> int:
+    return load_library().rnn_stack_device_bytes(stack)
+
+
+def _ptr_array(items):
+    if items is None:
+        return None
+    return (ctypes.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def rnn_stack_forward(stack: int, x, lengths, h0, c0, y, hT, cT, T: int, B: int, stream=None) -> int:
+    """h0, c0, hT, cT: None or one tensor (or None) per run; see include/rnn.h."""
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+    return load_library().rnn_stack_forward(stack, _ptr(x), _ptr(lengths), _ptr_array(h0), _ptr_array(c0), _ptr(y),
+                                            _ptr_array(hT), _ptr_array(cT), T, B, s)
 
 
 def rnn_probe_exchange_step(groups: int, workgroups: int, words: int, steps: int, stream=None):

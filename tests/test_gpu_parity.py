@@ -324,6 +324,85 @@ def test_input_projection_at_full_size(gpu, oracle):
     model.close()
 
 
+STACKS = [
+    # name, cell, D, I, hidden sizes per layer, T, B, dtype
+    ("lstm_bf16_128_128_256_64", 0, 1, 64, [128, 128, 256, 64], 9, 5, 1),       # 64 runs padded to 128 units
+    ("gru_f32_bidir_32_64_64", 1, 2, 12, [32, 64, 64], 8, 3, 0),
+    ("lstm_bf16_narrowing_512_256_128_b40", 0, 1, 256, [512, 256, 256, 128], 12, 40, 1),
+    ("lstm_f32_one_run", 0, 1, 20, [64, 64], 6, 4, 0),                         # one run: the same as a plain model
+]
+
+
+@pytest.mark.parametrize("spec", STACKS, ids=[s[0] for s in STACKS])
+def test_layers_of_different_hidden_sizes(gpu, oracle, spec):
+    """A stack whose layers differ in width runs as a chain of models, one per run of equal width, each planned on its
+    own.  The oracle runs the same chain: every run on the (fp64) output of the one below."""
+    import torch
+    harness, rnn, W = gpu
+    name, cell, D, I, hs, T, B, dtype = spec
+    # runs of equal width, each a workload of its own (its input as wide as the output below it)
+    runs, l = [], 0
+    while l < len(hs):
+        n = 1
+        while l + n < len(hs) and hs[l + n] == hs[l]:
+            n += 1
+        runs.append((l, n, hs[l]))
+        l += n
+    wls = []
+    for r, (l0, n, H) in enumerate(runs):
+        i_r = I if r == 0 else D * runs[r - 1][2]
+        cfg = W.Config("%s_run%d" % (name, r), cell, L=n, D=D, I=i_r, H=H, T=T, B=B, dtype=dtype,
+                       seed=W.BASE_SEED + 700 + 10 * STACKS.index(spec) + r, len_min=max(1, T // 2), h0_std=0.5)
+        wls.append(W.make_workload(cfg))
+    lengths = wls[0].lengths
+    weights = []
+    for wl in wls:
+        for w in wl.weights:
+            weights.append(W.f32_to_bf16_bits(w).reshape(w.shape) if dtype == W.BF16 else np.ascontiguousarray(w, dtype=np.float32))
+    stack = rnn.rnn_stack_create(cell, I, hs, D, dtype, weights, 0)
+    try:
+        assert rnn.rnn_stack_runs(stack) == len(runs)
+        for r, (l0, n, H) in enumerate(runs):
+            rc, a, b, c, handle = rnn.rnn_stack_run(stack, r)
+            assert (rc, a, b, c) == (rnn.RNN_OK, l0, n, H) and handle
+            assert rnn.rnn_model_set_plan(handle, rnn.RNN_PLAN_WAVEFRONT) == rnn.RNN_OK
+        assert rnn.rnn_stack_run(stack, len(runs))[0] == rnn.RNN_EINVAL
+        tdt = torch.bfloat16 if dtype == W.BF16 else torch.float32
+        x = harness.to_device_storage(wls[0].x, dtype)
+        dl = torch.from_numpy(lengths).to("cuda")
+        h0 = [torch.from_numpy(wl.h0).to("cuda") for wl in wls]
+        y = torch.full((T, B, D * hs[-1]), 7.0, dtype=tdt, device="cuda")
+        hT = [torch.full((n * D, B, H), 7.0, device="cuda") for (_, n, H) in runs]
+        cT = [torch.full((n * D, B, H), 7.0, device="cuda") for (_, n, H) in runs]
+        for call in range(2):          # the second call finds the buffers between the runs in place
+            assert rnn.rnn_stack_forward(stack, x, dl, h0, None, y, hT, cT, T, B, torch.cuda.current_stream()) == rnn.RNN_OK
+        torch.cuda.synchronize()
+        assert rnn.rnn_stack_device_bytes(stack) > 0
+        # the oracle, run by run
+        inp = wls[0].x
+        tol = TOL[dtype]
+        for r, wl in enumerate(wls):
+            c = wl.cfg
+            ry, rh, rc_ = oracle.forward(c.cell, c.L, c.D, c.I, c.H, wl.weights, inp, lengths, wl.h0, None, nthreads=4)
+            got_h = hT[r].cpu().numpy().astype(np.float64)
+            err_h = float(np.max(np.abs(got_h - rh)))
+            err_c = float(np.max(np.abs(cT[r].cpu().numpy().astype(np.float64) - rc_))) if cell == 0 else 0.0
+            _say("    run %d (%d layers of %d units): hT error %.3e cT error %.3e" % (r, c.L, c.H, err_h, err_c))
+            assert err_h <= tol and err_c <= tol
+            inp = ry
+        got_y = y.float().cpu().numpy().astype(np.float64)
+        err_y = float(np.max(np.abs(got_y - inp)))
+        _say("    y error %.3e (tolerance %.0e)" % (err_y, tol))
+        assert err_y <= tol
+        for j, n in enumerate(lengths):
+            assert not np.any(got_y[int(n):, j]), "padded positions must be zero"
+        for handle in [rnn.rnn_stack_run(stack, r)[4] for r in range(len(runs))]:
+            assert rnn.rnn_model_check(handle) == rnn.RNN_OK
+    finally:
+        torch.cuda.synchronize()
+        rnn.rnn_stack_destroy(stack)
+
+
 def test_matrix_rate_probe(gpu):
     """The measurement aid reports a plausible rate: a 32 x 32 x 16 bf16 matrix instruction takes 8 passes of 4
     clocks on its SIMD, and a wave that issues nothing else keeps the pipe full."""
