@@ -167,7 +167,7 @@ int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_i
     if (!graph_ok(n, pred_offset, pred_index) || !order || P < 1 || !exec_time || !kind || !latency || !n_passes)
         return RNN_EINVAL;
     if (pred_offset[n] > 0 && !comm) return RNN_EINVAL;
-    std::vector<int> where(n, -1), round(n, -1), waiting(order, order + n), left;
+    std::vector<int> where(n, -1), placed_in(n, -1), waiting(order, order + n), left;
     {
         std::vector<char> seen(n, 0);
         for (int v : waiting) {
@@ -186,7 +186,7 @@ int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_i
         double end = begin;
         for (int v : waiting) {
             bool ready = true;
-            for (int e = pred_offset[v]; e < pred_offset[v + 1] && ready; ++e) ready = round[pred_index[e]] >= 0;
+            for (int e = pred_offset[v]; e < pred_offset[v + 1] && ready; ++e) ready = placed_in[pred_index[e]] >= 0;
             int home = -1;                         // the processor that holds this kind in this pass
             for (int j = 0; j < P && home < 0; ++j)
                 if (!empty[j] && holds[j] == kind[v]) home = j;
@@ -208,7 +208,7 @@ int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_i
                 continue;
             }
             where[v] = best;
-            round[v] = r;
+            placed_in[v] = r;
             finish[v] = best_eft;
             free_at[best] = best_eft;
             holds[best] = kind[v];
@@ -224,7 +224,7 @@ int rnn_schedule_place_resident(int n, const int* pred_offset, const int* pred_i
     for (int v = 0; v < n; ++v) {
         if (finish[v] > worst) worst = finish[v];
         if (proc) proc[v] = where[v];
-        if (pass) pass[v] = round[v];
+        if (pass) pass[v] = placed_in[v];
         if (aft) aft[v] = finish[v];
     }
     *latency = worst;
