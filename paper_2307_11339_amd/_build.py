@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -53,7 +54,106 @@ def _check_no_spill(src: str, remarks: str) -> None:
                            % (src, kernel, piece))
 
 
+# Sources whose kernels issue matrix instructions by hand (inline asm with the A operand and the accumulator in the
+# accumulation registers): the compiler neither sees the instruction nor inserts the waits it inserts for its own.
+HAND_ISSUED = ("wavefront_x.hip", "wavefront_x_b.hip")
+HAND_MIN_APART = 5        # a hand-issued matrix instruction and the next one on the same accumulator: four others between
+                          # (a 4-pass instruction has delivered its result by then; the tiles rotate over >= 4 accumulators)
+HAND_MIN_BEFORE_READ = 16  # wait states between a hand-issued matrix instruction and any other reader of its result
+HAND_MIN_AFTER_WRITE = 2   # wait states between v_accvgpr_write and a hand-issued matrix instruction that reads it
+
+_AGPR = re.compile(r"\ba\[(\d+):(\d+)\]|\ba(\d+)\b")
+
+
+def _agprs(operand: str):
+    out = []
+    for m in _AGPR.finditer(operand):
+        if m.group(3) is not None:
+            out.append(int(m.group(3)))
+        else:
+            out += list(range(int(m.group(1)), int(m.group(2)) + 1))
+    return out
+
+
+def _check_hand_issued(src: str, asm: str) -> int:
+    """Walks the generated code of every kernel in program order (branches ignored: a guard, not a proof) and
+    raises when a hand-issued matrix instruction (between #ASMSTART and #ASMEND) follows another one on the same
+    accumulator by fewer than HAND_MIN_APART instructions, when anything but a matrix instruction reads an
+    accumulation register fewer than HAND_MIN_BEFORE_READ wait states after a hand-issued instruction wrote it,
+    or when such an instruction reads a register fewer than HAND_MIN_AFTER_WRITE wait states after
+    v_accvgpr_write set it.  Returns the number of hand-issued instructions seen; none at all is an error too."""
+    seen = 0
+    in_asm = False
+    kernel = None
+    count = ws = 0
+    hand_at = {}      # register -> (instruction count, wait states) of the last hand-issued writer
+    set_at = {}       # register -> wait states at the last v_accvgpr_write
+    for raw in asm.splitlines():
+        t = raw.strip()
+        if t.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if t.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        if not t or t[0] in ";." or t.startswith("//"):
+            continue
+        if t.endswith(":") or (":" in t.split()[0] and not t.startswith("s_") and not t.startswith("v_")):
+            if not t.startswith(".L"):                    # a function label: a new kernel
+                kernel, count, ws, hand_at, set_at = t.split(":")[0], 0, 0, {}, {}
+            continue
+        t = t.split(";")[0].strip()
+        parts = t.split(None, 1)
+        op, args = parts[0], [a.strip() for a in (parts[1].split(",") if len(parts) > 1 else [])]
+        count += 1
+        if op == "s_nop":
+            ws += int(args[0], 0) + 1
+            continue
+        ws += 1
+        if op.startswith("v_mfma"):
+            dst = _agprs(args[0])
+            if in_asm:
+                seen += 1
+                for r in dst:
+                    if r in hand_at and count - hand_at[r][0] < HAND_MIN_APART:
+                        raise RuntimeError("%s: %s: hand-issued matrix instructions on a%d only %d instructions apart"
+                                           % (src, kernel, r, count - hand_at[r][0]))
+                for a in args[1:]:
+                    for r in _agprs(a):
+                        if r in set_at and ws - set_at[r] < HAND_MIN_AFTER_WRITE + 1:
+                            raise RuntimeError("%s: %s: a%d read by a hand-issued matrix instruction %d wait states "
+                                               "after v_accvgpr_write" % (src, kernel, r, ws - set_at[r] - 1))
+                for r in dst:
+                    hand_at[r] = (count, ws)
+            else:
+                for r in dst:
+                    hand_at.pop(r, None)                  # the compiler's own instruction: its waits are the compiler's
+            continue
+        writes_first = op.startswith(("global_load", "buffer_load", "ds_read", "flat_load", "scratch_load",
+                                      "v_accvgpr_write", "v_accvgpr_mov"))
+        for i, a in enumerate(args):
+            for r in _agprs(a):
+                if i == 0 and writes_first:
+                    hand_at.pop(r, None)
+                    if op.startswith("v_accvgpr_write"):
+                        set_at[r] = ws
+                elif r in hand_at and ws - hand_at[r][1] < HAND_MIN_BEFORE_READ + 1:
+                    raise RuntimeError("%s: %s: %s reads a%d %d wait states after a hand-issued matrix instruction"
+                                       % (src, kernel, op, r, ws - hand_at[r][1] - 1))
+    if seen == 0:
+        raise RuntimeError("%s: no hand-issued matrix instruction found in the generated code: the check checks nothing" % src)
+    return seen
+
+
 def _compile(src: str, obj: str) -> None:
+    if src in HAND_ISSUED:
+        asm = obj[:-2] + ".s"
+        r = subprocess.run([_hipcc()] + FLAGS + ["--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc -S failed for %s:\n%s" % (src, r.stdout))
+        _check_hand_issued(src, open(asm).read())
+        os.remove(asm)
     extra = ["-Rpass-analysis=kernel-resource-usage"] if src in NO_SPILL else []
     cmd = [_hipcc()] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
