@@ -59,6 +59,15 @@ def test_host_only_calls(lib):
     assert rnn.rnn_model_check(None) == rnn.RNN_EINVAL
     assert rnn.rnn_model_set_spin_limit(None, 5) == rnn.RNN_EINVAL
     rnn.rnn_model_destroy(None)
+    # the stack of layers of different widths and the probes refuse bad arguments before touching a device
+    assert lib.rnn_stack_create(None, 0, 1, 8, None, 1, 0, None, 0) == rnn.RNN_EINVAL
+    assert lib.rnn_stack_create(ctypes.byref(out), 0, 1, 8, None, 1, 0, None, 0) == rnn.RNN_EINVAL
+    assert rnn.rnn_stack_runs(None) == 0 and rnn.rnn_stack_device_bytes(None) == 0
+    assert rnn.rnn_stack_run(None, 0)[0] == rnn.RNN_EINVAL
+    assert rnn.rnn_stack_forward(None, None, None, None, None, None, None, None, 1, 1, None) == rnn.RNN_EINVAL
+    rnn.rnn_stack_destroy(None)
+    assert rnn.rnn_probe_matrix_rate(0, 10, None)[0] == rnn.RNN_EINVAL
+    assert rnn.rnn_probe_exchange_step(1, 8, 60, 10, None)[0] == rnn.RNN_EINVAL
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -403,6 +403,40 @@ def test_layers_of_different_hidden_sizes(gpu, oracle, spec):
         rnn.rnn_stack_destroy(stack)
 
 
+def test_forward_launches_what_the_scheduler_placed(gpu):
+    """The number of persistent launches a forward pass really makes (counted by the kernel events) is the number of
+    passes in the scheduler's placement that rnn_plan_launches reports for the same shape on this device."""
+    import torch
+    harness, rnn, W = gpu
+    prop = torch.cuda.get_device_properties(0)
+    by_name = {s[0]: s for s in SMALL}
+    cases = [W.CONFIGS["C2"], W.CONFIGS["C4"], W.paper_grid()[0], W.paper_grid()[3],
+             W.CONFIGS["C5"].scaled(T=6, B=40), W.CONFIGS["C5"].scaled(T=5, B=1),
+             _small_workload(W, by_name["lstm_bf16_inside_sq"]).cfg]
+    for cfg in cases:
+        wl = W.make_workload(cfg)
+        model = harness.DeviceModel(wl, plan=rnn.RNN_PLAN_WAVEFRONT)
+        io = harness.DeviceIO(wl)
+        rc, launch, group = rnn.rnn_plan_launches(cfg.cell, cfg.L, cfg.I, cfg.H, cfg.D, cfg.dtype, rnn.RNN_PLAN_WAVEFRONT,
+                                                  cfg.T, cfg.B, prop.multi_processor_count, prop.shared_memory_per_block)
+        assert rc == rnn.RNN_OK
+        rcq, plan, _ = rnn.rnn_plan_query(cfg.cell, cfg.L, cfg.I, cfg.H, cfg.D, cfg.dtype, rnn.RNN_PLAN_WAVEFRONT,
+                                          cfg.T, cfg.B, prop.multi_processor_count, prop.shared_memory_per_block)
+        assert rcq == rnn.RNN_OK
+        harness.forward(model, io)                      # sizes the workspace
+        assert rnn.rnn_model_set_profiling(model.handle, rnn.RNN_PROFILE_KERNELS) == rnn.RNN_OK
+        harness.forward(model, io)
+        torch.cuda.synchronize()
+        rc, ms, n = rnn.rnn_model_profile_read(model.handle, rnn.RNN_KERNEL_RECURRENT)
+        assert rc == rnn.RNN_OK
+        passes = max(launch) + 1
+        _say("    %s: layers -> launches %r, %d recurrent launches counted" % (cfg.name, launch, n))
+        assert n == plan["launches"]                    # includes the passes over blocks of sequences, if any
+        assert plan["launches"] % passes == 0 and sorted(set(launch)) == list(range(passes))
+        assert rnn.rnn_model_check(model.handle) == rnn.RNN_OK
+        model.close()
+
+
 def test_matrix_rate_probe(gpu):
     """The measurement aid reports a plausible rate: a 32 x 32 x 16 bf16 matrix instruction takes 8 passes of 4
     clocks on its SIMD, and a wave that issues nothing else keeps the pipe full."""
